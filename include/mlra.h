@@ -1,0 +1,134 @@
+/*
+ * libmlra -- decode-step attention of Multi-Head Low-Rank Attention (MLRA) for AMD MI355X (gfx950).
+ *
+ * C ABI.  Every buffer is a DEVICE pointer owned by the caller unless a comment says "host".
+ * The library enqueues kernels on the given HIP stream (hipStream_t passed as void*, NULL = the
+ * default stream) and returns without synchronising.  It allocates nothing; scratch memory is a
+ * caller-provided workspace.  No call throws; each returns
+ * an mlra_status.  Errors that the host can see (null pointer, unsupported shape or dtype, a
+ * workspace that is too small, a failed launch) return a negative status and enqueue nothing.
+ * Device-side preconditions are the caller's: page ids in [0, num_pages), seq_lens[b] <=
+ * max_pages_per_seq * page_size, positions[b] inside the pages mapped for sequence b.
+ *
+ * Notation follows the paper: n context length, h query heads, d_h head dim, d_r = d_h^R the
+ * partial-RoPE dim, d_c the KV latent dim cut into n_blocks channel blocks of d_cb = d_c/n_blocks
+ * (Section 2.1 "Block Multiplications"), tau = 1/sqrt(d_h + d_r) the softmax scale.
+ * MLRA-4 is n_blocks = 4; one device's share of 4-way tensor parallelism is n_blocks = 1 with that
+ * block's pool and weights (Section 3.1: the branches are independent up to a final sum).
+ *
+ * Layouts (row-major, last index fastest):
+ *   latent pool  [num_pages][n_blocks][page_size][d_cb]   C^KV, channel block b of a token in plane b
+ *   rope pool    [num_pages][page_size][d_r]              K^RoPE, already rotated, shared by all heads
+ *   page_table   [batch][max_pages_per_seq] int32         logical page -> physical page
+ *   seq_lens     [batch] int32                            valid tokens, including the newest one
+ *   w_uk, w_uv   [n_blocks][d_cb][h*d_h]                  the paper's W^UK, W^UV in R^{d_c x (h d_h)},
+ *                                                         i.e. row block b, head i in columns [i d_h,(i+1) d_h)
+ */
+#ifndef MLRA_H_
+#define MLRA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#if defined(__GNUC__)
+#define MLRA_API __attribute__((visibility("default")))
+#else
+#define MLRA_API
+#endif
+
+typedef enum {
+  MLRA_OK = 0,
+  MLRA_ERR_NULL = -1,      /* a required pointer is NULL                         */
+  MLRA_ERR_SHAPE = -2,     /* a dimension is non-positive or not supported        */
+  MLRA_ERR_DTYPE = -3,     /* unknown or unsupported element type                 */
+  MLRA_ERR_WORKSPACE = -4, /* workspace missing or smaller than required          */
+  MLRA_ERR_LAUNCH = -5     /* the HIP runtime refused a launch or a query         */
+} mlra_status;
+
+typedef enum { MLRA_BF16 = 0, MLRA_F32 = 1 } mlra_dtype;
+
+/* Paged latent KV cache (Section 2.1: both C^KV and K^RoPE are cached; per token d_c + d_r
+ * elements, Table 1 column "KV Cache").  A contiguous cache is the identity page table. */
+typedef struct mlra_cache {
+  void* latent;              /* device [num_pages][n_blocks][page_size][d_cb] */
+  void* rope;                /* device [num_pages][page_size][d_r]            */
+  const int32_t* page_table; /* device [batch][max_pages_per_seq]             */
+  const int32_t* seq_lens;   /* device [batch]                                */
+  int32_t num_pages;
+  int32_t page_size;
+  int32_t max_pages_per_seq;
+  int32_t n_blocks;
+  int32_t d_cb;
+  int32_t d_r;
+  int32_t dtype;             /* mlra_dtype of both pools                      */
+} mlra_cache;
+
+/* Human-readable text for a status (host pointer to a static string). */
+MLRA_API const char* mlra_strerror(int status);
+
+/* Stores the newest token's cache row of every sequence (Section 2.1: C^KV and K^RoPE of each token
+ * are cached).  Row b goes to logical slot positions[b] of sequence b; positions[b] < 0 skips the
+ * sequence.  Values are converted from src_dtype to the cache dtype with round-to-nearest-even.
+ * RMSNorm, the alpha_kv scaling of Eq. (9) and RoPE happen upstream and are not applied here.
+ *   c_kv_new   [batch][n_blocks*d_cb]  blocks side by side, block b in columns [b d_cb,(b+1) d_cb)
+ *   k_rope_new [batch][d_r]
+ *   positions  [batch] int32 (device) */
+MLRA_API int mlra_append_kv(const mlra_cache* cache, int32_t batch, const void* c_kv_new, const void* k_rope_new,
+                   int32_t src_dtype, const int32_t* positions, void* stream);
+
+/* Step 1 of the absorbed decode (Section 2.1 "Query-Side Weight Absorption"), per block:
+ *   q_abs[s][b][i][:] = W^UK_(b),(i) q_nope[s][i][:]      (einsum "hp,hpc->hc", c = d_cb)
+ *   q_nope [batch][h][d_h], w_uk [n_blocks][d_cb][h*d_h], q_abs [batch][n_blocks][h][d_cb];
+ * all three have element type dtype.  Accumulation is fp32. */
+MLRA_API int mlra_absorb_q(int32_t batch, int32_t h, int32_t d_h, int32_t n_blocks, int32_t d_cb,
+                  const void* q_nope, const void* w_uk, void* q_abs, int32_t dtype, void* stream);
+
+/* Bytes of workspace mlra_decode_attn / mla_decode_attn need for these sizes on the current device
+ * (0 on invalid sizes).  max_seq_len is max_pages_per_seq * page_size of the cache passed later. */
+MLRA_API size_t mlra_decode_workspace_bytes(int32_t batch, int32_t h, int32_t n_blocks, int32_t d_cb,
+                                   int32_t max_seq_len);
+
+/* Steps 2 and 3 of the absorbed decode, per block, and the block sum (Eq. (1) applied to each block;
+ * Eq. (5); output rescale of Eq. (10)).  For sequence s, head i:
+ *   score_b[t] = softmax_scale * ( q_abs[s][b][i] . C_(b)[t] + q_rope[s][i] . K^RoPE[t] ),  t < seq_lens[s]
+ *   z_b        = sum_t Softmax(score_b)[t] C_(b)[t]
+ *   out[s][i]  = out_scale * sum_b z_b W^UV_(b),(i)
+ * The single decode query attends to all seq_lens[s] cached rows (its own row included; append first).
+ * seq_lens[s] == 0 gives a zero output row and lse = -inf.
+ *   q_abs  [batch][n_blocks][h][d_cb], q_rope [batch][h][d_r], w_uv [n_blocks][d_cb][h*d_h]: cache dtype
+ *   out    [batch][h][d_h] of out_dtype
+ *   lse    optional [batch][n_blocks][h] fp32: natural-log sum of exp(score_b); may be NULL
+ *   workspace: at least mlra_decode_workspace_bytes(batch, h, n_blocks, d_cb,
+ *              max_pages_per_seq*page_size) bytes, 256-byte aligned; contents are overwritten.
+ * Context is split into chunks processed by independent workgroups whose partial (max, sum, z) are
+ * merged with a log-sum-exp merge; results are deterministic (no atomics). */
+MLRA_API int mlra_decode_attn(const mlra_cache* cache, int32_t batch, int32_t h, int32_t d_h, const void* q_abs,
+                     const void* q_rope, const void* w_uv, float softmax_scale, float out_scale, void* out,
+                     int32_t out_dtype, float* lse, void* workspace, size_t workspace_bytes, void* stream);
+
+/* MLA decode (Section 2.1, three-step algorithm): the same computation with one latent block of
+ * d_c channels.  Requires cache->n_blocks == 1; out_scale is 1. */
+MLRA_API int mla_decode_attn(const mlra_cache* cache, int32_t batch, int32_t h, int32_t d_h, const void* q_abs,
+                    const void* q_rope, const void* w_uv, float softmax_scale, void* out, int32_t out_dtype,
+                    float* lse, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Workspace bytes for gqa_decode_attn (0 on invalid sizes). */
+MLRA_API size_t gqa_decode_workspace_bytes(int32_t batch, int32_t h, int32_t d_h, int32_t max_seq_len);
+
+/* GQA decode (Appendix C, "MQA and GQA"): query head i reads KV head floor(i / (h/g)).
+ *   out[s][i] = Softmax(softmax_scale * q[s][i] . K[t][j])_t V[t][j],  j = floor(i*g/h), t < seq_lens[s]
+ *   k_pool, v_pool [num_pages][g][page_size][d_h] of dtype; q [batch][h][d_h] of dtype
+ *   page_table [batch][max_pages_per_seq], seq_lens [batch]; out [batch][h][d_h] of out_dtype. */
+MLRA_API int gqa_decode_attn(const void* k_pool, const void* v_pool, const int32_t* page_table, const int32_t* seq_lens,
+                    int32_t num_pages, int32_t page_size, int32_t max_pages_per_seq, int32_t batch, int32_t h,
+                    int32_t g, int32_t d_h, int32_t dtype, const void* q, float softmax_scale, void* out,
+                    int32_t out_dtype, void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MLRA_H_ */

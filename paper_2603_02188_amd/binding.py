@@ -1,0 +1,208 @@
+"""ctypes binding of libmlra.so: argument marshalling only.
+
+Function names and argument order follow include/mlra.h.  Tensors are torch CUDA (ROCm) tensors
+used purely as device memory; work is enqueued on torch's current stream.  Every step of the
+path runs inside the library's HIP kernels; there is no fallback: if the library has not been
+built, or an entry point reports an error, a RuntimeError is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmlra.so")
+_lib: Optional[ctypes.CDLL] = None
+
+MLRA_BF16, MLRA_F32 = 0, 1
+
+EXPORTS = ("mlra_strerror", "mlra_append_kv", "mlra_absorb_q", "mlra_decode_workspace_bytes",
+           "mlra_decode_attn", "mla_decode_attn", "gqa_decode_workspace_bytes", "gqa_decode_attn")
+
+
+class _CacheStruct(ctypes.Structure):
+    _fields_ = [("latent", ctypes.c_void_p), ("rope", ctypes.c_void_p),
+                ("page_table", ctypes.c_void_p), ("seq_lens", ctypes.c_void_p),
+                ("num_pages", ctypes.c_int32), ("page_size", ctypes.c_int32),
+                ("max_pages_per_seq", ctypes.c_int32), ("n_blocks", ctypes.c_int32),
+                ("d_cb", ctypes.c_int32), ("d_r", ctypes.c_int32), ("dtype", ctypes.c_int32)]
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library() -> ctypes.CDLL:
+    """Loads libmlra.so (built by `python -m paper_2603_02188_amd.build`); raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(f"{_LIB_PATH} is missing: build it with `python -m paper_2603_02188_amd.build` "
+                           "(there is no CPU or PyTorch fallback for the MLRA decode path)")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, i32, f32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_float, ctypes.c_size_t
+    cp = ctypes.POINTER(_CacheStruct)
+    lib.mlra_strerror.restype = ctypes.c_char_p
+    lib.mlra_strerror.argtypes = [ctypes.c_int]
+    lib.mlra_append_kv.restype = ctypes.c_int
+    lib.mlra_append_kv.argtypes = [cp, i32, vp, vp, i32, vp, vp]
+    lib.mlra_absorb_q.restype = ctypes.c_int
+    lib.mlra_absorb_q.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, i32, vp]
+    lib.mlra_decode_workspace_bytes.restype = sz
+    lib.mlra_decode_workspace_bytes.argtypes = [i32, i32, i32, i32, i32]
+    lib.mlra_decode_attn.restype = ctypes.c_int
+    lib.mlra_decode_attn.argtypes = [cp, i32, i32, i32, vp, vp, vp, f32, f32, vp, i32, vp, vp, sz, vp]
+    lib.mla_decode_attn.restype = ctypes.c_int
+    lib.mla_decode_attn.argtypes = [cp, i32, i32, i32, vp, vp, vp, f32, vp, i32, vp, vp, sz, vp]
+    lib.gqa_decode_workspace_bytes.restype = sz
+    lib.gqa_decode_workspace_bytes.argtypes = [i32, i32, i32, i32]
+    lib.gqa_decode_attn.restype = ctypes.c_int
+    lib.gqa_decode_attn.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp, f32, vp, i32, vp,
+                                    sz, vp]
+    _lib = lib
+    return lib
+
+
+def strerror(status: int) -> str:
+    return load_library().mlra_strerror(int(status)).decode()
+
+
+def _check(status: int, what: str) -> None:
+    if status != 0:
+        raise RuntimeError(f"{what} failed: {strerror(status)} (status {status})")
+
+
+def _dt(t: torch.dtype) -> int:
+    if t == torch.bfloat16:
+        return MLRA_BF16
+    if t == torch.float32:
+        return MLRA_F32
+    raise TypeError(f"libmlra supports bfloat16 and float32, not {t}")
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("libmlra takes contiguous device tensors")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+@dataclass
+class Cache:
+    """Paged latent KV cache (struct mlra_cache): device tensors plus their dimensions."""
+
+    latent: torch.Tensor      # [num_pages][n_blocks][page_size][d_cb]
+    rope: torch.Tensor        # [num_pages][page_size][d_r]
+    page_table: torch.Tensor  # [batch][max_pages_per_seq] int32
+    seq_lens: torch.Tensor    # [batch] int32
+
+    def struct(self) -> _CacheStruct:
+        P, NB, ps, dcb = self.latent.shape
+        assert self.rope.shape[0] == P and self.rope.shape[1] == ps
+        assert self.page_table.dtype == torch.int32 and self.seq_lens.dtype == torch.int32
+        assert self.rope.dtype == self.latent.dtype
+        return _CacheStruct(self.latent.data_ptr(), self.rope.data_ptr(), self.page_table.data_ptr(),
+                            self.seq_lens.data_ptr(), P, ps, self.page_table.shape[1], NB, dcb,
+                            self.rope.shape[2], _dt(self.latent.dtype))
+
+    @property
+    def max_seq_len(self) -> int:
+        return int(self.page_table.shape[1] * self.latent.shape[2])
+
+
+def mlra_append_kv(cache: Cache, c_kv_new: torch.Tensor, k_rope_new: torch.Tensor, positions: torch.Tensor,
+                   stream=None) -> None:
+    lib = load_library()
+    cs = cache.struct()
+    batch = int(positions.shape[0])
+    assert c_kv_new.dtype == k_rope_new.dtype and positions.dtype == torch.int32
+    _check(lib.mlra_append_kv(ctypes.byref(cs), batch, _ptr(c_kv_new), _ptr(k_rope_new), _dt(c_kv_new.dtype),
+                              _ptr(positions), _stream(stream)), "mlra_append_kv")
+
+
+def mlra_absorb_q(q_nope: torch.Tensor, w_uk: torch.Tensor, q_abs: Optional[torch.Tensor] = None,
+                  stream=None) -> torch.Tensor:
+    lib = load_library()
+    batch, h, d_h = q_nope.shape
+    n_blocks, d_cb, hd = w_uk.shape
+    assert hd == h * d_h and w_uk.dtype == q_nope.dtype
+    if q_abs is None:
+        q_abs = torch.empty((batch, n_blocks, h, d_cb), dtype=q_nope.dtype, device=q_nope.device)
+    _check(lib.mlra_absorb_q(batch, h, d_h, n_blocks, d_cb, _ptr(q_nope), _ptr(w_uk), _ptr(q_abs),
+                             _dt(q_nope.dtype), _stream(stream)), "mlra_absorb_q")
+    return q_abs
+
+
+def mlra_decode_workspace_bytes(batch: int, h: int, n_blocks: int, d_cb: int, max_seq_len: int) -> int:
+    return int(load_library().mlra_decode_workspace_bytes(batch, h, n_blocks, d_cb, max_seq_len))
+
+
+def _decode(entry: str, cache: Cache, q_abs, q_rope, w_uv, softmax_scale, out_scale, out, out_dtype, lse,
+            workspace, stream):
+    lib = load_library()
+    cs = cache.struct()
+    batch, n_blocks, h, d_cb = q_abs.shape
+    d_h = w_uv.shape[2] // h
+    assert w_uv.shape == (n_blocks, d_cb, h * d_h) and q_rope.shape[:2] == (batch, h)
+    if out is None:
+        out = torch.empty((batch, h, d_h), dtype=out_dtype or q_abs.dtype, device=q_abs.device)
+    if workspace is None:
+        need = mlra_decode_workspace_bytes(batch, h, n_blocks, d_cb, cache.max_seq_len)
+        workspace = torch.empty(need, dtype=torch.uint8, device=q_abs.device)
+    args = [ctypes.byref(cs), batch, h, d_h, _ptr(q_abs), _ptr(q_rope), _ptr(w_uv), float(softmax_scale)]
+    if entry == "mlra_decode_attn":
+        args.append(float(out_scale))
+    args += [_ptr(out), _dt(out.dtype), _ptr(lse), _ptr(workspace), workspace.numel() * workspace.element_size(),
+             _stream(stream)]
+    _check(getattr(lib, entry)(*args), entry)
+    return out
+
+
+def mlra_decode_attn(cache: Cache, q_abs: torch.Tensor, q_rope: torch.Tensor, w_uv: torch.Tensor,
+                     softmax_scale: float, out_scale: float = 1.0, out: Optional[torch.Tensor] = None,
+                     out_dtype: Optional[torch.dtype] = None, lse: Optional[torch.Tensor] = None,
+                     workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    return _decode("mlra_decode_attn", cache, q_abs, q_rope, w_uv, softmax_scale, out_scale, out, out_dtype, lse,
+                   workspace, stream)
+
+
+def mla_decode_attn(cache: Cache, q_abs: torch.Tensor, q_rope: torch.Tensor, w_uv: torch.Tensor,
+                    softmax_scale: float, out: Optional[torch.Tensor] = None,
+                    out_dtype: Optional[torch.dtype] = None, lse: Optional[torch.Tensor] = None,
+                    workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    return _decode("mla_decode_attn", cache, q_abs, q_rope, w_uv, softmax_scale, 1.0, out, out_dtype, lse,
+                   workspace, stream)
+
+
+def gqa_decode_workspace_bytes(batch: int, h: int, d_h: int, max_seq_len: int) -> int:
+    return int(load_library().gqa_decode_workspace_bytes(batch, h, d_h, max_seq_len))
+
+
+def gqa_decode_attn(k_pool: torch.Tensor, v_pool: torch.Tensor, page_table: torch.Tensor, seq_lens: torch.Tensor,
+                    q: torch.Tensor, softmax_scale: float, out: Optional[torch.Tensor] = None,
+                    out_dtype: Optional[torch.dtype] = None, workspace: Optional[torch.Tensor] = None,
+                    stream=None) -> torch.Tensor:
+    lib = load_library()
+    P, g, ps, d_h = k_pool.shape
+    batch, h, _ = q.shape
+    max_pages = int(page_table.shape[1])
+    if out is None:
+        out = torch.empty((batch, h, d_h), dtype=out_dtype or q.dtype, device=q.device)
+    if workspace is None:
+        workspace = torch.empty(gqa_decode_workspace_bytes(batch, h, d_h, max_pages * ps), dtype=torch.uint8,
+                                device=q.device)
+    _check(lib.gqa_decode_attn(_ptr(k_pool), _ptr(v_pool), _ptr(page_table), _ptr(seq_lens), P, ps, max_pages,
+                               batch, h, g, d_h, _dt(k_pool.dtype), _ptr(q), float(softmax_scale), _ptr(out),
+                               _dt(out.dtype), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                               _stream(stream)), "gqa_decode_attn")
+    return out

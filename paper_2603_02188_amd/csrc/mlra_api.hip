@@ -1,0 +1,198 @@
+// C ABI of libmlra: argument validation, context-split planning, workspace carving and dispatch.
+#include <stdlib.h>
+
+#include "mlra_internal.h"
+
+namespace mlra {
+
+int device_cu_count() {
+  static int cached = 0;
+  if (cached > 0) return cached;
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) == hipSuccess &&
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0) {
+    cached = cus;
+    return cached;
+  }
+  (void)hipGetLastError();
+  return 256;  // MI355X; used only when no device can be queried (e.g. sizing on a CPU-only host)
+}
+
+// Enough workgroups to cover every CU about twice when the batch alone cannot, never chunks shorter
+// than 128 tokens (a partial costs as much traffic as ~170 cached tokens of one block).
+SplitPlan plan_splits(int batch, int n_blocks, int max_seq_len) {
+  const int kMinChunk = 128, kTile = 64;
+  const long units = (long)batch * n_blocks;
+  const long target = 2L * device_cu_count();
+  long want = (target + units - 1) / units;
+  const long max_splits = (max_seq_len + kMinChunk - 1) / kMinChunk;
+  if (want > max_splits) want = max_splits;
+  if (want < 1) want = 1;
+  long chunk = (max_seq_len + want - 1) / want;
+  chunk = (chunk + kTile - 1) / kTile * kTile;
+  if (chunk < kMinChunk) chunk = kMinChunk;
+  SplitPlan p;
+  p.chunk_tokens = (int)chunk;
+  p.n_splits = (int)((max_seq_len + chunk - 1) / chunk);
+  if (p.n_splits < 1) p.n_splits = 1;
+  return p;
+}
+
+static bool valid_dtype(int d) { return d == MLRA_BF16 || d == MLRA_F32; }
+
+static size_t decode_ws_bytes(int batch, int h, int n_blocks, int d_cb, const SplitPlan& p) {
+  const size_t units = (size_t)batch * n_blocks * p.n_splits;
+  return align_up(units * h * d_cb * sizeof(float), 256) + align_up(units * h * 2 * sizeof(float), 256);
+}
+
+static int decode_common(const mlra_cache* c, int batch, int h, int d_h, const void* q_abs, const void* q_rope,
+                         const void* w_uv, float softmax_scale, float out_scale, void* out, int out_dtype,
+                         float* lse, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!c || !q_abs || !q_rope || !w_uv || !out) return MLRA_ERR_NULL;
+  if (!c->latent || !c->rope || !c->page_table || !c->seq_lens) return MLRA_ERR_NULL;
+  if (!valid_dtype(c->dtype) || !valid_dtype(out_dtype)) return MLRA_ERR_DTYPE;
+  if (batch <= 0 || h <= 0 || d_h <= 0 || c->n_blocks <= 0 || c->d_cb <= 0 || c->d_r <= 0 || c->page_size <= 0 ||
+      c->max_pages_per_seq <= 0 || c->num_pages <= 0)
+    return MLRA_ERR_SHAPE;
+  if ((long)c->max_pages_per_seq * c->page_size > 0x7fffffffL) return MLRA_ERR_SHAPE;
+  if ((long)c->n_blocks * c->d_cb > 8192 || h > 65535 || batch > 65535) return MLRA_ERR_SHAPE;
+  const int max_seq_len = c->max_pages_per_seq * c->page_size;
+  DecodeArgs a;
+  a.plan = plan_splits(batch, c->n_blocks, max_seq_len);
+  const size_t need = decode_ws_bytes(batch, h, c->n_blocks, c->d_cb, a.plan);
+  if (!workspace || workspace_bytes < need) return MLRA_ERR_WORKSPACE;
+  if (((uintptr_t)workspace) % 256 != 0) return MLRA_ERR_WORKSPACE;
+  const size_t units = (size_t)batch * c->n_blocks * a.plan.n_splits;
+  a.part_z = (float*)workspace;
+  a.part_ml = (float*)((char*)workspace + align_up(units * h * c->d_cb * sizeof(float), 256));
+  a.latent = c->latent;
+  a.rope = c->rope;
+  a.page_table = c->page_table;
+  a.seq_lens = c->seq_lens;
+  a.page_size = c->page_size;
+  a.max_pages = c->max_pages_per_seq;
+  a.n_blocks = c->n_blocks;
+  a.d_cb = c->d_cb;
+  a.d_r = c->d_r;
+  a.batch = batch;
+  a.h = h;
+  a.d_h = d_h;
+  a.q_abs = q_abs;
+  a.q_rope = q_rope;
+  a.w_uv = w_uv;
+  a.softmax_scale = softmax_scale;
+  a.out_scale = out_scale;
+  a.out = out;
+  a.out_dtype = out_dtype;
+  a.lse = lse;
+  a.dtype = c->dtype;
+  a.stream = (hipStream_t)stream;
+  int st = decode_mfma_supported(a) ? launch_decode_mfma(a) : launch_decode_generic(a);
+  if (st != MLRA_OK) return st;
+  return launch_merge_upproj_generic(a);
+}
+
+}  // namespace mlra
+
+using namespace mlra;
+
+extern "C" {
+
+const char* mlra_strerror(int status) {
+  switch (status) {
+    case MLRA_OK: return "ok";
+    case MLRA_ERR_NULL: return "a required pointer is NULL";
+    case MLRA_ERR_SHAPE: return "a dimension is non-positive or not supported";
+    case MLRA_ERR_DTYPE: return "unknown or unsupported element type";
+    case MLRA_ERR_WORKSPACE: return "workspace missing, misaligned or smaller than required";
+    case MLRA_ERR_LAUNCH: return "the HIP runtime refused a launch or a query";
+    default: return "unknown status";
+  }
+}
+
+int mlra_append_kv(const mlra_cache* c, int32_t batch, const void* c_kv_new, const void* k_rope_new,
+                   int32_t src_dtype, const int32_t* positions, void* stream) {
+  if (!c || !c_kv_new || !k_rope_new || !positions) return MLRA_ERR_NULL;
+  if (!c->latent || !c->rope || !c->page_table) return MLRA_ERR_NULL;
+  if (!valid_dtype(c->dtype) || !valid_dtype(src_dtype)) return MLRA_ERR_DTYPE;
+  if (batch <= 0 || c->n_blocks <= 0 || c->d_cb <= 0 || c->d_r <= 0 || c->page_size <= 0 ||
+      c->max_pages_per_seq <= 0 || c->num_pages <= 0)
+    return MLRA_ERR_SHAPE;
+  return launch_append_kv(c, batch, c_kv_new, k_rope_new, src_dtype, positions, (hipStream_t)stream);
+}
+
+int mlra_absorb_q(int32_t batch, int32_t h, int32_t d_h, int32_t n_blocks, int32_t d_cb, const void* q_nope,
+                  const void* w_uk, void* q_abs, int32_t dtype, void* stream) {
+  if (!q_nope || !w_uk || !q_abs) return MLRA_ERR_NULL;
+  if (!valid_dtype(dtype)) return MLRA_ERR_DTYPE;
+  if (batch <= 0 || h <= 0 || d_h <= 0 || n_blocks <= 0 || d_cb <= 0) return MLRA_ERR_SHAPE;
+  if (h > 65535 || batch > 65535 || n_blocks > 65535 || d_h > 8192) return MLRA_ERR_SHAPE;
+  return launch_absorb_q_generic(batch, h, d_h, n_blocks, d_cb, q_nope, w_uk, q_abs, dtype, (hipStream_t)stream);
+}
+
+size_t mlra_decode_workspace_bytes(int32_t batch, int32_t h, int32_t n_blocks, int32_t d_cb, int32_t max_seq_len) {
+  if (batch <= 0 || h <= 0 || n_blocks <= 0 || d_cb <= 0 || max_seq_len <= 0) return 0;
+  return decode_ws_bytes(batch, h, n_blocks, d_cb, plan_splits(batch, n_blocks, max_seq_len));
+}
+
+int mlra_decode_attn(const mlra_cache* cache, int32_t batch, int32_t h, int32_t d_h, const void* q_abs,
+                     const void* q_rope, const void* w_uv, float softmax_scale, float out_scale, void* out,
+                     int32_t out_dtype, float* lse, void* workspace, size_t workspace_bytes, void* stream) {
+  return decode_common(cache, batch, h, d_h, q_abs, q_rope, w_uv, softmax_scale, out_scale, out, out_dtype, lse,
+                       workspace, workspace_bytes, stream);
+}
+
+int mla_decode_attn(const mlra_cache* cache, int32_t batch, int32_t h, int32_t d_h, const void* q_abs,
+                    const void* q_rope, const void* w_uv, float softmax_scale, void* out, int32_t out_dtype,
+                    float* lse, void* workspace, size_t workspace_bytes, void* stream) {
+  if (cache && cache->n_blocks != 1) return MLRA_ERR_SHAPE;
+  return decode_common(cache, batch, h, d_h, q_abs, q_rope, w_uv, softmax_scale, 1.0f, out, out_dtype, lse,
+                       workspace, workspace_bytes, stream);
+}
+
+size_t gqa_decode_workspace_bytes(int32_t batch, int32_t h, int32_t d_h, int32_t max_seq_len) {
+  if (batch <= 0 || h <= 0 || d_h <= 0 || max_seq_len <= 0) return 0;
+  const SplitPlan p = plan_splits(batch, 1, max_seq_len);
+  const size_t units = (size_t)batch * p.n_splits;
+  return align_up(units * h * d_h * sizeof(float), 256) + align_up(units * h * 2 * sizeof(float), 256);
+}
+
+int gqa_decode_attn(const void* k_pool, const void* v_pool, const int32_t* page_table, const int32_t* seq_lens,
+                    int32_t num_pages, int32_t page_size, int32_t max_pages_per_seq, int32_t batch, int32_t h,
+                    int32_t g, int32_t d_h, int32_t dtype, const void* q, float softmax_scale, void* out,
+                    int32_t out_dtype, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!k_pool || !v_pool || !page_table || !seq_lens || !q || !out) return MLRA_ERR_NULL;
+  if (!valid_dtype(dtype) || !valid_dtype(out_dtype)) return MLRA_ERR_DTYPE;
+  if (num_pages <= 0 || page_size <= 0 || max_pages_per_seq <= 0 || batch <= 0 || h <= 0 || g <= 0 || d_h <= 0)
+    return MLRA_ERR_SHAPE;
+  if (h % g != 0 || h > 65535 || batch > 65535 || d_h > 1024) return MLRA_ERR_SHAPE;
+  if ((long)max_pages_per_seq * page_size > 0x7fffffffL) return MLRA_ERR_SHAPE;
+  GqaArgs a;
+  a.plan = plan_splits(batch, 1, max_pages_per_seq * page_size);
+  const size_t units = (size_t)batch * a.plan.n_splits;
+  const size_t need = align_up(units * h * d_h * sizeof(float), 256) + align_up(units * h * 2 * sizeof(float), 256);
+  if (!workspace || workspace_bytes < need || ((uintptr_t)workspace) % 256 != 0) return MLRA_ERR_WORKSPACE;
+  a.part_o = (float*)workspace;
+  a.part_ml = (float*)((char*)workspace + align_up(units * h * d_h * sizeof(float), 256));
+  a.k_pool = k_pool;
+  a.v_pool = v_pool;
+  a.page_table = page_table;
+  a.seq_lens = seq_lens;
+  a.page_size = page_size;
+  a.max_pages = max_pages_per_seq;
+  a.batch = batch;
+  a.h = h;
+  a.g = g;
+  a.d_h = d_h;
+  a.dtype = dtype;
+  a.q = q;
+  a.softmax_scale = softmax_scale;
+  a.out = out;
+  a.out_dtype = out_dtype;
+  a.stream = (hipStream_t)stream;
+  int st = launch_gqa_generic(a);
+  if (st != MLRA_OK) return st;
+  return launch_gqa_merge(a);
+}
+
+}  // extern "C"

@@ -1,0 +1,94 @@
+// Internal helpers shared by the HIP sources of libmlra (not part of the public ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "mlra.h"
+
+namespace mlra {
+
+typedef uint16_t bf16_t;  // raw bfloat16 bit pattern
+
+// ---- element conversion ---------------------------------------------------------------------
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// Round-to-nearest-even; NaN stays NaN (quiet).
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)0x7fc0;
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float load_f32(const float* p, size_t i) { return p[i]; }
+__device__ __forceinline__ float load_f32(const bf16_t* p, size_t i) { return bf16_to_f32(p[i]); }
+__device__ __forceinline__ void store_f32(float* p, size_t i, float v) { p[i] = v; }
+__device__ __forceinline__ void store_f32(bf16_t* p, size_t i, float v) { p[i] = f32_to_bf16(v); }
+
+// ---- context split plan -------------------------------------------------------------------------
+// Context is cut into n_splits chunks of chunk_tokens (a multiple of 64) per (sequence, block).
+struct SplitPlan {
+  int n_splits;
+  int chunk_tokens;
+};
+
+int device_cu_count();
+SplitPlan plan_splits(int batch, int n_blocks, int max_seq_len);
+
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// ---- launchers implemented in the kernel sources -----------------------------------------------
+struct DecodeArgs {
+  const void* latent;
+  const void* rope;
+  const int32_t* page_table;
+  const int32_t* seq_lens;
+  int page_size, max_pages, n_blocks, d_cb, d_r;
+  int batch, h, d_h;
+  const void* q_abs;
+  const void* q_rope;
+  const void* w_uv;
+  float softmax_scale, out_scale;
+  void* out;
+  int out_dtype;
+  float* lse;
+  float* part_z;   // [batch][n_blocks][n_splits][h][d_cb]
+  float* part_ml;  // [batch][n_blocks][n_splits][h][2]  (running max, running sum)
+  SplitPlan plan;
+  int dtype;
+  hipStream_t stream;
+};
+
+int launch_append_kv(const mlra_cache* c, int batch, const void* c_kv_new, const void* k_rope_new, int src_dtype,
+                     const int32_t* positions, hipStream_t stream);
+int launch_absorb_q_generic(int batch, int h, int d_h, int n_blocks, int d_cb, const void* q_nope,
+                            const void* w_uk, void* q_abs, int dtype, hipStream_t stream);
+int launch_decode_generic(const DecodeArgs& a);
+int launch_merge_upproj_generic(const DecodeArgs& a);
+
+// Fast path (bf16, MFMA); returns false when the shape is outside what it was written for.
+bool decode_mfma_supported(const DecodeArgs& a);
+int launch_decode_mfma(const DecodeArgs& a);
+
+struct GqaArgs {
+  const void* k_pool;
+  const void* v_pool;
+  const int32_t* page_table;
+  const int32_t* seq_lens;
+  int page_size, max_pages, batch, h, g, d_h, dtype;
+  const void* q;
+  float softmax_scale;
+  void* out;
+  int out_dtype;
+  float* part_o;   // [batch][n_splits][h][d_h]
+  float* part_ml;  // [batch][n_splits][h][2]
+  SplitPlan plan;
+  hipStream_t stream;
+};
+int launch_gqa_generic(const GqaArgs& a);
+int launch_gqa_merge(const GqaArgs& a);
+
+static inline int check_launch() { return hipGetLastError() == hipSuccess ? MLRA_OK : MLRA_ERR_LAUNCH; }
+
+}  // namespace mlra

@@ -1,0 +1,81 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, and turns host-visible mistakes into error codes without launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2603_02188_amd import binding as mlra
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "mlra.h")).read()
+    return sorted(set(re.findall(r"MLRA_API\s+[\w\s\*]+?\b(\w+)\s*\(", text)))
+
+
+def test_header_and_binding_agree_on_exports():
+    assert sorted(mlra.EXPORTS) == _declared()
+
+
+def test_library_exports_every_declared_symbol():
+    lib = mlra.load_library()
+    for name in _declared():
+        assert hasattr(lib, name), name
+
+
+def test_strerror_texts():
+    assert mlra.strerror(0) == "ok"
+    for code in (-1, -2, -3, -4, -5):
+        assert mlra.strerror(code) not in ("ok", "unknown status")
+    assert mlra.strerror(-99) == "unknown status"
+
+
+def test_null_and_shape_errors_are_reported_on_the_host():
+    lib = mlra.load_library()
+    cs = mlra._CacheStruct(0, 0, 0, 0, 1, 64, 1, 4, 128, 64, 0)
+    null = ctypes.c_void_p(None)
+    assert lib.mlra_append_kv(ctypes.byref(cs), 1, null, null, 1, null, null) == -1
+    assert lib.mlra_absorb_q(1, 8, 64, 4, 64, null, null, null, 1, null) == -1
+    one = ctypes.c_void_p(256)   # never dereferenced: the shape/dtype checks come first
+    assert lib.mlra_absorb_q(0, 8, 64, 4, 64, one, one, one, 1, null) == -2
+    assert lib.mlra_absorb_q(1, 8, 64, 4, 64, one, one, one, 7, null) == -3
+    assert lib.mlra_decode_attn(None, 1, 8, 64, one, one, one, 0.1, 1.0, one, 1, null, one, 1 << 30, null) == -1
+    cs2 = mlra._CacheStruct(256, 256, 256, 256, 4, 64, 4, 4, 64, 32, 1)
+    assert lib.mlra_decode_attn(ctypes.byref(cs2), 1, 8, 64, one, one, one, 0.1, 1.0, one, 5, null, one, 1 << 30,
+                                null) == -3
+    assert lib.mlra_decode_attn(ctypes.byref(cs2), 0, 8, 64, one, one, one, 0.1, 1.0, one, 1, null, one, 1 << 30,
+                                null) == -2
+    # workspace: missing, too small, misaligned
+    assert lib.mlra_decode_attn(ctypes.byref(cs2), 1, 8, 64, one, one, one, 0.1, 1.0, one, 1, null, null, 0,
+                                null) == -4
+    assert lib.mlra_decode_attn(ctypes.byref(cs2), 1, 8, 64, one, one, one, 0.1, 1.0, one, 1, null, one, 16,
+                                null) == -4
+    assert lib.mlra_decode_attn(ctypes.byref(cs2), 1, 8, 64, one, one, one, 0.1, 1.0, one, 1, null,
+                                ctypes.c_void_p(264), 1 << 30, null) == -4
+    # MLA entry point insists on a single latent block
+    assert lib.mla_decode_attn(ctypes.byref(cs2), 1, 8, 64, one, one, one, 0.1, one, 1, null, one, 1 << 30,
+                               null) == -2
+    assert lib.gqa_decode_attn(one, one, one, one, 4, 64, 4, 1, 8, 3, 64, 0, one, 0.1, one, 1, one, 1 << 30,
+                               null) == -2   # h % g != 0
+    assert lib.gqa_decode_attn(null, one, one, one, 4, 64, 4, 1, 8, 2, 64, 0, one, 0.1, one, 1, one, 1 << 30,
+                               null) == -1
+
+
+def test_workspace_sizing():
+    assert mlra.mlra_decode_workspace_bytes(0, 8, 4, 64, 256) == 0
+    small = mlra.mlra_decode_workspace_bytes(1, 8, 4, 64, 256)
+    # at least one partial (z, m, l) per (sequence, block, head)
+    assert small >= 1 * 4 * 8 * (64 + 2) * 4
+    big = mlra.mlra_decode_workspace_bytes(64, 128, 4, 128, 8192)
+    assert big >= 64 * 4 * 128 * (128 + 2) * 4 and big % 256 == 0
+    assert mlra.gqa_decode_workspace_bytes(2, 16, 128, 4096) >= 2 * 16 * 130 * 4
+
+
+def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
+    monkeypatch.setattr(mlra, "_lib", None)
+    monkeypatch.setattr(mlra, "_LIB_PATH", str(tmp_path / "libmlra.so"))
+    with pytest.raises(RuntimeError, match="no CPU or PyTorch fallback"):
+        mlra.load_library()
