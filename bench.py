@@ -1,0 +1,186 @@
+#!/usr/bin/env python3
+"""Benchmark of the MLRA-4 decode hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C3|C2|C4|C5] [--no-cpu-baseline]
+
+One "step" = mlra_append_kv + mlra_absorb_q + mlra_decode_attn over one batch of synthetic,
+seeded inputs that are already resident in HBM.  Successive steps read different copies of the
+cache so that the 256 MB Infinity Cache cannot serve the reads.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+
+def _args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="C3", choices=["C2", "C3", "C4", "C5"])
+    ap.add_argument("--copies", type=int, default=0, help="cache copies to rotate over (0 = enough for ~3 GB)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--parity", action="store_true", help="also compare the GPU output with the oracle")
+    return ap.parse_args()
+
+
+def _cpu_baseline(inp, max_seconds=25.0):
+    """The fp64 oracle, as it stands, timed on this host on a bounded sample of the same workload."""
+    from oracle import mlra_oracle as orc
+    from paper_2603_02188_amd import inputs as gen
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    wl = inp.wl
+    lat = gen.to_f64(inp.latent_pool, wl.dtype)
+    rope = gen.to_f64(inp.rope_pool, wl.dtype)
+    qn, qr = gen.to_f64(inp.q_nope, wl.dtype), gen.to_f64(inp.q_rope, wl.dtype)
+    wk, wv = gen.to_f64(inp.w_uk, wl.dtype), gen.to_f64(inp.w_uv, wl.dtype)
+    done_tokens, done_seqs = 0, 0
+    t0 = time.perf_counter()
+    outs = []
+    for b in range(wl.batch):
+        outs.append(orc.mlra_decode_batch(lat, rope, inp.page_table, inp.seq_lens, qn, qr, wk, wv, wl.tau,
+                                          seqs=[b])[0])
+        done_tokens += int(inp.seq_lens[b])
+        done_seqs += 1
+        if time.perf_counter() - t0 > max_seconds:
+            break
+    dt = time.perf_counter() - t0
+    total_tokens = int(inp.seq_lens.sum())
+    est_step_us = dt * 1e6 * total_tokens / max(1, done_tokens)
+    return {"value": est_step_us, "unit": "us/step", "cores": int(threads), "kind": "oracle",
+            "sample": f"{done_seqs} of {wl.batch} sequences ({done_tokens} of {total_tokens} cached tokens), "
+                      f"{dt:.1f} s of fp64 numpy, scaled to the whole batch by token count"}, np.stack(outs)
+
+
+def main():
+    a = _args()
+    if a.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (the 4-way tensor-parallel case is "
+              "benchmarked as one device's share, workload C2). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2603_02188_amd import binding as mlra
+    from paper_2603_02188_amd import inputs as gen
+    from paper_2603_02188_amd import roofline as rf
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU (the MLRA decode path has no CPU fallback)", file=sys.stderr)
+        sys.exit(2)
+    mlra.load_library()
+    wl = gen.WORKLOADS[a.workload]
+    dev = "cuda"
+    t_gen = time.perf_counter()
+    inp = gen.make_decode_inputs(wl, poison=False, hole=False)
+    t_gen = time.perf_counter() - t_gen
+
+    def up(x, tag=None):
+        t = torch.from_numpy(np.ascontiguousarray(x))
+        if tag == "bf16":
+            t = t.view(torch.bfloat16)
+        return t.to(dev)
+
+    cache_bytes = inp.latent_pool.nbytes + inp.rope_pool.nbytes
+    copies = a.copies or max(2, min(16, int(np.ceil(3.0e9 / cache_bytes))))
+    lat0, rope0 = up(inp.latent_pool, wl.dtype), up(inp.rope_pool, wl.dtype)
+    page_table, seq_lens = up(inp.page_table), up(inp.seq_lens)
+    caches = [mlra.Cache(lat0, rope0, page_table, seq_lens)]
+    for _ in range(copies - 1):
+        caches.append(mlra.Cache(lat0.clone(), rope0.clone(), page_table, seq_lens))
+    q_nope, q_rope = up(inp.q_nope, wl.dtype), up(inp.q_rope, wl.dtype)
+    w_uk, w_uv = up(inp.w_uk, wl.dtype), up(inp.w_uv, wl.dtype)
+    c_new, k_new, positions = up(inp.c_kv_new), up(inp.k_rope_new), up(inp.positions)
+    q_abs = torch.empty((wl.batch, wl.n_blocks, wl.h, wl.d_cb), dtype=q_nope.dtype, device=dev)
+    out = torch.empty((wl.batch, wl.h, wl.d_h), dtype=torch.bfloat16, device=dev)
+    ws_bytes = mlra.mlra_decode_workspace_bytes(wl.batch, wl.h, wl.n_blocks, wl.d_cb, caches[0].max_seq_len)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+
+    def step(i):
+        c = caches[i % copies]
+        mlra.mlra_append_kv(c, c_new, k_new, positions)
+        mlra.mlra_absorb_q(q_nope, w_uk, q_abs)
+        mlra.mlra_decode_attn(c, q_abs, q_rope, w_uv, wl.tau, 1.0, out=out, workspace=ws)
+
+    def decode_only(i):
+        mlra.mlra_decode_attn(caches[i % copies], q_abs, q_rope, w_uv, wl.tau, 1.0, out=out, workspace=ws)
+
+    for i in range(a.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(a.steps):
+        step(a.warmup + i)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / a.steps
+
+    # the same loop again with HIP events around the decode kernels (recorded inside the library on
+    # the launch stream), for the roofline of the dominant kernel
+    mlra.mlra_kernel_timing_begin(a.steps)
+    for i in range(a.steps):
+        step(a.warmup + a.steps + i)
+    torch.cuda.synchronize()
+    main_ms, epi_ms, calls = mlra.mlra_kernel_timing_end()
+
+    # decode-attention-only latency (per-step samples with events on the launch stream)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(a.steps)]
+    for i, (e0, e1) in enumerate(evs):
+        e0.record()
+        decode_only(i)
+        e1.record()
+    torch.cuda.synchronize()
+    dec = np.array([e0.elapsed_time(e1) for e0, e1 in evs]) * 1e3
+
+    bytes_decode = rf.decode_bytes(inp.seq_lens, wl.h, wl.d_h, wl.n_blocks, wl.d_cb, wl.d_r)
+    bytes_step = (bytes_decode["total"] + rf.absorb_bytes(wl.batch, wl.h, wl.d_h, wl.n_blocks, wl.d_cb)
+                  + rf.append_bytes(wl.batch, wl.n_blocks, wl.d_cb, wl.d_r))
+    flops = rf.decode_flops(inp.seq_lens, wl.h, wl.d_h, wl.n_blocks, wl.d_cb, wl.d_r)
+    # dominant kernel: the context-streaming decode kernel; its algorithmic bytes are the cache rows of
+    # every valid token plus the absorbed / RoPE queries (W^UV and the output belong to the epilogue)
+    kernel_bytes = bytes_decode["cache"] + bytes_decode["q_abs"] + bytes_decode["q_rope"]
+    achieved = kernel_bytes / (main_ms * 1e-3) / 1e9 if main_ms > 0 else 0.0
+
+    res = {
+        "metric": "decode attention us/step, MLRA-4 bf16 (append_kv + absorb_q + decode_attn)",
+        "value": ms_per_step * 1e3, "unit": "us/step", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": wl.name, "batch": wl.batch, "context": [wl.n_min, wl.n_max], "n_blocks": wl.n_blocks,
+                   "d_cb": wl.d_cb, "d_r": wl.d_r, "h": wl.h, "d_h": wl.d_h, "page_size": wl.page_size,
+                   "cache_copies_rotated": copies, "seed": wl.seed},
+        "step_gbps": bytes_step / (ms_per_step * 1e-3) / 1e9,
+        "step_frac_of_hbm_peak": bytes_step / (ms_per_step * 1e-3) / 1e9 / rf.HBM_PEAK_GBS,
+        "decode_attn_us": {"median": float(np.median(dec)), "p10": float(np.percentile(dec, 10)),
+                           "p90": float(np.percentile(dec, 90))},
+        "decode_attn_gbps": bytes_decode["total"] / (float(np.median(dec)) * 1e-6) / 1e9,
+        "decode_attn_tflops": flops / (float(np.median(dec)) * 1e-6) / 1e12,
+        "kernels_us": {"decode_main": main_ms * 1e3, "merge_upproj": epi_ms * 1e3, "calls": calls},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": rf.HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / rf.HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "mlra decode main kernel", "algorithmic_bytes": kernel_bytes,
+                     "mfma_tflops": (flops - wl.batch * wl.h * 2.0 * wl.n_blocks * wl.d_cb * wl.d_h)
+                     / (main_ms * 1e-3) / 1e12 if main_ms > 0 else 0.0},
+        "input_gen_s": t_gen,
+    }
+    if not a.no_cpu_baseline:
+        base, ref = _cpu_baseline(inp)
+        res["cpu_baseline"] = base
+        if a.parity:
+            got = out.to(torch.float64).cpu().numpy()[: ref.shape[0]]
+            res["max_rel_err_vs_oracle"] = float(np.max(np.abs(got - ref)) / np.max(np.abs(ref)))
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

@@ -20,7 +20,8 @@ _lib: Optional[ctypes.CDLL] = None
 MLRA_BF16, MLRA_F32 = 0, 1
 
 EXPORTS = ("mlra_strerror", "mlra_append_kv", "mlra_absorb_q", "mlra_decode_workspace_bytes",
-           "mlra_decode_attn", "mla_decode_attn", "gqa_decode_workspace_bytes", "gqa_decode_attn")
+           "mlra_decode_attn", "mla_decode_attn", "gqa_decode_workspace_bytes", "gqa_decode_attn", "mlra_kernel_timing_begin",
+           "mlra_kernel_timing_end")
 
 
 class _CacheStruct(ctypes.Structure):
@@ -63,6 +64,11 @@ def load_library() -> ctypes.CDLL:
     lib.gqa_decode_attn.restype = ctypes.c_int
     lib.gqa_decode_attn.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp, f32, vp, i32, vp,
                                     sz, vp]
+    lib.mlra_kernel_timing_begin.restype = ctypes.c_int
+    lib.mlra_kernel_timing_begin.argtypes = [i32]
+    lib.mlra_kernel_timing_end.restype = ctypes.c_int
+    lib.mlra_kernel_timing_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
+                                           ctypes.POINTER(ctypes.c_int32)]
     _lib = lib
     return lib
 
@@ -206,3 +212,15 @@ def gqa_decode_attn(k_pool: torch.Tensor, v_pool: torch.Tensor, page_table: torc
                                _dt(out.dtype), _ptr(workspace), workspace.numel() * workspace.element_size(),
                                _stream(stream)), "gqa_decode_attn")
     return out
+
+
+def mlra_kernel_timing_begin(max_calls: int) -> None:
+    _check(load_library().mlra_kernel_timing_begin(int(max_calls)), "mlra_kernel_timing_begin")
+
+
+def mlra_kernel_timing_end():
+    """Returns (main kernel ms, epilogue kernel ms, calls measured), averages over the calls."""
+    a, b, n = ctypes.c_double(), ctypes.c_double(), ctypes.c_int32()
+    _check(load_library().mlra_kernel_timing_end(ctypes.byref(a), ctypes.byref(b), ctypes.byref(n)),
+           "mlra_kernel_timing_end")
+    return a.value, b.value, n.value

@@ -1,9 +1,19 @@
 // C ABI of libmlra: argument validation, context-split planning, workspace carving and dispatch.
 #include <stdlib.h>
 
+#include <vector>
+
 #include "mlra_internal.h"
 
 namespace mlra {
+
+// Optional per-kernel timing of the decode entry points (see mlra_kernel_timing_begin).
+static std::vector<hipEvent_t> g_events;
+static int g_timing_cap = 0, g_timing_calls = 0;
+
+static void timing_mark(int which, hipStream_t stream) {
+  if (g_timing_calls < g_timing_cap) (void)hipEventRecord(g_events[3 * g_timing_calls + which], stream);
+}
 
 int device_cu_count() {
   static int cached = 0;
@@ -87,9 +97,14 @@ static int decode_common(const mlra_cache* c, int batch, int h, int d_h, const v
   a.lse = lse;
   a.dtype = c->dtype;
   a.stream = (hipStream_t)stream;
+  timing_mark(0, a.stream);
   int st = decode_mfma_supported(a) ? launch_decode_mfma(a) : launch_decode_generic(a);
   if (st != MLRA_OK) return st;
-  return launch_merge_upproj_generic(a);
+  timing_mark(1, a.stream);
+  st = launch_merge_upproj_generic(a);
+  timing_mark(2, a.stream);
+  if (g_timing_calls < g_timing_cap) ++g_timing_calls;
+  return st;
 }
 
 }  // namespace mlra
@@ -148,6 +163,41 @@ int mla_decode_attn(const mlra_cache* cache, int32_t batch, int32_t h, int32_t d
   if (cache && cache->n_blocks != 1) return MLRA_ERR_SHAPE;
   return decode_common(cache, batch, h, d_h, q_abs, q_rope, w_uv, softmax_scale, 1.0f, out, out_dtype, lse,
                        workspace, workspace_bytes, stream);
+}
+
+int mlra_kernel_timing_begin(int32_t max_calls) {
+  if (max_calls <= 0 || max_calls > 100000) return MLRA_ERR_SHAPE;
+  for (hipEvent_t e : g_events) (void)hipEventDestroy(e);
+  g_events.assign((size_t)3 * max_calls, nullptr);
+  for (hipEvent_t& e : g_events)
+    if (hipEventCreate(&e) != hipSuccess) return MLRA_ERR_LAUNCH;
+  g_timing_calls = 0;
+  g_timing_cap = max_calls;
+  return MLRA_OK;
+}
+
+int mlra_kernel_timing_end(double* main_kernel_ms, double* epilogue_kernel_ms, int32_t* calls) {
+  if (!main_kernel_ms || !epilogue_kernel_ms || !calls) return MLRA_ERR_NULL;
+  double a = 0.0, b = 0.0;
+  int st = MLRA_OK;
+  for (int i = 0; i < g_timing_calls; ++i) {
+    float ms0 = 0.f, ms1 = 0.f;
+    if (hipEventSynchronize(g_events[3 * i + 2]) != hipSuccess ||
+        hipEventElapsedTime(&ms0, g_events[3 * i], g_events[3 * i + 1]) != hipSuccess ||
+        hipEventElapsedTime(&ms1, g_events[3 * i + 1], g_events[3 * i + 2]) != hipSuccess) {
+      st = MLRA_ERR_LAUNCH;
+      break;
+    }
+    a += ms0;
+    b += ms1;
+  }
+  *calls = g_timing_calls;
+  *main_kernel_ms = g_timing_calls ? a / g_timing_calls : 0.0;
+  *epilogue_kernel_ms = g_timing_calls ? b / g_timing_calls : 0.0;
+  for (hipEvent_t e : g_events) (void)hipEventDestroy(e);
+  g_events.clear();
+  g_timing_cap = g_timing_calls = 0;
+  return st;
 }
 
 size_t gqa_decode_workspace_bytes(int32_t batch, int32_t h, int32_t d_h, int32_t max_seq_len) {

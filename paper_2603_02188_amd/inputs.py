@@ -229,13 +229,16 @@ def make_decode_inputs(wl: Workload, poison: bool = True, hole: bool = False,
         n_fill = n - 1 if hole else n
         lat_s = to_storage(latent[:n_fill], wl.dtype)
         rope_s = to_storage(rope[:n_fill], wl.dtype)
-        n_pages_b = (n_fill + ps - 1) // ps
-        for p in range(n_pages_b):
-            lo, hi = p * ps, min((p + 1) * ps, n_fill)
-            phys = int(table[b, p])
-            blk = lat_s[lo:hi].reshape(hi - lo, NB, dcb).transpose(1, 0, 2)
-            latent_pool[phys, :, : hi - lo, :] = blk
-            rope_pool[phys, : hi - lo, :] = rope_s[lo:hi]
+        full = n_fill // ps                      # whole pages in one scatter, then the ragged tail
+        if full:
+            phys = table[b, :full]
+            latent_pool[phys] = lat_s[:full * ps].reshape(full, ps, NB, dcb).transpose(0, 2, 1, 3)
+            rope_pool[phys] = rope_s[:full * ps].reshape(full, ps, dr)
+        rem = n_fill - full * ps
+        if rem:
+            phys = int(table[b, full])
+            latent_pool[phys, :, :rem, :] = lat_s[full * ps:].reshape(rem, NB, dcb).transpose(1, 0, 2)
+            rope_pool[phys, :rem, :] = rope_s[full * ps:]
     q_nope, q_rope, w_uk, w_uv = draw_queries_weights(wl)
     return DecodeInputs(wl, latent_pool, rope_pool, table, seq_lens, q_nope, q_rope, w_uk, w_uv,
                         c_kv_new, k_rope_new, (seq_lens - 1).astype(np.int32))
@@ -292,11 +295,16 @@ def make_gqa_inputs(wl: Workload, poison: bool = True,
         rng = np.random.default_rng([wl.seed, 0xE55, b])
         k = to_storage(rng.standard_normal((n, g, dh), dtype=np.float32), wl.dtype)
         v = to_storage(rng.standard_normal((n, g, dh), dtype=np.float32), wl.dtype)
-        for p in range((n + ps - 1) // ps):
-            lo, hi = p * ps, min((p + 1) * ps, n)
-            phys = int(table[b, p])
-            k_pool[phys, :, : hi - lo, :] = k[lo:hi].transpose(1, 0, 2)
-            v_pool[phys, :, : hi - lo, :] = v[lo:hi].transpose(1, 0, 2)
+        full = n // ps
+        if full:
+            phys = table[b, :full]
+            k_pool[phys] = k[:full * ps].reshape(full, ps, g, dh).transpose(0, 2, 1, 3)
+            v_pool[phys] = v[:full * ps].reshape(full, ps, g, dh).transpose(0, 2, 1, 3)
+        rem = n - full * ps
+        if rem:
+            phys = int(table[b, full])
+            k_pool[phys, :, :rem, :] = k[full * ps:].transpose(1, 0, 2)
+            v_pool[phys, :, :rem, :] = v[full * ps:].transpose(1, 0, 2)
     rng = np.random.default_rng([wl.seed, 0xF66])
     q = to_storage(rng.standard_normal((wl.batch, wl.h, dh), dtype=np.float32), wl.dtype)
     return GqaInputs(wl, k_pool, v_pool, table, seq_lens, q)
