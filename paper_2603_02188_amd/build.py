@@ -21,6 +21,7 @@ LIB = os.path.join(PKG, "libmlra.so")
 HIP_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # keep packed-fp32 VALU forms out
+    "-mllvm", "-amdgpu-mfma-vgpr-form",   # MFMA results in VGPRs: AGPRs are left to the pinned query operands
     "-Wno-unused-command-line-argument",
 ]
 

@@ -99,6 +99,12 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) qreg[nt][8 + ks] = *(const bf16x8*)(qr + ks * 16);
   }
+  // Pin the queries into accumulation registers: MFMA reads its B operand from there directly, which
+  // leaves the architectural VGPRs to the per-tile working set.
+#pragma unroll
+  for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+    for (int ks = 0; ks < 12; ++ks) asm volatile("" : "+a"(qreg[nt][ks]));
 
   // ---- page ids of up to 64 tiles ahead, one per lane ----
   const int32_t* pt_row = p.page_table + (size_t)seq * p.max_pages;
@@ -164,25 +170,6 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
     }
   }
 
-  auto compute_s = [&](int stage_idx, f32x16 (&sacc)[2]) {
-    const unsigned char* lat = smem + stage_idx * kStageBytes;
-    const unsigned char* rope = lat + kLatBytes;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) { sacc[0][i] = 0.f; sacc[1][i] = 0.f; }
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      const bf16x8 a = *(const bf16x8*)(lat + s_tok * (kDcb * 2) + (((2 * ks + g) ^ s_f) << 4));
-      sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[0][ks], sacc[0], 0, 0, 0);
-      sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[1][ks], sacc[1], 0, 0, 0);
-    }
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      const bf16x8 a = *(const bf16x8*)(rope + s_tok * (kDr * 2) + (((2 * ks + g) ^ s_f) << 4));
-      sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[0][8 + ks], sacc[0], 0, 0, 0);
-      sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[1][8 + ks], sacc[1], 0, 0, 0);
-    }
-  };
-
   float m_run[2] = {kNegBig, kNegBig}, l_run[2] = {0.f, 0.f};
   f32x16 zacc[4][2];
 #pragma unroll
@@ -194,80 +181,93 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
 
   const float sc = p.scale_log2;
 
-  // online softmax of one 32-token x 64-head score tile, then Z^T += V^T P^T
-  auto softmax_pv = [&](int j, f32x16 (&s)[2]) {
-    bf16x8 pb[2][2];
-    const bool tail = (j == ntiles - 1) && (nvalid_last < kTile);
-#pragma unroll
-    for (int nt = 0; nt < 2; ++nt) {
-      if (tail) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int tok = tw * 32 + (r >> 2) * 8 + g * 4 + (r & 3);
-          if (tok >= nvalid_last) s[nt][r] = -INFINITY;
-        }
-      }
-      float mx = s[nt][0];
-#pragma unroll
-      for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[nt][r]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float cand = mx * sc;
-      const bool need = cand > m_run[nt] + kLazy;
-      if (__any(need)) {
-        const float m_new = need ? cand : m_run[nt];
-        const float alpha = __builtin_amdgcn_exp2f(m_run[nt] - m_new);
-#pragma unroll
-        for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) zacc[mt][nt][i] *= alpha;
-        l_run[nt] *= alpha;
-        m_run[nt] = m_new;
-      }
-      const float neg_m = -m_run[nt];
-      float lsum = 0.f;
+  // online softmax of one 32-token x 32-head score tile (accumulator layout: this lane owns head
+  // column c32 of head tile nt and 16 of the 32 tokens); returns P^T as the two B operands of PV
+  auto softmax = [&](int nt, bool tail, f32x16& s, bf16x8 (&pb)[2]) {
+    if (tail) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(s[nt][r], sc, neg_m));
-        lsum += pr;
-        pb[nt][r >> 3][r & 7] = (__bf16)pr;
+        const int tok = tw * 32 + (r >> 2) * 8 + g * 4 + (r & 3);
+        if (tok >= nvalid_last) s[r] = -INFINITY;
       }
-      l_run[nt] += lsum;
     }
-    const unsigned char* lat = smem + (j % STAGES) * kStageBytes;
+    float mx = s[0];
 #pragma unroll
-    for (int ss = 0; ss < 2; ++ss) {
+    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float cand = mx * sc;
+    const bool need = cand > m_run[nt] + kLazy;
+    if (__any(need)) {
+      const float m_new = need ? cand : m_run[nt];
+      const float alpha = __builtin_amdgcn_exp2f(m_run[nt] - m_new);
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) zacc[mt][nt][i] *= alpha;
+      l_run[nt] *= alpha;
+      m_run[nt] = m_new;
+    }
+    const float neg_m = -m_run[nt];
+    float lsum = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], sc, neg_m));
+      lsum += pr;
+      pb[r >> 3][r & 7] = (__bf16)pr;
+    }
+    l_run[nt] += lsum;
+  };
+
+  // ---- main loop: loads run STAGES-1 tiles ahead of the tile being consumed ----
+  for (int jj = 0; jj < STAGES - 1 && jj < ntiles; ++jj) issue_tile(jj);
+
+  for (int j = 0; j < ntiles; ++j) {
+    if (j + STAGES - 2 <= ntiles - 1) wait_vmcnt<kLoadsPerTile * (STAGES - 2)>(); else wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();   // tile j landed for every wave; everyone is done with tile j-1
+    if (j + STAGES - 1 < ntiles) issue_tile(j + STAGES - 1);
+
+    const unsigned char* lat = smem + (j % STAGES) * kStageBytes;
+    const unsigned char* rope = lat + kLatBytes;
+    const bool tail = (j == ntiles - 1) && (nvalid_last < kTile);
+
+    // key operands (this wave's 32 token rows, all 192 channels) and transposed value operands
+    bf16x8 ka[12], va[2][4];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks)
+      ka[ks] = *(const bf16x8*)(lat + s_tok * (kDcb * 2) + (((2 * ks + g) ^ s_f) << 4));
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+      ka[8 + ks] = *(const bf16x8*)(rope + s_tok * (kDr * 2) + (((2 * ks + g) ^ s_f) << 4));
+#pragma unroll
+    for (int ss = 0; ss < 2; ++ss)
 #pragma unroll
       for (int mt = 0; mt < 4; ++mt) {
         const short4v lo = lds_tr16(lat + pv_off[ss][mt]);
         const short4v hi = lds_tr16(lat + pv_off[ss][mt] + 8 * (kDcb * 2));
-        const short8v both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        const bf16x8 a = __builtin_bit_cast(bf16x8, both);
-        zacc[mt][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[0][ss], zacc[mt][0], 0, 0, 0);
-        zacc[mt][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[1][ss], zacc[mt][1], 0, 0, 0);
+        va[ss][mt] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
       }
-    }
-  };
 
-  // ---- software pipeline: loads run STAGES-1 tiles ahead, scores one tile ahead of softmax/PV ----
-  for (int jj = 0; jj < STAGES - 1 && jj < ntiles; ++jj) issue_tile(jj);
-  if (ntiles - 1 >= STAGES - 2) wait_vmcnt<kLoadsPerTile * (STAGES - 2)>(); else wait_vmcnt<0>();
-  __builtin_amdgcn_s_barrier();
+    f32x16 s0, s1;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { s0[i] = 0.f; s1[i] = 0.f; }
+#pragma unroll
+    for (int ks = 0; ks < 12; ++ks) s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[0][ks], s0, 0, 0, 0);
+#pragma unroll
+    for (int ks = 0; ks < 12; ++ks) s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[1][ks], s1, 0, 0, 0);
 
-  f32x16 s_a[2], s_b[2];
-  compute_s(0, s_a);
-
-  auto iteration = [&](int j, f32x16 (&s_cur)[2], f32x16 (&s_nxt)[2]) {
-    if (j + 1 < ntiles) {
-      if (j + STAGES - 2 <= ntiles - 1) wait_vmcnt<kLoadsPerTile * (STAGES - 3)>(); else wait_vmcnt<0>();
-    }
-    __builtin_amdgcn_s_barrier();   // tile j+1 landed for every wave; everyone is done with tile j-1
-    if (j + STAGES - 1 < ntiles) issue_tile(j + STAGES - 1);
-    if (j + 1 < ntiles) compute_s((j + 1) % STAGES, s_nxt);
-    softmax_pv(j, s_cur);
-  };
-  for (int j = 0; j < ntiles; j += 2) {
-    iteration(j, s_a, s_b);
-    if (j + 1 < ntiles) iteration(j + 1, s_b, s_a);
+    bf16x8 pb0[2], pb1[2];
+    softmax(0, tail, s0, pb0);
+#pragma unroll
+    for (int ss = 0; ss < 2; ++ss)
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt)
+        zacc[mt][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[ss][mt], pb0[ss], zacc[mt][0], 0, 0, 0);
+    softmax(1, tail, s1, pb1);
+#pragma unroll
+    for (int ss = 0; ss < 2; ++ss)
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt)
+        zacc[mt][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[ss][mt], pb1[ss], zacc[mt][1], 0, 0, 0);
   }
 
   // ---- merge the two token halves of each head half through LDS, write the chunk's partial ----
