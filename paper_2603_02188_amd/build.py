@@ -14,6 +14,11 @@ import subprocess
 import sys
 from concurrent.futures import ThreadPoolExecutor
 
+try:
+    from .check_isa import find_overlaps
+except ImportError:  # run as a script
+    from check_isa import find_overlaps
+
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 LIB = os.path.join(PKG, "libmlra.so")
@@ -54,6 +59,13 @@ def build(verbose: bool = False, jobs: int = 8) -> str:
         out = _run([hipcc, *HIP_FLAGS, *inc, "-DMLRA_BUILDING", "-c", src, "-o", obj])
         if verbose and out.strip():
             print(out)
+        # device assembly of the same translation unit, scanned for MFMA register overlaps
+        asm = obj[:-2] + ".s"
+        _run([hipcc, *HIP_FLAGS, *inc, "-DMLRA_BUILDING", "--cuda-device-only", "-S", src, "-o", asm])
+        bad = find_overlaps(open(asm).read())
+        if bad:
+            raise RuntimeError(f"{src}: MFMA destination overlaps a source operand:\n" +
+                               "\n".join(f"  {asm}:{ln}: {text}" for ln, text in bad))
         return obj
 
     with ThreadPoolExecutor(max_workers=max(1, min(jobs, len(srcs)))) as ex:

@@ -1,0 +1,39 @@
+"""Scans generated gfx950 assembly for MFMA register overlaps that the hardware does not allow.
+
+A multi-pass MFMA whose destination is not tied to its accumulator input (srcC is a constant) must
+not write registers it still reads as srcA / srcB.  The build runs this over every kernel's assembly
+and fails if such an instruction was emitted.
+"""
+from __future__ import annotations
+
+import re
+import sys
+
+_MFMA = re.compile(r"^\s*v_mfma_\w+\s+([av])\[(\d+):(\d+)\],\s*([av])\[(\d+):(\d+)\],\s*([av])\[(\d+):(\d+)\],\s*(\S+)")
+
+
+def _overlap(a, b):
+    return a[0] == b[0] and not (a[2] < b[1] or b[2] < a[1])
+
+
+def find_overlaps(asm_text: str):
+    bad = []
+    for ln, line in enumerate(asm_text.splitlines(), 1):
+        m = _MFMA.match(line)
+        if not m:
+            continue
+        dst = (m.group(1), int(m.group(2)), int(m.group(3)))
+        src_a = (m.group(4), int(m.group(5)), int(m.group(6)))
+        src_b = (m.group(7), int(m.group(8)), int(m.group(9)))
+        if _overlap(dst, src_a) or _overlap(dst, src_b):
+            bad.append((ln, line.strip()))
+    return bad
+
+
+if __name__ == "__main__":
+    total = 0
+    for path in sys.argv[1:]:
+        for ln, text in find_overlaps(open(path).read()):
+            print(f"{path}:{ln}: {text}")
+            total += 1
+    sys.exit(1 if total else 0)

@@ -11,12 +11,15 @@
 //     Z^T += V^T P^T (channels x heads); V^T comes from the row-major tile through LDS transpose reads.
 //   * Running max is updated lazily (only when it grows by more than 2^8), which is exact: the
 //     partial (m, l, z) stays self-consistent and the merge kernel normalises.
+#include <type_traits>
+
 #include "mlra_internal.h"
 
 namespace mlra {
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(4))) short short4v;
 typedef __attribute__((ext_vector_type(8))) short short8v;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
@@ -56,19 +59,26 @@ __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt((N & 0xF) | (0x7 << 4) | (0xF << 8) | ((N >> 4) << 14));
 }
 
-// Direct-to-LDS load: lane i's 16 bytes at (sbase + voff_i) land at LDS byte address m0_base + 16 i.
-// Written as inline asm so that the compiler's wait-count insertion does not tie later LDS reads to
-// these loads (it would drain all of them before every transpose read); completion is tracked by the
-// explicit wait_vmcnt + barrier pairs below.  m0 is not otherwise used in this kernel.
-__device__ __forceinline__ void lds_dma16(const void* sbase, unsigned voff, unsigned m0_base) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-               :
-               : "s"(m0_base), "v"(voff), "s"(sbase)
-               : "memory");
+// Direct-to-LDS load: lane i's 16 bytes at (sbase + voff_i + OFF) land at LDS byte address
+// m0 + OFF + 16 i (the instruction offset moves both sides).  Written as inline asm so that the
+// compiler's wait-count insertion does not tie later LDS reads to these loads (it would drain all of
+// them before every transpose read); completion is tracked by the explicit wait_vmcnt + barrier pairs
+// below.  m0 is not otherwise used in this kernel.
+__device__ __forceinline__ void set_m0(unsigned v) { asm volatile("s_mov_b32 m0, %0\n\ts_nop 0" : : "s"(v) : "memory"); }
+template <int OFF>
+__device__ __forceinline__ void lds_dma16(const void* sbase, unsigned voff) {
+  asm volatile("global_load_lds_dwordx4 %0, %1 offset:%2" : : "v"(voff), "s"(sbase), "n"(OFF) : "memory");
 }
 
 __device__ __forceinline__ short4v lds_tr16(const void* p) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3)))*)p);
+}
+
+// Z accumulation MFMA with the accumulator held in accumulation registers (the rest of the kernel is
+// compiled with MFMA results in architectural VGPRs).  The compiler does not know this is an MFMA, so
+// before any non-MFMA instruction reads or writes these accumulators the code passes zacc_fence().
+__device__ __forceinline__ void mfma_acc(f32x16& acc, const bf16x8& a, const bf16x8& b) {
+  asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
 }
 
 template <int STAGES>
@@ -115,57 +125,82 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
   int pid_vec = load_page_ids(0);
   int pid_next = 0;
 
-  // per-lane constants of the tile loads: row within the tile and byte offset within the row
-  int lat_t[4], lat_off[4], rope_t[2], rope_off[2];
+  // ---- tile loads.  Wave w fills LDS chunks [256 w, 256 w + 256) of the latent tile with four loads
+  // and chunks [128 w, 128 w + 128) of the RoPE tile with two; load q of a wave sits 1024 bytes after
+  // load q-1 both in LDS and (four latent rows / eight RoPE rows further) in global memory, so the
+  // instruction offset covers it and only the swizzle parity of the row changes the lane offset.
+  unsigned lat_voff[2], rope_voff;
 #pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    const int P = (wave * 4 + q) * 64 + lane;
-    lat_t[q] = P >> 4;
-    lat_off[q] = ((P & 15) ^ swz((P >> 4) & 7)) << 4;
-  }
-#pragma unroll
-  for (int q = 0; q < 2; ++q) {
-    const int P = (wave * 2 + q) * 64 + lane;
-    rope_t[q] = P >> 3;
-    rope_off[q] = ((P & 7) ^ swz((P >> 3) & 7)) << 4;
-  }
+  for (int par = 0; par < 2; ++par)
+    lat_voff[par] = (lane >> 4) * (kDcb * 2) + (((lane & 15) ^ swz(4 * par + (lane >> 4))) << 4);
+  rope_voff = (lane >> 3) * (kDr * 2) + (((lane & 7) ^ swz(lane >> 3)) << 4);
   const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
   const unsigned wave_u = __builtin_amdgcn_readfirstlane(wave);
+  const size_t lat_page_bytes = (size_t)p.n_blocks * p.page_size * (kDcb * 2);
+  const size_t rope_page_bytes = (size_t)p.page_size * (kDr * 2);
+  const char* lat_blk = (const char*)p.latent + (size_t)blk * p.page_size * (kDcb * 2);
+  int issue_slot = t0 % p.page_size;   // slot of the next tile to issue inside its page (tiles go in order)
+  int issue_stage = 0;
 
   auto issue_tile = [&](int jj) {
     if ((jj & 63) == 32) pid_next = load_page_ids(jj + 32);
     if ((jj & 63) == 0 && jj > 0) pid_vec = pid_next;
     const int page = __builtin_amdgcn_readlane(pid_vec, jj & 63);
-    const int tok0 = t0 + jj * kTile;
-    const int slot0 = tok0 % p.page_size;
-    const int last = min(kTile, t1 - tok0) - 1;   // rows past the chunk re-read its last row (finite, weight 0)
-    const char* lat_base =
-        (const char*)p.latent + ((((size_t)page * p.n_blocks + blk) * p.page_size + slot0) * kDcb) * 2;
-    const char* rope_base = (const char*)p.rope + (((size_t)page * p.page_size + slot0) * kDr) * 2;
-    const unsigned stage = lds_base + (jj % STAGES) * kStageBytes;
+    const int last = min(kTile, t1 - t0 - jj * kTile) - 1;
+    // start of this tile's latent rows (block plane blk) and RoPE rows inside the page
+    const char* lat_tile = lat_blk + (size_t)page * lat_page_bytes + (size_t)issue_slot * (kDcb * 2);
+    const char* rope_tile = (const char*)p.rope + (size_t)page * rope_page_bytes + (size_t)issue_slot * (kDr * 2);
+    const unsigned stage = lds_base + issue_stage * kStageBytes;
+    if (last == kTile - 1) {
+      set_m0(stage + wave_u * 4096);
+      lds_dma16<0>(lat_tile + wave_u * 4096, lat_voff[0]);
+      lds_dma16<1024>(lat_tile + wave_u * 4096, lat_voff[1]);
+      lds_dma16<2048>(lat_tile + wave_u * 4096, lat_voff[0]);
+      lds_dma16<3072>(lat_tile + wave_u * 4096, lat_voff[1]);
+      set_m0(stage + kLatBytes + wave_u * 2048);
+      lds_dma16<0>(rope_tile + wave_u * 2048, rope_voff);
+      lds_dma16<1024>(rope_tile + wave_u * 2048, rope_voff);
+    } else {
+      // ragged end of the chunk: rows past it re-read its last row (finite values, weight 0 later).
+      // Offsets are taken from the tile start so that they never go negative.
 #pragma unroll
-    for (int q = 0; q < 4; ++q)
-      lds_dma16(lat_base, min(lat_t[q], last) * (kDcb * 2) + lat_off[q], stage + (wave_u * 4 + q) * 1024);
+      for (int q = 0; q < 4; ++q) {
+        const int t = (wave * 4 + q) * 4 + (lane >> 4);     // 0..63
+        const unsigned row = (unsigned)min(t, last);          // 0..last
+        set_m0(stage + wave_u * 4096 + q * 1024);
+        lds_dma16<0>(lat_tile, row * (kDcb * 2) + (((lane & 15) ^ swz(t & 7)) << 4));
+      }
 #pragma unroll
-    for (int q = 0; q < 2; ++q)
-      lds_dma16(rope_base, min(rope_t[q], last) * (kDr * 2) + rope_off[q],
-                stage + kLatBytes + (wave_u * 2 + q) * 1024);
+      for (int q = 0; q < 2; ++q) {
+        const int t = (wave * 2 + q) * 8 + (lane >> 3);     // 0..63
+        const unsigned row = (unsigned)min(t, last);
+        set_m0(stage + kLatBytes + wave_u * 2048 + q * 1024);
+        lds_dma16<0>(rope_tile, row * (kDr * 2) + (((lane & 7) ^ swz(t & 7)) << 4));
+      }
+    }
+    issue_slot += kTile;
+    if (issue_slot >= p.page_size) issue_slot = 0;
+    issue_stage = (issue_stage + 1 == STAGES) ? 0 : issue_stage + 1;
   };
 
-  // ---- per-lane LDS read offsets ----
+  // ---- per-lane LDS read offsets inside a stage ----
   const int s_tok = tw * 32 + c32;
   const int s_f = swz(s_tok & 7);
-  int pv_off[2][4];
+  unsigned k_off[12], v_off[2][4];
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) k_off[ks] = s_tok * (kDcb * 2) + (((2 * ks + g) ^ s_f) << 4);
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) k_off[8 + ks] = kLatBytes + s_tok * (kDr * 2) + (((2 * ks + g) ^ s_f) << 4);
   {
     const int k = (lane & 15) >> 2, seg = lane & 3, hb = (lane >> 4) & 1;
 #pragma unroll
-    for (int s = 0; s < 2; ++s) {
-      const int ta = tw * 32 + 16 * s + 4 * g + k;
+    for (int ss = 0; ss < 2; ++ss) {
+      const int ta = tw * 32 + 16 * ss + 4 * g + k;
       const int f = swz(ta & 7);
 #pragma unroll
       for (int mt = 0; mt < 4; ++mt) {
         const int cc = 4 * mt + 2 * hb + (seg >> 1);
-        pv_off[s][mt] = ta * (kDcb * 2) + ((cc ^ f) << 4) + ((seg & 1) << 3);
+        v_off[ss][mt] = ta * (kDcb * 2) + ((cc ^ f) << 4) + ((seg & 1) << 3);
       }
     }
   }
@@ -175,100 +210,261 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
 #pragma unroll
   for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt)
+    for (int nt = 0; nt < 2; ++nt) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) zacc[mt][nt][i] = 0.f;
+      asm volatile("" : "+a"(zacc[mt][nt]));
+    }
+  // waits out any in-flight Z MFMA before ordinary instructions touch the accumulators (and after they did)
+  auto zacc_fence = [&]() {
+    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 7"
+                 : "+a"(zacc[0][0]), "+a"(zacc[0][1]), "+a"(zacc[1][0]), "+a"(zacc[1][1]), "+a"(zacc[2][0]),
+                   "+a"(zacc[2][1]), "+a"(zacc[3][0]), "+a"(zacc[3][1]));
+  };
 
   const float sc = p.scale_log2;
 
-  // online softmax of one 32-token x 32-head score tile (accumulator layout: this lane owns head
-  // column c32 of head tile nt and 16 of the 32 tokens); returns P^T as the two B operands of PV
-  auto softmax = [&](int nt, bool tail, f32x16& s, bf16x8 (&pb)[2]) {
-    if (tail) {
+  // K operands (this wave's 32 token rows x 192 channels) of the tile in stage st
+  auto load_k = [&](int st, bf16x8 (&ka)[12]) {
+    const unsigned char* base = smem + st * kStageBytes;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int tok = tw * 32 + (r >> 2) * 8 + g * 4 + (r & 3);
-        if (tok >= nvalid_last) s[r] = -INFINITY;
-      }
-    }
-    float mx = s[0];
-#pragma unroll
-    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float cand = mx * sc;
-    const bool need = cand > m_run[nt] + kLazy;
-    if (__any(need)) {
-      const float m_new = need ? cand : m_run[nt];
-      const float alpha = __builtin_amdgcn_exp2f(m_run[nt] - m_new);
-#pragma unroll
-      for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) zacc[mt][nt][i] *= alpha;
-      l_run[nt] *= alpha;
-      m_run[nt] = m_new;
-    }
-    const float neg_m = -m_run[nt];
-    float lsum = 0.f;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], sc, neg_m));
-      lsum += pr;
-      pb[r >> 3][r & 7] = (__bf16)pr;
-    }
-    l_run[nt] += lsum;
+    for (int ks = 0; ks < 12; ++ks) ka[ks] = *(const bf16x8*)(base + k_off[ks]);
   };
-
-  // ---- main loop: loads run STAGES-1 tiles ahead of the tile being consumed ----
-  for (int jj = 0; jj < STAGES - 1 && jj < ntiles; ++jj) issue_tile(jj);
-
-  for (int j = 0; j < ntiles; ++j) {
-    if (j + STAGES - 2 <= ntiles - 1) wait_vmcnt<kLoadsPerTile * (STAGES - 2)>(); else wait_vmcnt<0>();
-    __builtin_amdgcn_s_barrier();   // tile j landed for every wave; everyone is done with tile j-1
-    if (j + STAGES - 1 < ntiles) issue_tile(j + STAGES - 1);
-
-    const unsigned char* lat = smem + (j % STAGES) * kStageBytes;
-    const unsigned char* rope = lat + kLatBytes;
-    const bool tail = (j == ntiles - 1) && (nvalid_last < kTile);
-
-    // key operands (this wave's 32 token rows, all 192 channels) and transposed value operands
-    bf16x8 ka[12], va[2][4];
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks)
-      ka[ks] = *(const bf16x8*)(lat + s_tok * (kDcb * 2) + (((2 * ks + g) ^ s_f) << 4));
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks)
-      ka[8 + ks] = *(const bf16x8*)(rope + s_tok * (kDr * 2) + (((2 * ks + g) ^ s_f) << 4));
+  // transposed V operands (all 128 channels x this wave's 32 token rows) of the tile in stage st
+  auto load_v = [&](int st, bf16x8 (&va)[2][4]) {
+    const unsigned char* base = smem + st * kStageBytes;
 #pragma unroll
     for (int ss = 0; ss < 2; ++ss)
 #pragma unroll
       for (int mt = 0; mt < 4; ++mt) {
-        const short4v lo = lds_tr16(lat + pv_off[ss][mt]);
-        const short4v hi = lds_tr16(lat + pv_off[ss][mt] + 8 * (kDcb * 2));
+        const short4v lo = lds_tr16(base + v_off[ss][mt]);
+        const short4v hi = lds_tr16(base + v_off[ss][mt] + 8 * (kDcb * 2));
         va[ss][mt] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
       }
+  };
+  // raw scores S^T = K Q^T of this wave's 32 token rows against its 64 heads
+  auto scores = [&](const bf16x8 (&ka)[12], f32x16& sa, f32x16& sb) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { sa[i] = 0.f; sb[i] = 0.f; }
+#pragma unroll
+    for (int ks = 0; ks < 12; ++ks) {
+      sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[0][ks], sa, 0, 0, 0);
+      sb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[1][ks], sb, 0, 0, 0);
+    }
+  };
+  // running-max bookkeeping of head tile nt for raw scores s (accumulator layout: this lane owns head
+  // column c32 and 16 of the 32 tokens); returns true if this lane's head needs a rescale
+  auto new_max = [&](int nt, const f32x16& sv, float& m_new) {
+    float mx = sv[0];
+#pragma unroll
+    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sv[r]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float cand = mx * sc;
+    const bool need = cand > m_run[nt] + kLazy;
+    m_new = need ? cand : m_run[nt];
+    return need;
+  };
+  auto rescale = [&](int nt, float m_new) {
+    const float alpha = __builtin_amdgcn_exp2f(m_run[nt] - m_new);   // 1 for heads that keep their max
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) zacc[mt][nt][i] *= alpha;
+    l_run[nt] *= alpha;
+    m_run[nt] = m_new;
+  };
+  // decides, for the scores (c0, c1) of one tile, whether any head of this wave must refresh its
+  // running max (returns the wave-wide answer) and leaves the would-be new maxima in mn0 / mn1
+  auto max_decision = [&](const f32x16& c0, const f32x16& c1, float& mn0, float& mn1) {
+    const bool need0 = new_max(0, c0, mn0);
+    const bool need1 = new_max(1, c1, mn1);
+    return __any(need0 || need1) != 0;
+  };
+  auto apply_rescale = [&](float mn0, float mn1) {
+    zacc_fence();
+    rescale(0, mn0);
+    rescale(1, mn1);
+    zacc_fence();
+  };
+  // four elements [4 q4, 4 q4 + 4) of P^T = 2^(s*sc - m) for head tile nt, rounded to bf16 into the
+  // PV B operands; the row sums of the rounded values go to l_run
+  auto probs4 = [&](int nt, int q4, const f32x16& sv, bf16x8 (&pb)[2], bool pin = false) {
+    float neg_m = -m_run[nt];
+    if (pin) asm volatile("" : "+v"(neg_m));   // anchors these vector ops in the caller's slot
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+#pragma unroll
+    for (int r = 4 * q4; r < 4 * q4 + 4; r += 2) {
+      const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[r], sc, neg_m));
+      const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[r + 1], sc, neg_m));
+      const bf16x2 pp = {(__bf16)p0, (__bf16)p1};
+      l_run[nt] = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, l_run[nt], false);
+      pb[r >> 3][r & 7] = pp[0];
+      pb[r >> 3][(r & 7) + 1] = pp[1];
+    }
+  };
+  auto mask_tail = [&](f32x16& sv) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int tok = tw * 32 + (r >> 2) * 8 + g * 4 + (r & 3);
+      if (tok >= nvalid_last) sv[r] = -INFINITY;
+    }
+  };
+  // Z^T += V^T P^T, PV MFMA number e of 16 (consecutive e use different accumulators)
+  auto pv1 = [&](int e, const bf16x8 (&va)[2][4], const bf16x8 (&pb)[2][2]) {
+    const int nt = e & 1, mt = (e >> 1) & 3, ss = e >> 3;
+    mfma_acc(zacc[mt][nt], va[ss][mt], pb[nt][ss]);
+  };
 
-    f32x16 s0, s1;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) { s0[i] = 0.f; s1[i] = 0.f; }
-#pragma unroll
-    for (int ks = 0; ks < 12; ++ks) s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[0][ks], s0, 0, 0, 0);
-#pragma unroll
-    for (int ks = 0; ks < 12; ++ks) s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[1][ks], s1, 0, 0, 0);
+  // ---- three-stage software pipeline over the tiles of the chunk ----
+  //   A(t): raw scores S(t) = K(t) Q^T            matrix pipe, needs tile t in LDS
+  //   B(t): P(t) = 2^(S(t) sc - m), row sums      vector ALU, may first refresh the running max
+  //   C(t): Z^T += V(t)^T P(t)                     matrix pipe, needs tile t in LDS
+  // Step i runs A(i+2), B(i+1) and C(i) interleaved instruction by instruction; loads run STAGES-1
+  // tiles ahead.  S and P are double-buffered by tile parity.
+  f32x16 sbuf[2][2];       // [tile parity][head tile]
+  bf16x8 pbuf[2][2][2];    // [tile parity][head tile][token half]
+  int st_lo = 0;           // LDS stage of tile i (the oldest tile still needed)
 
-    bf16x8 pb0[2], pb1[2];
-    softmax(0, tail, s0, pb0);
+  auto stage_of = [&](int ahead) { int st = st_lo + ahead; return st >= STAGES ? st - STAGES : st; };
+  auto A_plain = [&](int st, f32x16 (&sv)[2]) {
+    bf16x8 ka[12];
+    load_k(st, ka);
 #pragma unroll
-    for (int ss = 0; ss < 2; ++ss)
+    for (int i = 0; i < 16; ++i) { sv[0][i] = 0.f; sv[1][i] = 0.f; }
 #pragma unroll
-      for (int mt = 0; mt < 4; ++mt)
-        zacc[mt][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[ss][mt], pb0[ss], zacc[mt][0], 0, 0, 0);
-    softmax(1, tail, s1, pb1);
+    for (int ks = 0; ks < 12; ++ks) {
+      sv[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[0][ks], sv[0], 0, 0, 0);
+      sv[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[1][ks], sv[1], 0, 0, 0);
+      // The first MFMA of a chain has a constant accumulator input, so its destination is a fresh
+      // register range; keeping ka[0] alive past it stops the allocator from placing that range on
+      // top of the A operand (which the hardware forbids; the build also scans the assembly for it).
+      if (ks == 1) asm volatile("" : : "v"(ka[0]));
+    }
+  };
+  auto B_plain = [&](f32x16 (&sv)[2], bf16x8 (&pb)[2][2]) {
+    float mn0, mn1;
+    if (max_decision(sv[0], sv[1], mn0, mn1)) apply_rescale(mn0, mn1);
 #pragma unroll
-    for (int ss = 0; ss < 2; ++ss)
-#pragma unroll
-      for (int mt = 0; mt < 4; ++mt)
-        zacc[mt][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[ss][mt], pb1[ss], zacc[mt][1], 0, 0, 0);
+    for (int q4 = 0; q4 < 4; ++q4) { probs4(0, q4, sv[0], pb[0]); probs4(1, q4, sv[1], pb[1]); }
+  };
+  // All sixteen Z MFMAs of one tile in a single asm statement that ends with enough wait states for the
+  // last result to be written back: the compiler cannot see that these are MFMAs, so it may place a
+  // register copy of an accumulator directly behind an asm statement.
+  auto pv_all = [&](const bf16x8 (&va)[2][4], const bf16x8 (&pb)[2][2]) {
+    asm volatile(
+        "v_mfma_f32_32x32x16_bf16 %0, %8, %16, %0\n\t"
+        "v_mfma_f32_32x32x16_bf16 %1, %8, %18, %1\n\t"
+        "v_mfma_f32_32x32x16_bf16 %2, %9, %16, %2\n\t"
+        "v_mfma_f32_32x32x16_bf16 %3, %9, %18, %3\n\t"
+        "v_mfma_f32_32x32x16_bf16 %4, %10, %16, %4\n\t"
+        "v_mfma_f32_32x32x16_bf16 %5, %10, %18, %5\n\t"
+        "v_mfma_f32_32x32x16_bf16 %6, %11, %16, %6\n\t"
+        "v_mfma_f32_32x32x16_bf16 %7, %11, %18, %7\n\t"
+        "v_mfma_f32_32x32x16_bf16 %0, %12, %17, %0\n\t"
+        "v_mfma_f32_32x32x16_bf16 %1, %12, %19, %1\n\t"
+        "v_mfma_f32_32x32x16_bf16 %2, %13, %17, %2\n\t"
+        "v_mfma_f32_32x32x16_bf16 %3, %13, %19, %3\n\t"
+        "v_mfma_f32_32x32x16_bf16 %4, %14, %17, %4\n\t"
+        "v_mfma_f32_32x32x16_bf16 %5, %14, %19, %5\n\t"
+        "v_mfma_f32_32x32x16_bf16 %6, %15, %17, %6\n\t"
+        "v_mfma_f32_32x32x16_bf16 %7, %15, %19, %7\n\t"
+        "s_nop 15\n\ts_nop 7"
+        : "+a"(zacc[0][0]), "+a"(zacc[0][1]), "+a"(zacc[1][0]), "+a"(zacc[1][1]), "+a"(zacc[2][0]),
+          "+a"(zacc[2][1]), "+a"(zacc[3][0]), "+a"(zacc[3][1])
+        : "v"(va[0][0]), "v"(va[0][1]), "v"(va[0][2]), "v"(va[0][3]), "v"(va[1][0]), "v"(va[1][1]),
+          "v"(va[1][2]), "v"(va[1][3]), "v"(pb[0][0]), "v"(pb[0][1]), "v"(pb[1][0]), "v"(pb[1][1]));
+  };
+  auto C_plain = [&](int st, const bf16x8 (&pb)[2][2]) {
+    bf16x8 va[2][4];
+    load_v(st, va);
+    pv_all(va, pb);
+  };
+
+  for (int jj = 0; jj < STAGES - 1 && jj < ntiles; ++jj) issue_tile(jj);
+  if (ntiles >= STAGES - 1) wait_vmcnt<kLoadsPerTile * (STAGES - 2)>(); else wait_vmcnt<0>();
+  __builtin_amdgcn_s_barrier();
+  A_plain(0, sbuf[0]);
+  if (ntiles < 2 && nvalid_last < kTile) {
+    mask_tail(sbuf[0][0]);
+    mask_tail(sbuf[0][1]);
   }
+  B_plain(sbuf[0], pbuf[0]);
+  if (ntiles >= 2) {
+    if (ntiles >= STAGES - 1) wait_vmcnt<kLoadsPerTile * (STAGES - 3)>(); else wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();
+    A_plain(1, sbuf[1]);
+  }
+
+  // steady step i (PAR = i & 1): A(i+2) into sbuf[PAR], B(i+1) from sbuf[PAR^1] into pbuf[PAR^1],
+  // C(i) from pbuf[PAR]
+  auto step = [&](auto PAR, int i) {
+    constexpr int par = decltype(PAR)::value;
+    if (i + STAGES - 2 <= ntiles - 1) wait_vmcnt<kLoadsPerTile * (STAGES - 4)>(); else wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();   // tile i+2 landed for every wave; everyone is done with tile i-1
+    bf16x8 ka[12], va[2][4];
+    load_k(stage_of(2), ka);
+    load_v(st_lo, va);
+    __builtin_amdgcn_sched_barrier(0);
+    float mn0, mn1;
+    bool pv_done = false;
+    if (max_decision(sbuf[par ^ 1][0], sbuf[par ^ 1][1], mn0, mn1)) {
+      // rare once the running max has settled: Z must take P(i), computed under the old max, first
+      pv_all(va, pbuf[par]);
+      apply_rescale(mn0, mn1);
+      pv_done = true;
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    auto body = [&](auto WITH_PV) {
+      constexpr bool with_pv = decltype(WITH_PV)::value;
+#pragma unroll
+      for (int i16 = 0; i16 < 16; ++i16) { sbuf[par][0][i16] = 0.f; sbuf[par][1][i16] = 0.f; }
+#pragma unroll
+      for (int ks = 0; ks < 12; ++ks) {
+        // matrix pipe: two score MFMAs of tile i+2 with one or two Z MFMAs of tile i between them
+        // (all Z MFMAs sit in the first eight slots: whatever the compiler places behind this block
+        //  is then at least eight MFMAs away from the last opaque one)
+        sbuf[par][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[0][ks], sbuf[par][0], 0, 0, 0);
+        if (with_pv && ks < 8) pv1(2 * ks, va, pbuf[par]);
+        sbuf[par][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[1][ks], sbuf[par][1], 0, 0, 0);
+        if (with_pv && ks < 8) pv1(2 * ks + 1, va, pbuf[par]);
+        // vector ALU in their shadow: four probabilities of tile i+1
+        if (ks < 8) probs4(ks >> 2, ks & 3, sbuf[par ^ 1][ks >> 2], pbuf[par ^ 1][ks >> 2], true);
+        if (ks == 1) asm volatile("" : : "v"(ka[0]));   // see A_plain: no destination on top of ka[0]
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    };
+    if (pv_done) body(std::false_type{}); else body(std::true_type{});
+    if (i + STAGES - 1 < ntiles) issue_tile(i + STAGES - 1);
+    __builtin_amdgcn_sched_barrier(0);
+    st_lo = stage_of(1);
+  };
+  int i = 0;
+  for (; i + 3 < ntiles; i += 2) {
+    step(std::integral_constant<int, 0>{}, i);
+    step(std::integral_constant<int, 1>{}, i + 1);
+  }
+  if (i + 2 < ntiles) {          // one more steady step; then renumber the buffers so that parity 0 = tile i
+    step(std::integral_constant<int, 0>{}, i);
+    ++i;
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) {
+      const f32x16 ts = sbuf[0][nt]; sbuf[0][nt] = sbuf[1][nt]; sbuf[1][nt] = ts;
+#pragma unroll
+      for (int ss = 0; ss < 2; ++ss) {
+        const bf16x8 tp = pbuf[0][nt][ss]; pbuf[0][nt][ss] = pbuf[1][nt][ss]; pbuf[1][nt][ss] = tp;
+      }
+    }
+  }
+  // drain: here i = max(ntiles - 2, 0); P(i) is in pbuf[0]; S(i+1), if that tile exists, is in sbuf[1]
+  if (ntiles >= 2) {
+    if (nvalid_last < kTile) { mask_tail(sbuf[1][0]); mask_tail(sbuf[1][1]); }
+    C_plain(st_lo, pbuf[0]);
+    B_plain(sbuf[1], pbuf[1]);
+    C_plain(stage_of(1), pbuf[1]);
+  } else {
+    C_plain(st_lo, pbuf[0]);
+  }
+  zacc_fence();
 
   // ---- merge the two token halves of each head half through LDS, write the chunk's partial ----
 #pragma unroll
@@ -351,7 +547,7 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
   }
 }
 
-constexpr int kStages = 4;
+constexpr int kStages = 6;
 
 }  // namespace
 
