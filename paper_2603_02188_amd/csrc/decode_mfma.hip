@@ -11,8 +11,6 @@
 //     Z^T += V^T P^T (channels x heads); V^T comes from the row-major tile through LDS transpose reads.
 //   * Running max is updated lazily (only when it grows by more than 2^8), which is exact: the
 //     partial (m, l, z) stays self-consistent and the merge kernel normalises.
-#include <type_traits>
-
 #include "mlra_internal.h"
 
 namespace mlra {
@@ -72,13 +70,6 @@ __device__ __forceinline__ void lds_dma16(const void* sbase, unsigned voff) {
 
 __device__ __forceinline__ short4v lds_tr16(const void* p) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3)))*)p);
-}
-
-// Z accumulation MFMA with the accumulator held in accumulation registers (the rest of the kernel is
-// compiled with MFMA results in architectural VGPRs).  The compiler does not know this is an MFMA, so
-// before any non-MFMA instruction reads or writes these accumulators the code passes zacc_fence().
-__device__ __forceinline__ void mfma_acc(f32x16& acc, const bf16x8& a, const bf16x8& b) {
-  asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
 }
 
 template <int STAGES>
@@ -210,17 +201,9 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
 #pragma unroll
   for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt) {
+    for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
       for (int i = 0; i < 16; ++i) zacc[mt][nt][i] = 0.f;
-      asm volatile("" : "+a"(zacc[mt][nt]));
-    }
-  // waits out any in-flight Z MFMA before ordinary instructions touch the accumulators (and after they did)
-  auto zacc_fence = [&]() {
-    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 7"
-                 : "+a"(zacc[0][0]), "+a"(zacc[0][1]), "+a"(zacc[1][0]), "+a"(zacc[1][1]), "+a"(zacc[2][0]),
-                   "+a"(zacc[2][1]), "+a"(zacc[3][0]), "+a"(zacc[3][1]));
-  };
 
   const float sc = p.scale_log2;
 
@@ -241,16 +224,6 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
         const short4v hi = lds_tr16(base + v_off[ss][mt] + 8 * (kDcb * 2));
         va[ss][mt] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
       }
-  };
-  // raw scores S^T = K Q^T of this wave's 32 token rows against its 64 heads
-  auto scores = [&](const bf16x8 (&ka)[12], f32x16& sa, f32x16& sb) {
-#pragma unroll
-    for (int i = 0; i < 16; ++i) { sa[i] = 0.f; sb[i] = 0.f; }
-#pragma unroll
-    for (int ks = 0; ks < 12; ++ks) {
-      sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[0][ks], sa, 0, 0, 0);
-      sb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[1][ks], sb, 0, 0, 0);
-    }
   };
   // running-max bookkeeping of head tile nt for raw scores s (accumulator layout: this lane owns head
   // column c32 and 16 of the 32 tokens); returns true if this lane's head needs a rescale
@@ -273,27 +246,13 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
     l_run[nt] *= alpha;
     m_run[nt] = m_new;
   };
-  // decides, for the scores (c0, c1) of one tile, whether any head of this wave must refresh its
-  // running max (returns the wave-wide answer) and leaves the would-be new maxima in mn0 / mn1
-  auto max_decision = [&](const f32x16& c0, const f32x16& c1, float& mn0, float& mn1) {
-    const bool need0 = new_max(0, c0, mn0);
-    const bool need1 = new_max(1, c1, mn1);
-    return __any(need0 || need1) != 0;
-  };
-  auto apply_rescale = [&](float mn0, float mn1) {
-    zacc_fence();
-    rescale(0, mn0);
-    rescale(1, mn1);
-    zacc_fence();
-  };
-  // four elements [4 q4, 4 q4 + 4) of P^T = 2^(s*sc - m) for head tile nt, rounded to bf16 into the
-  // PV B operands; the row sums of the rounded values go to l_run
-  auto probs4 = [&](int nt, int q4, const f32x16& sv, bf16x8 (&pb)[2], bool pin = false) {
-    float neg_m = -m_run[nt];
-    if (pin) asm volatile("" : "+v"(neg_m));   // anchors these vector ops in the caller's slot
+  // P^T = 2^(s*sc - m) for head tile nt, rounded to bf16 into the two PV B operands; the row sums of
+  // the rounded values go to l_run
+  auto probs = [&](int nt, const f32x16& sv, bf16x8 (&pb)[2]) {
+    const float neg_m = -m_run[nt];
     const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
-    for (int r = 4 * q4; r < 4 * q4 + 4; r += 2) {
+    for (int r = 0; r < 16; r += 2) {
       const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[r], sc, neg_m));
       const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[r + 1], sc, neg_m));
       const bf16x2 pp = {(__bf16)p0, (__bf16)p1};
@@ -309,162 +268,55 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
       if (tok >= nvalid_last) sv[r] = -INFINITY;
     }
   };
-  // Z^T += V^T P^T, PV MFMA number e of 16 (consecutive e use different accumulators)
-  auto pv1 = [&](int e, const bf16x8 (&va)[2][4], const bf16x8 (&pb)[2][2]) {
-    const int nt = e & 1, mt = (e >> 1) & 3, ss = e >> 3;
-    mfma_acc(zacc[mt][nt], va[ss][mt], pb[nt][ss]);
-  };
 
-  // ---- three-stage software pipeline over the tiles of the chunk ----
-  //   A(t): raw scores S(t) = K(t) Q^T            matrix pipe, needs tile t in LDS
-  //   B(t): P(t) = 2^(S(t) sc - m), row sums      vector ALU, may first refresh the running max
-  //   C(t): Z^T += V(t)^T P(t)                     matrix pipe, needs tile t in LDS
-  // Step i runs A(i+2), B(i+1) and C(i) interleaved instruction by instruction; loads run STAGES-1
-  // tiles ahead.  S and P are double-buffered by tile parity.
-  f32x16 sbuf[2][2];       // [tile parity][head tile]
-  bf16x8 pbuf[2][2][2];    // [tile parity][head tile][token half]
-  int st_lo = 0;           // LDS stage of tile i (the oldest tile still needed)
+  // ---- main loop: loads run STAGES-1 tiles ahead of the tile being consumed.  Per tile: scores
+  //      (matrix pipe), running max, then probabilities of one head tile on the vector ALU while the
+  //      matrix pipe accumulates Z for the other ----
+  for (int jj = 0; jj < STAGES - 1 && jj < ntiles; ++jj) issue_tile(jj);
+  int st_cur = 0;
 
-  auto stage_of = [&](int ahead) { int st = st_lo + ahead; return st >= STAGES ? st - STAGES : st; };
-  auto A_plain = [&](int st, f32x16 (&sv)[2]) {
-    bf16x8 ka[12];
-    load_k(st, ka);
+  for (int j = 0; j < ntiles; ++j) {
+    if (j + STAGES - 2 <= ntiles - 1) wait_vmcnt<kLoadsPerTile * (STAGES - 2)>(); else wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();   // tile j landed for every wave; everyone is done with tile j-1
+    if (j + STAGES - 1 < ntiles) issue_tile(j + STAGES - 1);
+
+    bf16x8 ka[12], va[2][4];
+    load_k(st_cur, ka);
+    load_v(st_cur, va);
+
+    f32x16 s0, s1;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) { sv[0][i] = 0.f; sv[1][i] = 0.f; }
+    for (int i = 0; i < 16; ++i) { s0[i] = 0.f; s1[i] = 0.f; }
 #pragma unroll
     for (int ks = 0; ks < 12; ++ks) {
-      sv[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[0][ks], sv[0], 0, 0, 0);
-      sv[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[1][ks], sv[1], 0, 0, 0);
-      // The first MFMA of a chain has a constant accumulator input, so its destination is a fresh
-      // register range; keeping ka[0] alive past it stops the allocator from placing that range on
-      // top of the A operand (which the hardware forbids; the build also scans the assembly for it).
+      s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[0][ks], s0, 0, 0, 0);
+      s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[1][ks], s1, 0, 0, 0);
+      // keeps ka[0] alive past the two MFMAs whose accumulator input is the constant 0, so that the
+      // allocator cannot place their destination on top of it (the build also scans for that)
       if (ks == 1) asm volatile("" : : "v"(ka[0]));
     }
-  };
-  auto B_plain = [&](f32x16 (&sv)[2], bf16x8 (&pb)[2][2]) {
-    float mn0, mn1;
-    if (max_decision(sv[0], sv[1], mn0, mn1)) apply_rescale(mn0, mn1);
-#pragma unroll
-    for (int q4 = 0; q4 < 4; ++q4) { probs4(0, q4, sv[0], pb[0]); probs4(1, q4, sv[1], pb[1]); }
-  };
-  // All sixteen Z MFMAs of one tile in a single asm statement that ends with enough wait states for the
-  // last result to be written back: the compiler cannot see that these are MFMAs, so it may place a
-  // register copy of an accumulator directly behind an asm statement.
-  auto pv_all = [&](const bf16x8 (&va)[2][4], const bf16x8 (&pb)[2][2]) {
-    asm volatile(
-        "v_mfma_f32_32x32x16_bf16 %0, %8, %16, %0\n\t"
-        "v_mfma_f32_32x32x16_bf16 %1, %8, %18, %1\n\t"
-        "v_mfma_f32_32x32x16_bf16 %2, %9, %16, %2\n\t"
-        "v_mfma_f32_32x32x16_bf16 %3, %9, %18, %3\n\t"
-        "v_mfma_f32_32x32x16_bf16 %4, %10, %16, %4\n\t"
-        "v_mfma_f32_32x32x16_bf16 %5, %10, %18, %5\n\t"
-        "v_mfma_f32_32x32x16_bf16 %6, %11, %16, %6\n\t"
-        "v_mfma_f32_32x32x16_bf16 %7, %11, %18, %7\n\t"
-        "v_mfma_f32_32x32x16_bf16 %0, %12, %17, %0\n\t"
-        "v_mfma_f32_32x32x16_bf16 %1, %12, %19, %1\n\t"
-        "v_mfma_f32_32x32x16_bf16 %2, %13, %17, %2\n\t"
-        "v_mfma_f32_32x32x16_bf16 %3, %13, %19, %3\n\t"
-        "v_mfma_f32_32x32x16_bf16 %4, %14, %17, %4\n\t"
-        "v_mfma_f32_32x32x16_bf16 %5, %14, %19, %5\n\t"
-        "v_mfma_f32_32x32x16_bf16 %6, %15, %17, %6\n\t"
-        "v_mfma_f32_32x32x16_bf16 %7, %15, %19, %7\n\t"
-        "s_nop 15\n\ts_nop 7"
-        : "+a"(zacc[0][0]), "+a"(zacc[0][1]), "+a"(zacc[1][0]), "+a"(zacc[1][1]), "+a"(zacc[2][0]),
-          "+a"(zacc[2][1]), "+a"(zacc[3][0]), "+a"(zacc[3][1])
-        : "v"(va[0][0]), "v"(va[0][1]), "v"(va[0][2]), "v"(va[0][3]), "v"(va[1][0]), "v"(va[1][1]),
-          "v"(va[1][2]), "v"(va[1][3]), "v"(pb[0][0]), "v"(pb[0][1]), "v"(pb[1][0]), "v"(pb[1][1]));
-  };
-  auto C_plain = [&](int st, const bf16x8 (&pb)[2][2]) {
-    bf16x8 va[2][4];
-    load_v(st, va);
-    pv_all(va, pb);
-  };
+    if (j == ntiles - 1 && nvalid_last < kTile) { mask_tail(s0); mask_tail(s1); }
 
-  for (int jj = 0; jj < STAGES - 1 && jj < ntiles; ++jj) issue_tile(jj);
-  if (ntiles >= STAGES - 1) wait_vmcnt<kLoadsPerTile * (STAGES - 2)>(); else wait_vmcnt<0>();
-  __builtin_amdgcn_s_barrier();
-  A_plain(0, sbuf[0]);
-  if (ntiles < 2 && nvalid_last < kTile) {
-    mask_tail(sbuf[0][0]);
-    mask_tail(sbuf[0][1]);
-  }
-  B_plain(sbuf[0], pbuf[0]);
-  if (ntiles >= 2) {
-    if (ntiles >= STAGES - 1) wait_vmcnt<kLoadsPerTile * (STAGES - 3)>(); else wait_vmcnt<0>();
-    __builtin_amdgcn_s_barrier();
-    A_plain(1, sbuf[1]);
-  }
-
-  // steady step i (PAR = i & 1): A(i+2) into sbuf[PAR], B(i+1) from sbuf[PAR^1] into pbuf[PAR^1],
-  // C(i) from pbuf[PAR]
-  auto step = [&](auto PAR, int i) {
-    constexpr int par = decltype(PAR)::value;
-    if (i + STAGES - 2 <= ntiles - 1) wait_vmcnt<kLoadsPerTile * (STAGES - 4)>(); else wait_vmcnt<0>();
-    __builtin_amdgcn_s_barrier();   // tile i+2 landed for every wave; everyone is done with tile i-1
-    bf16x8 ka[12], va[2][4];
-    load_k(stage_of(2), ka);
-    load_v(st_lo, va);
-    __builtin_amdgcn_sched_barrier(0);
     float mn0, mn1;
-    bool pv_done = false;
-    if (max_decision(sbuf[par ^ 1][0], sbuf[par ^ 1][1], mn0, mn1)) {
-      // rare once the running max has settled: Z must take P(i), computed under the old max, first
-      pv_all(va, pbuf[par]);
-      apply_rescale(mn0, mn1);
-      pv_done = true;
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    auto body = [&](auto WITH_PV) {
-      constexpr bool with_pv = decltype(WITH_PV)::value;
+    const bool need0 = new_max(0, s0, mn0);
+    const bool need1 = new_max(1, s1, mn1);
+    if (__any(need0 || need1)) { rescale(0, mn0); rescale(1, mn1); }
+
+    bf16x8 pb0[2], pb1[2];
+    probs(0, s0, pb0);
 #pragma unroll
-      for (int i16 = 0; i16 < 16; ++i16) { sbuf[par][0][i16] = 0.f; sbuf[par][1][i16] = 0.f; }
+    for (int ss = 0; ss < 2; ++ss)
 #pragma unroll
-      for (int ks = 0; ks < 12; ++ks) {
-        // matrix pipe: two score MFMAs of tile i+2 with one or two Z MFMAs of tile i between them
-        // (all Z MFMAs sit in the first eight slots: whatever the compiler places behind this block
-        //  is then at least eight MFMAs away from the last opaque one)
-        sbuf[par][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[0][ks], sbuf[par][0], 0, 0, 0);
-        if (with_pv && ks < 8) pv1(2 * ks, va, pbuf[par]);
-        sbuf[par][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[1][ks], sbuf[par][1], 0, 0, 0);
-        if (with_pv && ks < 8) pv1(2 * ks + 1, va, pbuf[par]);
-        // vector ALU in their shadow: four probabilities of tile i+1
-        if (ks < 8) probs4(ks >> 2, ks & 3, sbuf[par ^ 1][ks >> 2], pbuf[par ^ 1][ks >> 2], true);
-        if (ks == 1) asm volatile("" : : "v"(ka[0]));   // see A_plain: no destination on top of ka[0]
-        __builtin_amdgcn_sched_barrier(0);
-      }
-    };
-    if (pv_done) body(std::false_type{}); else body(std::true_type{});
-    if (i + STAGES - 1 < ntiles) issue_tile(i + STAGES - 1);
-    __builtin_amdgcn_sched_barrier(0);
-    st_lo = stage_of(1);
-  };
-  int i = 0;
-  for (; i + 3 < ntiles; i += 2) {
-    step(std::integral_constant<int, 0>{}, i);
-    step(std::integral_constant<int, 1>{}, i + 1);
+      for (int mt = 0; mt < 4; ++mt)
+        zacc[mt][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[ss][mt], pb0[ss], zacc[mt][0], 0, 0, 0);
+    probs(1, s1, pb1);
+#pragma unroll
+    for (int ss = 0; ss < 2; ++ss)
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt)
+        zacc[mt][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[ss][mt], pb1[ss], zacc[mt][1], 0, 0, 0);
+    st_cur = (st_cur + 1 == STAGES) ? 0 : st_cur + 1;
   }
-  if (i + 2 < ntiles) {          // one more steady step; then renumber the buffers so that parity 0 = tile i
-    step(std::integral_constant<int, 0>{}, i);
-    ++i;
-#pragma unroll
-    for (int nt = 0; nt < 2; ++nt) {
-      const f32x16 ts = sbuf[0][nt]; sbuf[0][nt] = sbuf[1][nt]; sbuf[1][nt] = ts;
-#pragma unroll
-      for (int ss = 0; ss < 2; ++ss) {
-        const bf16x8 tp = pbuf[0][nt][ss]; pbuf[0][nt][ss] = pbuf[1][nt][ss]; pbuf[1][nt][ss] = tp;
-      }
-    }
-  }
-  // drain: here i = max(ntiles - 2, 0); P(i) is in pbuf[0]; S(i+1), if that tile exists, is in sbuf[1]
-  if (ntiles >= 2) {
-    if (nvalid_last < kTile) { mask_tail(sbuf[1][0]); mask_tail(sbuf[1][1]); }
-    C_plain(st_lo, pbuf[0]);
-    B_plain(sbuf[1], pbuf[1]);
-    C_plain(stage_of(1), pbuf[1]);
-  } else {
-    C_plain(st_lo, pbuf[0]);
-  }
-  zacc_fence();
 
   // ---- merge the two token halves of each head half through LDS, write the chunk's partial ----
 #pragma unroll
@@ -547,7 +399,7 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
   }
 }
 
-constexpr int kStages = 6;
+constexpr int kStages = 5;
 
 }  // namespace
 
