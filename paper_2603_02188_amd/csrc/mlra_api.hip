@@ -101,7 +101,7 @@ static int decode_common(const mlra_cache* c, int batch, int h, int d_h, const v
   int st = decode_mfma_supported(a) ? launch_decode_mfma(a) : launch_decode_generic(a);
   if (st != MLRA_OK) return st;
   timing_mark(1, a.stream);
-  st = launch_merge_upproj_generic(a);
+  st = merge_upproj_mfma_supported(a) ? launch_merge_upproj_mfma(a) : launch_merge_upproj_generic(a);
   timing_mark(2, a.stream);
   if (g_timing_calls < g_timing_cap) ++g_timing_calls;
   return st;
@@ -142,6 +142,8 @@ int mlra_absorb_q(int32_t batch, int32_t h, int32_t d_h, int32_t n_blocks, int32
   if (!valid_dtype(dtype)) return MLRA_ERR_DTYPE;
   if (batch <= 0 || h <= 0 || d_h <= 0 || n_blocks <= 0 || d_cb <= 0) return MLRA_ERR_SHAPE;
   if (h > 65535 || batch > 65535 || n_blocks > 65535 || d_h > 8192) return MLRA_ERR_SHAPE;
+  if (absorb_q_mfma_supported(d_h, d_cb, dtype))
+    return launch_absorb_q_mfma(batch, h, d_h, n_blocks, d_cb, q_nope, w_uk, q_abs, (hipStream_t)stream);
   return launch_absorb_q_generic(batch, h, d_h, n_blocks, d_cb, q_nope, w_uk, q_abs, dtype, (hipStream_t)stream);
 }
 

@@ -67,9 +67,14 @@ int launch_absorb_q_generic(int batch, int h, int d_h, int n_blocks, int d_cb, c
 int launch_decode_generic(const DecodeArgs& a);
 int launch_merge_upproj_generic(const DecodeArgs& a);
 
-// Fast path (bf16, MFMA); returns false when the shape is outside what it was written for.
+// Fast paths (bf16, MFMA); the *_supported predicates are false outside the shapes they were written for.
 bool decode_mfma_supported(const DecodeArgs& a);
 int launch_decode_mfma(const DecodeArgs& a);
+bool absorb_q_mfma_supported(int d_h, int d_cb, int dtype);
+int launch_absorb_q_mfma(int batch, int h, int d_h, int n_blocks, int d_cb, const void* q_nope, const void* w_uk,
+                         void* q_abs, hipStream_t stream);
+bool merge_upproj_mfma_supported(const DecodeArgs& a);
+int launch_merge_upproj_mfma(const DecodeArgs& a);
 
 struct GqaArgs {
   const void* k_pool;

@@ -1,0 +1,218 @@
+// MFMA kernels for the two per-head projections around the decode kernel (bf16, d_h = 128):
+//   * absorb_q:  q~_b[i] = W^UK_(b),(i) q_i                (Step 1, Section 2.1, per block)
+//   * merge + up-projection + block sum:  out[i] = out_scale * sum_b z_b[i] W^UV_(b),(i)
+//     (log-sum-exp merge of the context chunks, then Step 3 and the block sum of Eq. (5) as one
+//      contraction over all n_blocks * d_cb latent channels)
+// Both are batched over sequences as the MFMA M dimension so that each weight element is read once
+// per workgroup, and both put the head index on the grid.
+#include "mlra_internal.h"
+
+namespace mlra {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(4))) short short4v;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+constexpr int kDh = 128;
+constexpr float kNegBig = -1.0e30f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+__device__ __forceinline__ int swz(int t) { return ((t & 3) << 1) | ((t >> 2) & 1); }
+
+// Zero that the compiler cannot fold: an accumulator initialised from it is a real register operand, so
+// every MFMA is emitted in the tied form (destination = accumulator input) and its destination can
+// never be placed on top of its A / B operands.
+__device__ __forceinline__ f32x16 opaque_zero() {
+  float z = 0.f;
+  asm volatile("" : "+v"(z));
+  f32x16 acc;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) acc[i] = z;
+  return acc;
+}
+
+__device__ __forceinline__ short4v lds_tr16(const void* p) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3)))*)p);
+}
+
+// ------------------------------------------------------------------------------------------------
+// absorb_q.  One workgroup per (head, block); wave w produces channel tiles ct = w, w+4, ... of 32
+// channels.  S^T-free formulation: out[seq][c] = sum_p q[seq][p] W[c][p], so the A operand (rows =
+// sequences) and the B operand (columns = channels) are both contiguous 16-byte global loads.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void absorb_q_mfma_kernel(const bf16_t* __restrict__ q_nope,
+                                                            const bf16_t* __restrict__ w_uk,
+                                                            bf16_t* __restrict__ q_abs, int batch, int h,
+                                                            int n_blocks, int d_cb) {
+  const int head = blockIdx.x, b = blockIdx.y;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, g = lane >> 5, c32 = lane & 31;
+  const size_t ldw = (size_t)h * kDh;
+  for (int ct = wave; ct * 32 < d_cb; ct += 4) {
+    const int c = ct * 32 + c32;
+    const bf16_t* wrow = w_uk + ((size_t)b * d_cb + c) * ldw + (size_t)head * kDh + g * 8;
+    bf16x8 breg[8];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) breg[ks] = *(const bf16x8*)(wrow + ks * 16);
+    for (int m0 = 0; m0 < batch; m0 += 32) {
+      const int seq = min(m0 + c32, batch - 1);
+      const bf16_t* qrow = q_nope + ((size_t)seq * h + head) * kDh + g * 8;
+      f32x16 acc = opaque_zero();
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        const bf16x8 a = *(const bf16x8*)(qrow + ks * 16);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, breg[ks], acc, 0, 0, 0);
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int s = m0 + (r >> 2) * 8 + g * 4 + (r & 3);
+        if (s < batch) q_abs[(((size_t)s * n_blocks + b) * h + head) * d_cb + c] = f32_to_bf16(acc[r]);
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// merge + up-projection.  One workgroup per (head, tile of 32 sequences).
+//   phase 1: the merged, normalised z of the 32 sequences for all R = n_blocks*d_cb latent channels,
+//            rounded to bf16, is built in LDS (row = sequence);
+//   phase 2: out[seq][j] = sum_r z[seq][r] W^UV[r][head*128 + j]; W^UV streams through LDS in chunks
+//            of 32 rows and reaches the MFMA B operand through transpose reads; wave w owns output
+//            columns [32 w, 32 w + 32).
+// ------------------------------------------------------------------------------------------------
+template <typename TO>
+__global__ __launch_bounds__(256) void merge_upproj_mfma_kernel(
+    const float* __restrict__ part_z, const float* __restrict__ part_ml, const int32_t* __restrict__ seq_lens,
+    const bf16_t* __restrict__ w_uv, TO* __restrict__ out, float* __restrict__ lse, int batch, int h, int n_blocks,
+    int d_cb, int n_splits, int chunk, float out_scale) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  const int R = n_blocks * d_cb;
+  const int zpitch = R + 8;                               // bf16 elements per z row (+16 B against conflicts)
+  bf16_t* zt = (bf16_t*)smem;                             // [32][zpitch]
+  unsigned char* wt = smem + (size_t)32 * zpitch * 2;     // [32 rows][256 B], 16-byte chunks swizzled
+  const int head = blockIdx.x, m0 = blockIdx.y * 32;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, c32 = lane & 31;
+
+  // ---- phase 1 ----
+  const int items_per_row = R / 8;
+  for (int item = tid; item < 32 * items_per_row; item += 256) {
+    const int sl = item / items_per_row, r0 = (item % items_per_row) * 8;
+    const int seq = m0 + sl;
+    float z[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (seq < batch) {
+      const int b = r0 / d_cb, c0 = r0 % d_cb;
+      const int n = seq_lens[seq];
+      const int active = min(n_splits, (n + chunk - 1) / chunk);
+      const size_t unit0 = ((size_t)seq * n_blocks + b) * n_splits;
+      float m_star = kNegBig;
+      for (int k = 0; k < active; ++k) m_star = fmaxf(m_star, part_ml[((unit0 + k) * h + head) * 2]);
+      float L = 0.f;
+      for (int k = 0; k < active; ++k) {
+        const float* ml = part_ml + ((unit0 + k) * h + head) * 2;
+        const float w = exp2f(ml[0] - m_star);
+        L += w * ml[1];
+        const f32x4* pz = (const f32x4*)(part_z + ((unit0 + k) * h + head) * d_cb + c0);
+        const f32x4 lo = pz[0], hi = pz[1];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { z[e] += w * lo[e]; z[4 + e] += w * hi[e]; }
+      }
+      const float inv = L > 0.f ? 1.f / L : 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) z[e] *= inv;
+      if (c0 == 0 && lse) lse[((size_t)seq * n_blocks + b) * h + head] = L > 0.f ? (m_star + log2f(L)) * kLn2 : -INFINITY;
+    }
+    bf16x8 packed;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) packed[e] = (__bf16)z[e];
+    *(bf16x8*)(zt + sl * zpitch + r0) = packed;
+  }
+
+  // ---- phase 2 ----
+  f32x16 acc = opaque_zero();
+  const size_t ldw = (size_t)h * kDh;
+  // transpose-read offsets: the 16 lanes of a block fetch 4 consecutive rows x 16 output columns
+  unsigned tr_off[2][2];
+  {
+    const int k = (lane & 15) >> 2, seg = lane & 3, hb = (lane >> 4) & 1;
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+      for (int half = 0; half < 2; ++half) {
+        const int row = 16 * ks + 8 * g + 4 * half + k;
+        const int cc = 4 * wave + 2 * hb + (seg >> 1);
+        tr_off[ks][half] = row * 256 + ((cc ^ swz(row & 7)) << 4) + ((seg & 1) << 3);
+      }
+  }
+  for (int kc = 0; kc < R; kc += 32) {
+    __syncthreads();   // phase 1 done / previous chunk consumed
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int ch = tid + i * 256;           // 512 chunks of 16 bytes: row = ch / 16, chunk = ch % 16
+      const int row = ch >> 4, cc = ch & 15;
+      const bf16x8 v = *(const bf16x8*)(w_uv + (size_t)(kc + row) * ldw + (size_t)head * kDh + cc * 8);
+      *(bf16x8*)(wt + row * 256 + ((cc ^ swz(row & 7)) << 4)) = v;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      const bf16x8 a = *(const bf16x8*)(zt + c32 * zpitch + kc + ks * 16 + g * 8);
+      const short4v lo = lds_tr16(wt + tr_off[ks][0]);
+      const short4v hi = lds_tr16(wt + tr_off[ks][1]);
+      const bf16x8 bm = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bm, acc, 0, 0, 0);
+    }
+  }
+  const int j = wave * 32 + c32;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const int s = m0 + (r >> 2) * 8 + g * 4 + (r & 3);
+    if (s < batch) store_f32(out, ((size_t)s * h + head) * kDh + j, acc[r] * out_scale);
+  }
+}
+
+}  // namespace
+
+bool absorb_q_mfma_supported(int d_h, int d_cb, int dtype) {
+  return dtype == MLRA_BF16 && d_h == kDh && d_cb % 32 == 0;
+}
+
+int launch_absorb_q_mfma(int batch, int h, int d_h, int n_blocks, int d_cb, const void* q_nope, const void* w_uk,
+                         void* q_abs, hipStream_t stream) {
+  (void)d_h;
+  dim3 grid(h, n_blocks);
+  absorb_q_mfma_kernel<<<grid, 256, 0, stream>>>((const bf16_t*)q_nope, (const bf16_t*)w_uk, (bf16_t*)q_abs, batch, h,
+                                                 n_blocks, d_cb);
+  return check_launch();
+}
+
+bool merge_upproj_mfma_supported(const DecodeArgs& a) {
+  return a.dtype == MLRA_BF16 && a.d_h == kDh && a.d_cb % 32 == 0 && a.n_blocks * a.d_cb <= 1024;
+}
+
+int launch_merge_upproj_mfma(const DecodeArgs& a) {
+  const int R = a.n_blocks * a.d_cb;
+  const size_t lds = (size_t)32 * (R + 8) * 2 + 32 * 256;
+  static bool configured = false;
+  if (!configured) {
+    if (hipFuncSetAttribute((const void*)merge_upproj_mfma_kernel<bf16_t>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            96 * 1024) != hipSuccess ||
+        hipFuncSetAttribute((const void*)merge_upproj_mfma_kernel<float>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            96 * 1024) != hipSuccess)
+      return MLRA_ERR_LAUNCH;
+    configured = true;
+  }
+  dim3 grid(a.h, (a.batch + 31) / 32);
+  if (a.out_dtype == MLRA_BF16)
+    merge_upproj_mfma_kernel<bf16_t><<<grid, 256, lds, a.stream>>>(
+        a.part_z, a.part_ml, a.seq_lens, (const bf16_t*)a.w_uv, (bf16_t*)a.out, a.lse, a.batch, a.h, a.n_blocks, a.d_cb,
+        a.plan.n_splits, a.plan.chunk_tokens, a.out_scale);
+  else
+    merge_upproj_mfma_kernel<float><<<grid, 256, lds, a.stream>>>(
+        a.part_z, a.part_ml, a.seq_lens, (const bf16_t*)a.w_uv, (float*)a.out, a.lse, a.batch, a.h, a.n_blocks, a.d_cb,
+        a.plan.n_splits, a.plan.chunk_tokens, a.out_scale);
+  return check_launch();
+}
+
+}  // namespace mlra
