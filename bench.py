@@ -30,6 +30,8 @@ def _args():
     ap.add_argument("--copies", type=int, default=0, help="cache copies to rotate over (0 = enough for ~3 GB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--parity", action="store_true", help="also compare the GPU output with the oracle")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run plain 1 GiB device copies (reference dispatches for rocprofv3 byte counters)")
     return ap.parse_args()
 
 
@@ -115,6 +117,15 @@ def main():
 
     def decode_only(i):
         mlra.mlra_decode_attn(caches[i % copies], q_abs, q_rope, w_uv, wl.tau, 1.0, out=out, workspace=ws)
+
+    if a.copy_calibration:
+        # a plain copy of known size: 2^30 bytes read, 2^30 bytes written per dispatch
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for i in range(a.warmup):
         step(i)

@@ -41,14 +41,18 @@ struct MfmaParams {
   const bf16_t* q_rope;
   float* part_z;
   float* part_ml;
-  int page_size, max_pages, n_blocks, h, n_splits, chunk;
+  int page_size, max_pages, n_blocks, h, n_splits, chunk, batch;
   float scale_log2;
 };
 
-// 16-byte chunk c of token row t is stored at chunk position c ^ swz(t & 7) of its row: eight
-// consecutive tokens spread one logical chunk over all 32 banks (128-bit score reads), and four
-// consecutive tokens spread a pair of chunks over all banks (64-bit transpose reads).
-__device__ __forceinline__ int swz(int t) { return ((t & 3) << 1) | ((t >> 2) & 1); }
+// LDS has 64 four-byte banks; a 128-bit read is served 16 lanes at a time and a 64-bit transpose read
+// 32 lanes at a time.  16-byte chunk c of latent token row t (256 bytes = one sweep of the banks) is
+// stored at chunk position c ^ lat_swz(t): sixteen consecutive tokens put one logical chunk on sixteen
+// different bank groups (score reads), and four consecutive tokens put a run of four chunks on four
+// different quarters of the banks (transpose reads).  RoPE rows are 128 bytes, so two rows make one
+// sweep and the row pair index is what permutes the eight chunks.
+__device__ __forceinline__ int lat_swz(int t) { return ((t & 3) << 2) | ((t >> 2) & 3); }
+__device__ __forceinline__ int rope_swz(int t) { return (t >> 1) & 7; }
 
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
@@ -75,10 +79,26 @@ __device__ __forceinline__ short4v lds_tr16(const void* p) {
 template <int STAGES>
 __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
-  const int split = blockIdx.x;
+  // Workgroup -> (sequence, chunk, block, head group).  The workgroups of one (sequence, chunk) read the
+  // same RoPE rows (and, across head groups, the same latent rows).  Workgroup ids go round-robin over
+  // the 8 XCDs, each with its own L2, so the members of such a family are given ids 8 apart: they land
+  // on one XCD at about the same time and all but the first read of a shared row hit in that L2.
   const int n_hg = (p.h + kHeadsWG - 1) / kHeadsWG;
-  const int blk = blockIdx.y / n_hg, hgrp = blockIdx.y % n_hg;
-  const int seq = blockIdx.z;
+  const int fam = p.n_blocks * n_hg;
+  const int n_units = p.n_splits * p.batch;
+  const int full_units = n_units & ~7;
+  int wg = blockIdx.x, su, member;
+  if (wg < full_units * fam) {
+    const int r = wg >> 3;
+    member = r % fam;
+    su = (r / fam) * 8 + (wg & 7);
+  } else {
+    wg -= full_units * fam;
+    su = full_units + wg / fam;
+    member = wg % fam;
+  }
+  const int split = su % p.n_splits, seq = su / p.n_splits;
+  const int blk = member / n_hg, hgrp = member % n_hg;
   const int n = p.seq_lens[seq];
   const int t0 = split * p.chunk;
   if (t0 >= n) return;
@@ -107,24 +127,26 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
 #pragma unroll
     for (int ks = 0; ks < 12; ++ks) asm volatile("" : "+a"(qreg[nt][ks]));
 
-  // ---- page ids of up to 64 tiles ahead, one per lane ----
-  const int32_t* pt_row = p.page_table + (size_t)seq * p.max_pages;
-  auto load_page_ids = [&](int tile_base) {
-    const int idx = min((t0 + (tile_base + lane) * kTile) / p.page_size, p.max_pages - 1);
-    return pt_row[idx];
-  };
-  int pid_vec = load_page_ids(0);
-  int pid_next = 0;
+  // ---- page ids: scalar loads through the constant address space (the table is read-only here), so
+  // that the compiler's vector-memory wait counts never see a load inside the main loop: a wait for one
+  // would also drain every direct-to-LDS load in flight.  The id of the next tile's page is fetched one
+  // tile ahead of its use.
+  typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
+  const const_i32_ptr pt_row = (const_i32_ptr)(p.page_table + (size_t)seq * p.max_pages);
+  int issue_page_idx = t0 / p.page_size;
+  int issue_page = pt_row[min(issue_page_idx, p.max_pages - 1)];
 
   // ---- tile loads.  Wave w fills LDS chunks [256 w, 256 w + 256) of the latent tile with four loads
   // and chunks [128 w, 128 w + 128) of the RoPE tile with two; load q of a wave sits 1024 bytes after
   // load q-1 both in LDS and (four latent rows / eight RoPE rows further) in global memory, so the
-  // instruction offset covers it and only the swizzle parity of the row changes the lane offset.
-  unsigned lat_voff[2], rope_voff;
+  // instruction offset covers it and only the swizzle of the row changes the lane offset.
+  unsigned lat_voff[4], rope_voff[2];
 #pragma unroll
-  for (int par = 0; par < 2; ++par)
-    lat_voff[par] = (lane >> 4) * (kDcb * 2) + (((lane & 15) ^ swz(4 * par + (lane >> 4))) << 4);
-  rope_voff = (lane >> 3) * (kDr * 2) + (((lane & 7) ^ swz(lane >> 3)) << 4);
+  for (int q = 0; q < 4; ++q)
+    lat_voff[q] = (lane >> 4) * (kDcb * 2) + (((lane & 15) ^ lat_swz(4 * q + (lane >> 4))) << 4);
+#pragma unroll
+  for (int q = 0; q < 2; ++q)
+    rope_voff[q] = (lane >> 3) * (kDr * 2) + (((lane & 7) ^ rope_swz(8 * q + (lane >> 3))) << 4);
   const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
   const unsigned wave_u = __builtin_amdgcn_readfirstlane(wave);
   const size_t lat_page_bytes = (size_t)p.n_blocks * p.page_size * (kDcb * 2);
@@ -134,9 +156,7 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
   int issue_stage = 0;
 
   auto issue_tile = [&](int jj) {
-    if ((jj & 63) == 32) pid_next = load_page_ids(jj + 32);
-    if ((jj & 63) == 0 && jj > 0) pid_vec = pid_next;
-    const int page = __builtin_amdgcn_readlane(pid_vec, jj & 63);
+    const int page = issue_page;
     const int last = min(kTile, t1 - t0 - jj * kTile) - 1;
     // start of this tile's latent rows (block plane blk) and RoPE rows inside the page
     const char* lat_tile = lat_blk + (size_t)page * lat_page_bytes + (size_t)issue_slot * (kDcb * 2);
@@ -146,11 +166,11 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
       set_m0(stage + wave_u * 4096);
       lds_dma16<0>(lat_tile + wave_u * 4096, lat_voff[0]);
       lds_dma16<1024>(lat_tile + wave_u * 4096, lat_voff[1]);
-      lds_dma16<2048>(lat_tile + wave_u * 4096, lat_voff[0]);
-      lds_dma16<3072>(lat_tile + wave_u * 4096, lat_voff[1]);
+      lds_dma16<2048>(lat_tile + wave_u * 4096, lat_voff[2]);
+      lds_dma16<3072>(lat_tile + wave_u * 4096, lat_voff[3]);
       set_m0(stage + kLatBytes + wave_u * 2048);
-      lds_dma16<0>(rope_tile + wave_u * 2048, rope_voff);
-      lds_dma16<1024>(rope_tile + wave_u * 2048, rope_voff);
+      lds_dma16<0>(rope_tile + wave_u * 2048, rope_voff[0]);
+      lds_dma16<1024>(rope_tile + wave_u * 2048, rope_voff[1]);
     } else {
       // ragged end of the chunk: rows past it re-read its last row (finite values, weight 0 later).
       // Offsets are taken from the tile start so that they never go negative.
@@ -159,39 +179,46 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
         const int t = (wave * 4 + q) * 4 + (lane >> 4);     // 0..63
         const unsigned row = (unsigned)min(t, last);          // 0..last
         set_m0(stage + wave_u * 4096 + q * 1024);
-        lds_dma16<0>(lat_tile, row * (kDcb * 2) + (((lane & 15) ^ swz(t & 7)) << 4));
+        lds_dma16<0>(lat_tile, row * (kDcb * 2) + (((lane & 15) ^ lat_swz(t)) << 4));
       }
 #pragma unroll
       for (int q = 0; q < 2; ++q) {
         const int t = (wave * 2 + q) * 8 + (lane >> 3);     // 0..63
         const unsigned row = (unsigned)min(t, last);
         set_m0(stage + kLatBytes + wave_u * 2048 + q * 1024);
-        lds_dma16<0>(rope_tile, row * (kDr * 2) + (((lane & 7) ^ swz(t & 7)) << 4));
+        lds_dma16<0>(rope_tile, row * (kDr * 2) + (((lane & 7) ^ rope_swz(t)) << 4));
       }
     }
     issue_slot += kTile;
-    if (issue_slot >= p.page_size) issue_slot = 0;
+    if (issue_slot >= p.page_size) {
+      issue_slot = 0;
+      ++issue_page_idx;
+      issue_page = pt_row[min(issue_page_idx, p.max_pages - 1)];
+    }
     issue_stage = (issue_stage + 1 == STAGES) ? 0 : issue_stage + 1;
   };
 
   // ---- per-lane LDS read offsets inside a stage ----
   const int s_tok = tw * 32 + c32;
-  const int s_f = swz(s_tok & 7);
-  unsigned k_off[12], v_off[2][4];
+  unsigned k_off[12], v_off[2][4][2];
 #pragma unroll
-  for (int ks = 0; ks < 8; ++ks) k_off[ks] = s_tok * (kDcb * 2) + (((2 * ks + g) ^ s_f) << 4);
+  for (int ks = 0; ks < 8; ++ks) k_off[ks] = s_tok * (kDcb * 2) + (((2 * ks + g) ^ lat_swz(s_tok)) << 4);
 #pragma unroll
-  for (int ks = 0; ks < 4; ++ks) k_off[8 + ks] = kLatBytes + s_tok * (kDr * 2) + (((2 * ks + g) ^ s_f) << 4);
+  for (int ks = 0; ks < 4; ++ks)
+    k_off[8 + ks] = kLatBytes + s_tok * (kDr * 2) + (((2 * ks + g) ^ rope_swz(s_tok)) << 4);
   {
     const int k = (lane & 15) >> 2, seg = lane & 3, hb = (lane >> 4) & 1;
 #pragma unroll
     for (int ss = 0; ss < 2; ++ss) {
-      const int ta = tw * 32 + 16 * ss + 4 * g + k;
-      const int f = swz(ta & 7);
 #pragma unroll
-      for (int mt = 0; mt < 4; ++mt) {
-        const int cc = 4 * mt + 2 * hb + (seg >> 1);
-        v_off[ss][mt] = ta * (kDcb * 2) + ((cc ^ f) << 4) + ((seg & 1) << 3);
+      for (int half = 0; half < 2; ++half) {
+        const int ta = tw * 32 + 16 * ss + 8 * half + 4 * g + k;
+        const int f = lat_swz(ta);
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) {
+          const int cc = 4 * mt + 2 * hb + (seg >> 1);
+          v_off[ss][mt][half] = ta * (kDcb * 2) + ((cc ^ f) << 4) + ((seg & 1) << 3);
+        }
       }
     }
   }
@@ -220,8 +247,8 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
     for (int ss = 0; ss < 2; ++ss)
 #pragma unroll
       for (int mt = 0; mt < 4; ++mt) {
-        const short4v lo = lds_tr16(base + v_off[ss][mt]);
-        const short4v hi = lds_tr16(base + v_off[ss][mt] + 8 * (kDcb * 2));
+        const short4v lo = lds_tr16(base + v_off[ss][mt][0]);
+        const short4v hi = lds_tr16(base + v_off[ss][mt][1]);
         va[ss][mt] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
       }
   };
@@ -432,10 +459,12 @@ int launch_decode_mfma(const DecodeArgs& a) {
   p.h = a.h;
   p.n_splits = a.plan.n_splits;
   p.chunk = a.plan.chunk_tokens;
+  p.batch = a.batch;
   p.scale_log2 = a.softmax_scale * 1.4426950408889634f;
   const int n_hg = (a.h + kHeadsWG - 1) / kHeadsWG;
-  dim3 grid(a.plan.n_splits, a.n_blocks * n_hg, a.batch);
-  decode_mfma_kernel<kStages><<<grid, 256, lds, a.stream>>>(p);
+  const long long n_wg = (long long)a.plan.n_splits * a.n_blocks * n_hg * a.batch;
+  if (n_wg <= 0 || n_wg > 0x7fffffffLL) return MLRA_ERR_SHAPE;
+  decode_mfma_kernel<kStages><<<dim3((unsigned)n_wg), 256, lds, a.stream>>>(p);
   return check_launch();
 }
 
