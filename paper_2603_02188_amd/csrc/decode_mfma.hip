@@ -13,6 +13,8 @@
 //     partial (m, l, z) stays self-consistent and the merge kernel normalises.
 #include "mlra_internal.h"
 
+#include <type_traits>
+
 namespace mlra {
 namespace {
 
@@ -61,6 +63,13 @@ __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt((N & 0xF) | (0x7 << 4) | (0xF << 8) | ((N >> 4) << 14));
 }
 
+// same, and also waits for every LDS / scalar-memory operation of this wave (lgkmcnt = 0)
+template <int N>
+__device__ __forceinline__ void wait_vm_lgkm() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit field");
+  __builtin_amdgcn_s_waitcnt((N & 0xF) | (0x7 << 4) | (0x0 << 8) | ((N >> 4) << 14));
+}
+
 // Direct-to-LDS load: lane i's 16 bytes at (sbase + voff_i + OFF) land at LDS byte address
 // m0 + OFF + 16 i (the instruction offset moves both sides).  Written as inline asm so that the
 // compiler's wait-count insertion does not tie later LDS reads to these loads (it would drain all of
@@ -72,7 +81,7 @@ __device__ __forceinline__ void lds_dma16(const void* sbase, unsigned voff) {
   asm volatile("global_load_lds_dwordx4 %0, %1 offset:%2" : : "v"(voff), "s"(sbase), "n"(OFF) : "memory");
 }
 
-__device__ __forceinline__ short4v lds_tr16(const void* p) {
+__device__ __forceinline__ short4v lds_tr16(const __attribute__((address_space(3))) unsigned char* p) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3)))*)p);
 }
 
@@ -155,40 +164,50 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
   int issue_slot = t0 % p.page_size;   // slot of the next tile to issue inside its page (tiles go in order)
   int issue_stage = 0;
 
-  auto issue_tile = [&](int jj) {
-    const int page = issue_page;
-    const int last = min(kTile, t1 - t0 - jj * kTile) - 1;
+  // A tile is issued in parts so that the parts can sit behind different MFMAs: issue_begin (scalar
+  // address work), six loads, issue_end (bookkeeping, next page id).
+  const char* iss_lat = nullptr;
+  const char* iss_rope = nullptr;
+  unsigned iss_stage = 0;
+  int iss_last = kTile - 1;
+  auto issue_begin = [&](int jj) {
+    const unsigned page = (unsigned)issue_page;
+    iss_last = min(kTile, t1 - t0 - jj * kTile) - 1;
     // start of this tile's latent rows (block plane blk) and RoPE rows inside the page
-    const char* lat_tile = lat_blk + (size_t)page * lat_page_bytes + (size_t)issue_slot * (kDcb * 2);
-    const char* rope_tile = (const char*)p.rope + (size_t)page * rope_page_bytes + (size_t)issue_slot * (kDr * 2);
-    const unsigned stage = lds_base + issue_stage * kStageBytes;
-    if (last == kTile - 1) {
-      set_m0(stage + wave_u * 4096);
-      lds_dma16<0>(lat_tile + wave_u * 4096, lat_voff[0]);
-      lds_dma16<1024>(lat_tile + wave_u * 4096, lat_voff[1]);
-      lds_dma16<2048>(lat_tile + wave_u * 4096, lat_voff[2]);
-      lds_dma16<3072>(lat_tile + wave_u * 4096, lat_voff[3]);
-      set_m0(stage + kLatBytes + wave_u * 2048);
-      lds_dma16<0>(rope_tile + wave_u * 2048, rope_voff[0]);
-      lds_dma16<1024>(rope_tile + wave_u * 2048, rope_voff[1]);
-    } else {
-      // ragged end of the chunk: rows past it re-read its last row (finite values, weight 0 later).
-      // Offsets are taken from the tile start so that they never go negative.
+    iss_lat = lat_blk + page * lat_page_bytes + (unsigned)issue_slot * (unsigned)(kDcb * 2);
+    iss_rope = (const char*)p.rope + page * rope_page_bytes + (unsigned)issue_slot * (unsigned)(kDr * 2);
+    iss_stage = lds_base + issue_stage * kStageBytes;
+  };
+  // full tile: part 0..3 = latent loads, 4..5 = RoPE loads
+  auto issue_full_part = [&](int part) {
+    if (part == 0) set_m0(iss_stage + wave_u * 4096);
+    if (part == 0) lds_dma16<0>(iss_lat + wave_u * 4096, lat_voff[0]);
+    if (part == 1) lds_dma16<1024>(iss_lat + wave_u * 4096, lat_voff[1]);
+    if (part == 2) lds_dma16<2048>(iss_lat + wave_u * 4096, lat_voff[2]);
+    if (part == 3) lds_dma16<3072>(iss_lat + wave_u * 4096, lat_voff[3]);
+    if (part == 4) set_m0(iss_stage + kLatBytes + wave_u * 2048);
+    if (part == 4) lds_dma16<0>(iss_rope + wave_u * 2048, rope_voff[0]);
+    if (part == 5) lds_dma16<1024>(iss_rope + wave_u * 2048, rope_voff[1]);
+  };
+  // ragged end of the chunk: rows past it re-read its last row (finite values, weight 0 later).
+  // Offsets are taken from the tile start so that they never go negative.
+  auto issue_ragged = [&]() {
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int t = (wave * 4 + q) * 4 + (lane >> 4);     // 0..63
-        const unsigned row = (unsigned)min(t, last);          // 0..last
-        set_m0(stage + wave_u * 4096 + q * 1024);
-        lds_dma16<0>(lat_tile, row * (kDcb * 2) + (((lane & 15) ^ lat_swz(t)) << 4));
-      }
-#pragma unroll
-      for (int q = 0; q < 2; ++q) {
-        const int t = (wave * 2 + q) * 8 + (lane >> 3);     // 0..63
-        const unsigned row = (unsigned)min(t, last);
-        set_m0(stage + kLatBytes + wave_u * 2048 + q * 1024);
-        lds_dma16<0>(rope_tile, row * (kDr * 2) + (((lane & 7) ^ rope_swz(t)) << 4));
-      }
+    for (int q = 0; q < 4; ++q) {
+      const int t = (wave * 4 + q) * 4 + (lane >> 4);          // 0..63
+      const unsigned row = (unsigned)min(t, iss_last);           // 0..last
+      set_m0(iss_stage + wave_u * 4096 + q * 1024);
+      lds_dma16<0>(iss_lat, row * (kDcb * 2) + (((lane & 15) ^ lat_swz(t)) << 4));
     }
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      const int t = (wave * 2 + q) * 8 + (lane >> 3);          // 0..63
+      const unsigned row = (unsigned)min(t, iss_last);
+      set_m0(iss_stage + kLatBytes + wave_u * 2048 + q * 1024);
+      lds_dma16<0>(iss_rope, row * (kDr * 2) + (((lane & 7) ^ rope_swz(t)) << 4));
+    }
+  };
+  auto issue_end = [&]() {
     issue_slot += kTile;
     if (issue_slot >= p.page_size) {
       issue_slot = 0;
@@ -197,29 +216,31 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
     }
     issue_stage = (issue_stage + 1 == STAGES) ? 0 : issue_stage + 1;
   };
+  auto issue_tile = [&](int jj) {   // whole tile at once (prologue, and the steps near the end of a chunk)
+    issue_begin(jj);
+    if (iss_last == kTile - 1) {
+#pragma unroll
+      for (int part = 0; part < 6; ++part) issue_full_part(part);
+    } else {
+      issue_ragged();
+    }
+    issue_end();
+  };
 
-  // ---- per-lane LDS read offsets inside a stage ----
+  // ---- per-lane LDS read offsets inside a stage.  The swizzle is an XOR on the chunk index, so the
+  // offsets of the 12 score reads (and of the 16 transpose reads) of a lane differ from one base offset
+  // by XORs with constants and by multiples of 2 KiB: four registers hold them all.  (Stage starts are
+  // multiples of 8 KiB and the LDS buffer is 1 KiB aligned, so the XORs commute with adding them.) ----
   const int s_tok = tw * 32 + c32;
-  unsigned k_off[12], v_off[2][4][2];
-#pragma unroll
-  for (int ks = 0; ks < 8; ++ks) k_off[ks] = s_tok * (kDcb * 2) + (((2 * ks + g) ^ lat_swz(s_tok)) << 4);
-#pragma unroll
-  for (int ks = 0; ks < 4; ++ks)
-    k_off[8 + ks] = kLatBytes + s_tok * (kDr * 2) + (((2 * ks + g) ^ rope_swz(s_tok)) << 4);
+  const unsigned k_lat_off = s_tok * (kDcb * 2) + ((g ^ lat_swz(s_tok)) << 4);                // ^ (ks << 5)
+  const unsigned k_rope_off = kLatBytes + s_tok * (kDr * 2) + ((g ^ rope_swz(s_tok)) << 4);   // ^ (ks << 5)
+  unsigned v_off[2];                                                          // ^ (mt << 6), + 4096 ss
   {
     const int k = (lane & 15) >> 2, seg = lane & 3, hb = (lane >> 4) & 1;
 #pragma unroll
-    for (int ss = 0; ss < 2; ++ss) {
-#pragma unroll
-      for (int half = 0; half < 2; ++half) {
-        const int ta = tw * 32 + 16 * ss + 8 * half + 4 * g + k;
-        const int f = lat_swz(ta);
-#pragma unroll
-        for (int mt = 0; mt < 4; ++mt) {
-          const int cc = 4 * mt + 2 * hb + (seg >> 1);
-          v_off[ss][mt][half] = ta * (kDcb * 2) + ((cc ^ f) << 4) + ((seg & 1) << 3);
-        }
-      }
+    for (int half = 0; half < 2; ++half) {
+      const int ta = tw * 32 + 8 * half + 4 * g + k;
+      v_off[half] = ta * (kDcb * 2) + (((2 * hb + (seg >> 1)) ^ lat_swz(ta)) << 4) + ((seg & 1) << 3);
     }
   }
 
@@ -234,35 +255,35 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
 
   const float sc = p.scale_log2;
 
-  // K operands (this wave's 32 token rows x 192 channels) of the tile in stage st
+  typedef const __attribute__((address_space(3))) bf16x8* lds_bf16x8_ptr;
+  typedef const __attribute__((address_space(3))) unsigned char* lds_byte_ptr;
+  // K operand ks (this wave's 32 token rows x 16 channels) of the tile in stage st
+  auto load_k_part = [&](int st, int ks, bf16x8 (&ka)[12]) {
+    const unsigned base = lds_base + st * kStageBytes + (ks < 8 ? k_lat_off : k_rope_off);
+    ka[ks] = *(lds_bf16x8_ptr)(size_t)(base ^ ((ks & 7) << 5));
+  };
   auto load_k = [&](int st, bf16x8 (&ka)[12]) {
-    const unsigned char* base = smem + st * kStageBytes;
 #pragma unroll
-    for (int ks = 0; ks < 12; ++ks) ka[ks] = *(const bf16x8*)(base + k_off[ks]);
+    for (int ks = 0; ks < 12; ++ks) load_k_part(st, ks, ka);
   };
-  // transposed V operands (all 128 channels x this wave's 32 token rows) of the tile in stage st
-  auto load_v = [&](int st, bf16x8 (&va)[2][4]) {
-    const unsigned char* base = smem + st * kStageBytes;
-#pragma unroll
-    for (int ss = 0; ss < 2; ++ss)
-#pragma unroll
-      for (int mt = 0; mt < 4; ++mt) {
-        const short4v lo = lds_tr16(base + v_off[ss][mt][0]);
-        const short4v hi = lds_tr16(base + v_off[ss][mt][1]);
-        va[ss][mt] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-      }
+  // transposed V operand (32 channels of tile mt x 16 of this wave's token rows) of the tile in stage st
+  auto load_v_part = [&](int st, int ss, int mt, bf16x8 (&va)[2][4]) {
+    const unsigned lo_base = lds_base + st * kStageBytes + v_off[0];
+    const unsigned hi_base = lds_base + st * kStageBytes + v_off[1];
+    const lds_byte_ptr lo_p = (lds_byte_ptr)(size_t)(lo_base ^ (mt << 6));
+    const lds_byte_ptr hi_p = (lds_byte_ptr)(size_t)(hi_base ^ (mt << 6));
+    const short4v lo = lds_tr16(lo_p + ss * 16 * (kDcb * 2));
+    const short4v hi = lds_tr16(hi_p + ss * 16 * (kDcb * 2));
+    va[ss][mt] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
   };
-  // running-max bookkeeping of head tile nt for raw scores s (accumulator layout: this lane owns head
-  // column c32 and 16 of the 32 tokens); returns true if this lane's head needs a rescale
-  auto new_max = [&](int nt, const f32x16& sv, float& m_new) {
-    float mx = sv[0];
+  // maximum of this lane's head column over the wave's 32 tokens (the accumulator holds 16 of them, the
+  // lane 32 away the other 16)
+  auto col_max = [&](const f32x16& sv) {
+    float mx = fmaxf(fmaxf(sv[0], sv[1]), sv[2]);
 #pragma unroll
-    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sv[r]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float cand = mx * sc;
-    const bool need = cand > m_run[nt] + kLazy;
-    m_new = need ? cand : m_run[nt];
-    return need;
+    for (int r = 3; r < 15; r += 2) mx = fmaxf(fmaxf(mx, sv[r]), sv[r + 1]);
+    mx = fmaxf(mx, sv[15]);
+    return fmaxf(mx, __shfl_xor(mx, 32));
   };
   auto rescale = [&](int nt, float m_new) {
     const float alpha = __builtin_amdgcn_exp2f(m_run[nt] - m_new);   // 1 for heads that keep their max
@@ -273,20 +294,23 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
     l_run[nt] *= alpha;
     m_run[nt] = m_new;
   };
-  // P^T = 2^(s*sc - m) for head tile nt, rounded to bf16 into the two PV B operands; the row sums of
-  // the rounded values go to l_run
-  auto probs = [&](int nt, const f32x16& sv, bf16x8 (&pb)[2]) {
+  // P^T = 2^(s*sc - m) for two consecutive accumulator rows of head tile nt, rounded to bf16 into the PV
+  // B operand; the row sum of the rounded values goes to l_run.  Split in two so that the halves can sit
+  // behind different MFMAs.
+  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+  auto prob_exp = [&](int nt, const f32x16& sv, int r, float& p0, float& p1) {
     const float neg_m = -m_run[nt];
-    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
-#pragma unroll
-    for (int r = 0; r < 16; r += 2) {
-      const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[r], sc, neg_m));
-      const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[r + 1], sc, neg_m));
-      const bf16x2 pp = {(__bf16)p0, (__bf16)p1};
-      l_run[nt] = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, l_run[nt], false);
-      pb[r >> 3][r & 7] = pp[0];
-      pb[r >> 3][(r & 7) + 1] = pp[1];
-    }
+    p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[r], sc, neg_m));
+    p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[r + 1], sc, neg_m));
+    asm volatile("" : "+v"(p0), "+v"(p1));   // computed here, not sunk to the first use
+  };
+  auto prob_pack = [&](int nt, int r, float p0, float p1, bf16x8 (&pb)[2]) {
+    bf16x2 pp = {(__bf16)p0, (__bf16)p1};
+    asm volatile("" : "+v"(pp));
+    l_run[nt] = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, l_run[nt], false);
+    asm volatile("" : "+v"(l_run[nt]));
+    pb[r >> 3][r & 7] = pp[0];
+    pb[r >> 3][(r & 7) + 1] = pp[1];
   };
   auto mask_tail = [&](f32x16& sv) {
 #pragma unroll
@@ -296,53 +320,123 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
     }
   };
 
-  // ---- main loop: loads run STAGES-1 tiles ahead of the tile being consumed.  Per tile: scores
-  //      (matrix pipe), running max, then probabilities of one head tile on the vector ALU while the
-  //      matrix pipe accumulates Z for the other ----
-  for (int jj = 0; jj < STAGES - 1 && jj < ntiles; ++jj) issue_tile(jj);
-  int st_cur = 0;
-
-  for (int j = 0; j < ntiles; ++j) {
-    if (j + STAGES - 2 <= ntiles - 1) wait_vmcnt<kLoadsPerTile * (STAGES - 2)>(); else wait_vmcnt<0>();
-    __builtin_amdgcn_s_barrier();   // tile j landed for every wave; everyone is done with tile j-1
-    if (j + STAGES - 1 < ntiles) issue_tile(j + STAGES - 1);
-
-    bf16x8 ka[12], va[2][4];
-    load_k(st_cur, ka);
-    load_v(st_cur, va);
-
-    f32x16 s0, s1;
+  // ---- prologue: every stage gets a tile; scores and column maxima of tile 0; K operands of tile 1 ----
+  for (int jj = 0; jj < STAGES && jj < ntiles; ++jj) issue_tile(jj);
+  if (ntiles >= STAGES) wait_vmcnt<kLoadsPerTile * (STAGES - 2)>(); else wait_vmcnt<0>();
+  __builtin_amdgcn_s_barrier();   // tiles 0 and 1 landed for every wave
+  f32x16 sa0, sa1, sb0, sb1;
+  bf16x8 ka[12];
+  {
+    load_k(0, ka);
 #pragma unroll
-    for (int i = 0; i < 16; ++i) { s0[i] = 0.f; s1[i] = 0.f; }
+    for (int i = 0; i < 16; ++i) { sa0[i] = 0.f; sa1[i] = 0.f; }
 #pragma unroll
     for (int ks = 0; ks < 12; ++ks) {
-      s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[0][ks], s0, 0, 0, 0);
-      s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[1][ks], s1, 0, 0, 0);
-      // keeps ka[0] alive past the two MFMAs whose accumulator input is the constant 0, so that the
-      // allocator cannot place their destination on top of it (the build also scans for that)
-      if (ks == 1) asm volatile("" : : "v"(ka[0]));
+      sa0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[0][ks], sa0, 0, 0, 0);
+      sa1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[1][ks], sa1, 0, 0, 0);
+      if (ks == 1) asm volatile("" : : "v"(ka[0]));   // see the main loop
     }
-    if (j == ntiles - 1 && nvalid_last < kTile) { mask_tail(s0); mask_tail(s1); }
+    m_run[0] = col_max(sa0) * sc;
+    m_run[1] = col_max(sa1) * sc;
+    __builtin_amdgcn_sched_barrier(0);
+    load_k(1 % STAGES, ka);   // (a stale stage if the chunk has a single tile: those scores are never used)
+  }
 
-    float mn0, mn1;
-    const bool need0 = new_max(0, s0, mn0);
-    const bool need1 = new_max(1, s1, mn1);
-    if (__any(need0 || need1)) { rescale(0, mn0); rescale(1, mn1); }
+  // ---- main loop, software-pipelined over tiles; every MFMA is followed by about six issue slots of
+  // other work, which is what the matrix pipe hides.  Step j:
+  //   block A: scores of tile j+1 (n0, n1; K operands were fetched during the previous step) on the
+  //            matrix pipe  ||  probabilities of tile j from its scores (c0, c1) and the LDS transpose
+  //            reads of V(j) on the other pipes;
+  //   block B: Z += V(j)^T P(j)^T on the matrix pipe  ||  wait for tile j+2 + workgroup barrier, loads of
+  //            tile j+STAGES into the stage tile j leaves, K operands of tile j+2, column maxima of
+  //            tile j+1.
+  // The barrier says two things: tile j+2 is visible to every wave, and every wave has finished its LDS
+  // reads of tile j (V, this step) and tile j+1 (K, previous step).  FAST steps issue a tile that is
+  // known to exist and to be full, so they are straight-line code; the last steps of a chunk run the
+  // generic form.  sched_barrier(0) pins the interleaving. ----
+  int st_cur = 0;
+  auto step = [&](auto fast_tag, int j, f32x16& c0, f32x16& c1, f32x16& n0, f32x16& n1) {
+    constexpr bool FAST = decltype(fast_tag)::value;
+    const bool has_next = j + 1 < ntiles;
+    // Rows past the end of a ragged last tile hold copies of its last valid row: their scores equal a
+    // valid score, so the column maxima (taken one step earlier) were right without a mask; their
+    // probabilities are what has to vanish.
+    if (!FAST && j == ntiles - 1 && nvalid_last < kTile) { mask_tail(c0); mask_tail(c1); }
+    const int st_k2 = (st_cur + 2 >= STAGES) ? st_cur + 2 - STAGES : st_cur + 2;   // stage of tile j+2
 
-    bf16x8 pb0[2], pb1[2];
-    probs(0, s0, pb0);
+    bf16x8 va[2][4], pb0[2], pb1[2];
+    __builtin_amdgcn_sched_barrier(0);
+    // ---- block A: 24 MFMAs in 8 groups of 3; group g carries probability pairs 2g and 2g+1 (pairs
+    // 0..7 belong to head tile 0, 8..15 to head tile 1) and V operand g
 #pragma unroll
-    for (int ss = 0; ss < 2; ++ss)
+    for (int i = 0; i < 16; ++i) { n0[i] = 0.f; n1[i] = 0.f; }
 #pragma unroll
-      for (int mt = 0; mt < 4; ++mt)
-        zacc[mt][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[ss][mt], pb0[ss], zacc[mt][0], 0, 0, 0);
-    probs(1, s1, pb1);
+    for (int grp = 0; grp < 8; ++grp) {
+      float e0, e1, f0, f1;
 #pragma unroll
-    for (int ss = 0; ss < 2; ++ss)
+      for (int sub = 0; sub < 3; ++sub) {
+        const int i = 3 * grp + sub, ks = i >> 1;
+        if ((i & 1) == 0) n0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[0][ks], n0, 0, 0, 0);
+        else n1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[1][ks], n1, 0, 0, 0);
+        // keeps ka[0] alive past the two MFMAs whose accumulator input is the constant 0, so that the
+        // allocator cannot place their destination on top of it (the build also scans for that)
+        if (i == 3) asm volatile("" : : "v"(ka[0]));
+        const int pa = 2 * grp, pbi = 2 * grp + 1;   // the two pairs of this group
+        if (sub == 0) { if (pa < 8) prob_exp(0, c0, 2 * pa, e0, e1); else prob_exp(1, c1, 2 * (pa - 8), e0, e1); }
+        if (sub == 1) { if (pbi < 8) prob_exp(0, c0, 2 * pbi, f0, f1); else prob_exp(1, c1, 2 * (pbi - 8), f0, f1); }
+        if (sub == 2) {
+          if (pa < 8) prob_pack(0, 2 * pa, e0, e1, pb0); else prob_pack(1, 2 * (pa - 8), e0, e1, pb1);
+          if (pbi < 8) prob_pack(0, 2 * pbi, f0, f1, pb0); else prob_pack(1, 2 * (pbi - 8), f0, f1, pb1);
+          load_v_part(st_cur, grp >> 2, grp & 3, va);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+
+    // ---- block B: 16 MFMAs (m = 0..15: ss = m / 8, mt = (m / 2) % 4, nt = m % 2)
+    float mx0 = 0.f, mx1 = 0.f;
 #pragma unroll
-      for (int mt = 0; mt < 4; ++mt)
-        zacc[mt][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[ss][mt], pb1[ss], zacc[mt][1], 0, 0, 0);
+    for (int m = 0; m < 16; ++m) {
+      const int ss = m >> 3, mt = (m >> 1) & 3;
+      if ((m & 1) == 0) zacc[mt][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[ss][mt], pb0[ss], zacc[mt][0], 0, 0, 0);
+      else zacc[mt][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[ss][mt], pb1[ss], zacc[mt][1], 0, 0, 0);
+      if (m == 1) {
+        // this wave's LDS reads of V(j) have returned (so has everything older) before it tells the
+        // others that the stage may be overwritten
+        if (FAST || j + STAGES - 1 <= ntiles - 1) wait_vm_lgkm<kLoadsPerTile * (STAGES - 3)>(); else wait_vm_lgkm<0>();
+        __builtin_amdgcn_s_barrier();
+        if (FAST) issue_begin(j + STAGES);
+        else if (j + STAGES < ntiles) issue_tile(j + STAGES);
+      }
+      if (FAST && m >= 2 && m <= 4) { issue_full_part(2 * (m - 2)); issue_full_part(2 * (m - 2) + 1); }
+      if (FAST && m == 5) issue_end();
+      if (m >= 6 && m <= 11) { load_k_part(st_k2, 2 * (m - 6), ka); load_k_part(st_k2, 2 * (m - 6) + 1, ka); }
+      if (m == 12) mx0 = col_max(n0);
+      if (m == 14) mx1 = col_max(n1);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    const float cand0 = mx0 * sc, cand1 = mx1 * sc;
+    const bool need0 = has_next && cand0 > m_run[0] + kLazy;
+    const bool need1 = has_next && cand1 > m_run[1] + kLazy;
+    if (__any(need0 || need1)) {
+      rescale(0, need0 ? cand0 : m_run[0]);
+      rescale(1, need1 ? cand1 : m_run[1]);
+    }
     st_cur = (st_cur + 1 == STAGES) ? 0 : st_cur + 1;
+  };
+  {
+    const std::integral_constant<bool, true> fast;
+    const std::integral_constant<bool, false> generic;
+    int j = 0;
+    // a FAST step j issues tile j + STAGES, which must not be the (possibly ragged) last tile
+    for (; j + 1 + STAGES <= ntiles - 2; j += 2) {
+      step(fast, j, sa0, sa1, sb0, sb1);
+      step(fast, j + 1, sb0, sb1, sa0, sa1);
+    }
+    for (; j < ntiles; j += 2) {
+      step(generic, j, sa0, sa1, sb0, sb1);
+      if (j + 1 < ntiles) step(generic, j + 1, sb0, sb1, sa0, sa1);
+    }
   }
 
   // ---- merge the two token halves of each head half through LDS, write the chunk's partial ----
@@ -426,7 +520,7 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
   }
 }
 
-constexpr int kStages = 5;
+constexpr int kStages = 6;
 
 }  // namespace
 
