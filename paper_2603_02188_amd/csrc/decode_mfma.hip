@@ -276,14 +276,26 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
     const short4v hi = lds_tr16(hi_p + ss * 16 * (kDcb * 2));
     va[ss][mt] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
   };
-  // maximum of this lane's head column over the wave's 32 tokens (the accumulator holds 16 of them, the
-  // lane 32 away the other 16)
-  auto col_max = [&](const f32x16& sv) {
-    float mx = fmaxf(fmaxf(sv[0], sv[1]), sv[2]);
-#pragma unroll
-    for (int r = 3; r < 15; r += 2) mx = fmaxf(fmaxf(mx, sv[r]), sv[r + 1]);
-    mx = fmaxf(mx, sv[15]);
-    return fmaxf(mx, __shfl_xor(mx, 32));
+  // Column maxima.  In the accumulator layout a lane holds 16 of the 32 token rows of its head column
+  // and the lane 32 away holds the other 16.  max4 folds four more rows into a running maximum;
+  // cross_max finishes both head tiles at once with two half-wave swaps (v_permlane32_swap exchanges
+  // the upper half of its first operand with the lower half of its second).
+  auto max4 = [&](float mx, const f32x16& sv, int r) {
+    return fmaxf(fmaxf(fmaxf(mx, sv[r]), fmaxf(sv[r + 1], sv[r + 2])), sv[r + 3]);
+  };
+  auto swap_halves = [&](float& a, float& b) {
+    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+  };
+  auto cross_max = [&](float& mx0, float& mx1) {
+    swap_halves(mx0, mx1);            // mx0 = {tile 0 lower, tile 1 lower}, mx1 = {tile 0 upper, tile 1 upper}
+    mx0 = fmaxf(mx0, mx1);            // lanes 0..31: column maxima of head tile 0, lanes 32..63: of head tile 1
+    mx1 = mx0;
+    swap_halves(mx0, mx1);            // mx0 = tile 0 maxima in both halves, mx1 = tile 1 maxima in both halves
+  };
+  auto col_max2 = [&](const f32x16& s0, const f32x16& s1, float& mx0, float& mx1) {
+    mx0 = max4(max4(max4(max4(s0[0], s0, 0), s0, 4), s0, 8), s0, 12);
+    mx1 = max4(max4(max4(max4(s1[0], s1, 0), s1, 4), s1, 8), s1, 12);
+    cross_max(mx0, mx1);
   };
   auto rescale = [&](int nt, float m_new) {
     const float alpha = __builtin_amdgcn_exp2f(m_run[nt] - m_new);   // 1 for heads that keep their max
@@ -294,21 +306,23 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
     l_run[nt] *= alpha;
     m_run[nt] = m_new;
   };
-  // P^T = 2^(s*sc - m) for two consecutive accumulator rows of head tile nt, rounded to bf16 into the PV
-  // B operand; the row sum of the rounded values goes to l_run.  Split in two so that the halves can sit
-  // behind different MFMAs.
-  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+  // P^T = 2^(s*sc - m) for two consecutive accumulator rows of head tile nt (prob_exp), the row sum in
+  // fp32 (prob_sum) and the rounding to bf16 into the PV B operand (prob_pack): three pieces, so that
+  // they can sit behind different MFMAs.
   auto prob_exp = [&](int nt, const f32x16& sv, int r, float& p0, float& p1) {
     const float neg_m = -m_run[nt];
     p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[r], sc, neg_m));
     p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[r + 1], sc, neg_m));
     asm volatile("" : "+v"(p0), "+v"(p1));   // computed here, not sunk to the first use
   };
-  auto prob_pack = [&](int nt, int r, float p0, float p1, bf16x8 (&pb)[2]) {
+  auto prob_sum = [&](int nt, float p0, float p1) {
+    l_run[nt] += p0;
+    l_run[nt] += p1;
+    asm volatile("" : "+v"(l_run[nt]));
+  };
+  auto prob_pack = [&](int r, float p0, float p1, bf16x8 (&pb)[2]) {
     bf16x2 pp = {(__bf16)p0, (__bf16)p1};
     asm volatile("" : "+v"(pp));
-    l_run[nt] = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, l_run[nt], false);
-    asm volatile("" : "+v"(l_run[nt]));
     pb[r >> 3][r & 7] = pp[0];
     pb[r >> 3][(r & 7) + 1] = pp[1];
   };
@@ -336,8 +350,10 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
       sa1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[1][ks], sa1, 0, 0, 0);
       if (ks == 1) asm volatile("" : : "v"(ka[0]));   // see the main loop
     }
-    m_run[0] = col_max(sa0) * sc;
-    m_run[1] = col_max(sa1) * sc;
+    float mx0, mx1;
+    col_max2(sa0, sa1, mx0, mx1);
+    m_run[0] = mx0 * sc;
+    m_run[1] = mx1 * sc;
     __builtin_amdgcn_sched_barrier(0);
     load_k(1 % STAGES, ka);   // (a stale stage if the chunk has a single tile: those scores are never used)
   }
@@ -366,31 +382,35 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
 
     bf16x8 va[2][4], pb0[2], pb1[2];
     __builtin_amdgcn_sched_barrier(0);
-    // ---- block A: 24 MFMAs in 8 groups of 3; group g carries probability pairs 2g and 2g+1 (pairs
-    // 0..7 belong to head tile 0, 8..15 to head tile 1) and V operand g
+    // ---- block A: 24 score MFMAs.  MFMA i < 16 carries the exponentials of probability pair i (pairs
+    // 0..7: head tile 0, 8..15: head tile 1) and the row-sum update of pair i-1; MFMA 16+q carries the
+    // bf16 packing of pairs 2q, 2q+1 and the LDS transpose reads of V operand q.
 #pragma unroll
     for (int i = 0; i < 16; ++i) { n0[i] = 0.f; n1[i] = 0.f; }
+    float pr[32];
 #pragma unroll
-    for (int grp = 0; grp < 8; ++grp) {
-      float e0, e1, f0, f1;
-#pragma unroll
-      for (int sub = 0; sub < 3; ++sub) {
-        const int i = 3 * grp + sub, ks = i >> 1;
-        if ((i & 1) == 0) n0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[0][ks], n0, 0, 0, 0);
-        else n1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[1][ks], n1, 0, 0, 0);
-        // keeps ka[0] alive past the two MFMAs whose accumulator input is the constant 0, so that the
-        // allocator cannot place their destination on top of it (the build also scans for that)
-        if (i == 3) asm volatile("" : : "v"(ka[0]));
-        const int pa = 2 * grp, pbi = 2 * grp + 1;   // the two pairs of this group
-        if (sub == 0) { if (pa < 8) prob_exp(0, c0, 2 * pa, e0, e1); else prob_exp(1, c1, 2 * (pa - 8), e0, e1); }
-        if (sub == 1) { if (pbi < 8) prob_exp(0, c0, 2 * pbi, f0, f1); else prob_exp(1, c1, 2 * (pbi - 8), f0, f1); }
-        if (sub == 2) {
-          if (pa < 8) prob_pack(0, 2 * pa, e0, e1, pb0); else prob_pack(1, 2 * (pa - 8), e0, e1, pb1);
-          if (pbi < 8) prob_pack(0, 2 * pbi, f0, f1, pb0); else prob_pack(1, 2 * (pbi - 8), f0, f1, pb1);
-          load_v_part(st_cur, grp >> 2, grp & 3, va);
-        }
-        __builtin_amdgcn_sched_barrier(0);
+    for (int i = 0; i < 24; ++i) {
+      const int ks = i >> 1;
+      if ((i & 1) == 0) n0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[0][ks], n0, 0, 0, 0);
+      else n1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[1][ks], n1, 0, 0, 0);
+      // keeps ka[0] alive past the two MFMAs whose accumulator input is the constant 0, so that the
+      // allocator cannot place their destination on top of it (the build also scans for that)
+      if (i == 3) asm volatile("" : : "v"(ka[0]));
+      if (i < 16) {
+        if (i < 8) prob_exp(0, c0, 2 * i, pr[2 * i], pr[2 * i + 1]);
+        else prob_exp(1, c1, 2 * (i - 8), pr[2 * i], pr[2 * i + 1]);
       }
+      if (i >= 1 && i <= 16) prob_sum((i - 1) >> 3, pr[2 * (i - 1)], pr[2 * (i - 1) + 1]);
+      if (i >= 16) {
+        const int q = i - 16;
+#pragma unroll
+        for (int pi = 2 * q; pi < 2 * q + 2; ++pi) {
+          if (pi < 8) prob_pack(2 * pi, pr[2 * pi], pr[2 * pi + 1], pb0);
+          else prob_pack(2 * (pi - 8), pr[2 * pi], pr[2 * pi + 1], pb1);
+        }
+        load_v_part(st_cur, q >> 2, q & 3, va);
+      }
+      __builtin_amdgcn_sched_barrier(0);
     }
 
     // ---- block B: 16 MFMAs (m = 0..15: ss = m / 8, mt = (m / 2) % 4, nt = m % 2)
@@ -410,9 +430,12 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
       }
       if (FAST && m >= 2 && m <= 4) { issue_full_part(2 * (m - 2)); issue_full_part(2 * (m - 2) + 1); }
       if (FAST && m == 5) issue_end();
-      if (m >= 6 && m <= 11) { load_k_part(st_k2, 2 * (m - 6), ka); load_k_part(st_k2, 2 * (m - 6) + 1, ka); }
-      if (m == 12) mx0 = col_max(n0);
-      if (m == 14) mx1 = col_max(n1);
+      if (m >= 4) load_k_part(st_k2, m - 4, ka);
+      if (m == 6) mx0 = max4(max4(n0[0], n0, 0), n0, 4);
+      if (m == 8) mx0 = max4(max4(mx0, n0, 8), n0, 12);
+      if (m == 10) mx1 = max4(max4(n1[0], n1, 0), n1, 4);
+      if (m == 12) mx1 = max4(max4(mx1, n1, 8), n1, 12);
+      if (m == 14) cross_max(mx0, mx1);
       __builtin_amdgcn_sched_barrier(0);
     }
     const float cand0 = mx0 * sc, cand1 = mx1 * sc;
