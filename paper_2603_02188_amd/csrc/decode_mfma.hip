@@ -108,16 +108,15 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
   }
   const int split = su % p.n_splits, seq = su / p.n_splits;
   const int blk = member / n_hg, hgrp = member % n_hg;
-  const int n = p.seq_lens[seq];
-  const int t0 = split * p.chunk;
-  if (t0 >= n) return;
-  const int t1 = min(n, t0 + p.chunk);
-  const int ntiles = (t1 - t0 + kTile - 1) / kTile;
-  const int nvalid_last = t1 - t0 - (ntiles - 1) * kTile;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int hw = wave & 1, tw = wave >> 1, g = lane >> 5, c32 = lane & 31;
 
-  // ---- absorbed + RoPE queries as MFMA B operands, resident in registers for the whole chunk ----
+  // ---- absorbed + RoPE queries as MFMA B operands, resident in accumulation registers for the whole
+  // chunk (MFMA reads its B operand from there directly, which leaves the architectural VGPRs to the
+  // per-tile working set).  The loads are issued first thing, straight into those registers and
+  // invisibly to the compiler's wait-count bookkeeping: they are older than every tile load, so the
+  // first explicit wait for a tile (vector-memory operations retire in order) also covers them, and
+  // nothing reads these registers before the first MFMA, which comes after that wait. ----
   bf16x8 qreg[2][12];
 #pragma unroll
   for (int nt = 0; nt < 2; ++nt) {
@@ -125,25 +124,30 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
     const bf16_t* qa = p.q_abs + (((size_t)seq * p.n_blocks + blk) * p.h + head) * kDcb + g * 8;
     const bf16_t* qr = p.q_rope + ((size_t)seq * p.h + head) * kDr + g * 8;
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) qreg[nt][ks] = *(const bf16x8*)(qa + ks * 16);
+    for (int ks = 0; ks < 8; ++ks)
+      asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=a"(qreg[nt][ks]) : "v"(qa), "n"(ks * 32) : "memory");
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) qreg[nt][8 + ks] = *(const bf16x8*)(qr + ks * 16);
+    for (int ks = 0; ks < 4; ++ks)
+      asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=a"(qreg[nt][8 + ks]) : "v"(qr), "n"(ks * 32) : "memory");
   }
-  // Pin the queries into accumulation registers: MFMA reads its B operand from there directly, which
-  // leaves the architectural VGPRs to the per-tile working set.
-#pragma unroll
-  for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-    for (int ks = 0; ks < 12; ++ks) asm volatile("" : "+a"(qreg[nt][ks]));
+
+  const int t0 = split * p.chunk;
+  // page id of the first tile, fetched before the sequence length is known (the index is in range for
+  // any length)
+  typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
+  const const_i32_ptr pt_row = (const_i32_ptr)(p.page_table + (size_t)seq * p.max_pages);
+  int issue_page_idx = t0 / p.page_size;
+  int issue_page = pt_row[min(issue_page_idx, p.max_pages - 1)];
+  const int n = ((const_i32_ptr)p.seq_lens)[seq];
+  if (t0 >= n) return;
+  const int t1 = min(n, t0 + p.chunk);
+  const int ntiles = (t1 - t0 + kTile - 1) / kTile;
+  const int nvalid_last = t1 - t0 - (ntiles - 1) * kTile;
 
   // ---- page ids: scalar loads through the constant address space (the table is read-only here), so
   // that the compiler's vector-memory wait counts never see a load inside the main loop: a wait for one
   // would also drain every direct-to-LDS load in flight.  The id of the next tile's page is fetched one
   // tile ahead of its use.
-  typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
-  const const_i32_ptr pt_row = (const_i32_ptr)(p.page_table + (size_t)seq * p.max_pages);
-  int issue_page_idx = t0 / p.page_size;
-  int issue_page = pt_row[min(issue_page_idx, p.max_pages - 1)];
 
   // ---- tile loads.  Wave w fills LDS chunks [256 w, 256 w + 256) of the latent tile with four loads
   // and chunks [128 w, 128 w + 128) of the RoPE tile with two; load q of a wave sits 1024 bytes after

@@ -28,12 +28,13 @@ int device_cu_count() {
   return 256;  // MI355X; used only when no device can be queried (e.g. sizing on a CPU-only host)
 }
 
-// Enough workgroups to cover every CU about twice when the batch alone cannot, never chunks shorter
+// Enough workgroups to cover every CU once when the batch alone cannot (the decode kernel runs one
+// workgroup per CU, and each workgroup pays a fixed start-up and write-out cost), never chunks shorter
 // than 128 tokens (a partial costs as much traffic as ~170 cached tokens of one block).
 SplitPlan plan_splits(int batch, int n_blocks, int max_seq_len) {
   const int kMinChunk = 128, kTile = 64;
   const long units = (long)batch * n_blocks;
-  const long target = 2L * device_cu_count();
+  const long target = 1L * device_cu_count();
   long want = (target + units - 1) / units;
   const long max_splits = (max_seq_len + kMinChunk - 1) / kMinChunk;
   if (want > max_splits) want = max_splits;
