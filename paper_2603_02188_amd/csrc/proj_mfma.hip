@@ -76,12 +76,20 @@ __global__ __launch_bounds__(256) void absorb_q_mfma_kernel(const bf16_t* __rest
 
 // ------------------------------------------------------------------------------------------------
 // merge + up-projection.  One workgroup per (head, tile of 32 sequences).
-//   phase 1: the merged, normalised z of the 32 sequences for all R = n_blocks*d_cb latent channels,
-//            rounded to bf16, is built in LDS (row = sequence);
-//   phase 2: out[seq][j] = sum_r z[seq][r] W^UV[r][head*128 + j]; W^UV streams through LDS in chunks
-//            of 32 rows and reaches the MFMA B operand through transpose reads; wave w owns output
-//            columns [32 w, 32 w + 32).
+//   phase 0: the loads of the first 512 rows of this head's W^UV slice are issued into registers, so
+//            that they are in flight while phase 1 runs;
+//   phase 1a: one thread per (sequence, block) turns the chunk partials' (m, l) into normalised merge
+//            weights w_k = 2^(m_k - m*) / L in LDS and writes the log-sum-exp;
+//   phase 1b: merged z = sum_k w_k z_k of the 32 sequences for all R = n_blocks*d_cb latent channels,
+//            rounded to bf16, is built in LDS (row = sequence), four independent items per thread at a
+//            time so that their loads overlap;
+//   phase 2: out[seq][j] = sum_r z[seq][r] W^UV[r][head*128 + j]; W^UV goes through LDS 256 rows at a
+//            time and reaches the MFMA B operand through transpose reads; wave w owns output columns
+//            [32 w, 32 w + 32).
 // ------------------------------------------------------------------------------------------------
+constexpr int kWRowsLds = 256;    // W^UV rows resident in LDS at a time (64 KiB)
+constexpr int kWRowsRegs = 512;   // W^UV rows prefetched into registers at a time (32 loads per thread)
+
 template <typename TO>
 __global__ __launch_bounds__(256) void merge_upproj_mfma_kernel(
     const float* __restrict__ part_z, const float* __restrict__ part_ml, const int32_t* __restrict__ seq_lens,
@@ -90,78 +98,155 @@ __global__ __launch_bounds__(256) void merge_upproj_mfma_kernel(
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   const int R = n_blocks * d_cb;
   const int zpitch = R + 8;                               // bf16 elements per z row (+16 B against conflicts)
-  bf16_t* zt = (bf16_t*)smem;                             // [32][zpitch]
-  unsigned char* wt = smem + (size_t)32 * zpitch * 2;     // [32 rows][256 B], 16-byte chunks swizzled
+  const int units_per_seq = n_blocks * n_splits;
+  unsigned char* wt = smem;                               // [256 rows][256 B], 16-byte chunks swizzled
+  bf16_t* zt = (bf16_t*)(smem + kWRowsLds * 256);         // [32][zpitch]
+  float* wtab = (float*)(smem + kWRowsLds * 256 + (size_t)32 * zpitch * 2);   // [32][units_per_seq]
+  float* ltab = wtab + 32 * units_per_seq;                 // [32][units_per_seq] row sums of the partials
+  int* act = (int*)(ltab + 32 * units_per_seq);           // [32] active chunks per sequence
   const int head = blockIdx.x, m0 = blockIdx.y * 32;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, c32 = lane & 31;
+  const size_t ldw = (size_t)h * kDh;
 
-  // ---- phase 1 ----
-  const int items_per_row = R / 8;
-  for (int item = tid; item < 32 * items_per_row; item += 256) {
-    const int sl = item / items_per_row, r0 = (item % items_per_row) * 8;
-    const int seq = m0 + sl;
-    float z[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  // ---- phase 0: thread t owns 16-byte chunk t % 16 of rows t / 16 + 16 i
+  bf16x8 wreg[kWRowsRegs / 16];
+  const bf16_t* wsrc = w_uv + (size_t)(tid >> 4) * ldw + (size_t)head * kDh + (tid & 15) * 8;
+  auto fetch_w = [&](int row0) {
+#pragma unroll
+    for (int i = 0; i < kWRowsRegs / 16; ++i)
+      if (row0 + 16 * i < R) wreg[i] = *(const bf16x8*)(wsrc + (size_t)(row0 + 16 * i) * ldw);
+  };
+  fetch_w(0);
+
+  // ---- phase 1a: every (sequence, block, chunk) partial's (m, l) goes to LDS with one load per thread,
+  // then one thread per (sequence, block) reduces them
+  for (int t = tid; t < 32 * units_per_seq; t += 256) {
+    const int sl = t / units_per_seq, seq = m0 + sl, k = t % n_splits;
+    float2 ml = make_float2(kNegBig, 0.f);
     if (seq < batch) {
-      const int b = r0 / d_cb, c0 = r0 % d_cb;
-      const int n = seq_lens[seq];
-      const int active = min(n_splits, (n + chunk - 1) / chunk);
-      const size_t unit0 = ((size_t)seq * n_blocks + b) * n_splits;
+      const int active = min(n_splits, (seq_lens[seq] + chunk - 1) / chunk);
+      if (k < active) ml = *(const float2*)(part_ml + (((size_t)seq * units_per_seq + t % units_per_seq) * h + head) * 2);
+    }
+    wtab[t] = ml.x;
+    ltab[t] = ml.y;
+  }
+  __syncthreads();
+  for (int t = tid; t < 32 * n_blocks; t += 256) {
+    const int sl = t / n_blocks, b = t % n_blocks, seq = m0 + sl;
+    float* wrow = wtab + sl * units_per_seq + b * n_splits;
+    const float* lrow = ltab + sl * units_per_seq + b * n_splits;
+    int active = 0;
+    if (seq < batch) {
+      active = min(n_splits, (seq_lens[seq] + chunk - 1) / chunk);
       float m_star = kNegBig;
-      for (int k = 0; k < active; ++k) m_star = fmaxf(m_star, part_ml[((unit0 + k) * h + head) * 2]);
+      for (int k = 0; k < active; ++k) m_star = fmaxf(m_star, wrow[k]);
       float L = 0.f;
       for (int k = 0; k < active; ++k) {
-        const float* ml = part_ml + ((unit0 + k) * h + head) * 2;
-        const float w = exp2f(ml[0] - m_star);
-        L += w * ml[1];
-        const f32x4* pz = (const f32x4*)(part_z + ((unit0 + k) * h + head) * d_cb + c0);
-        const f32x4 lo = pz[0], hi = pz[1];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) { z[e] += w * lo[e]; z[4 + e] += w * hi[e]; }
+        const float w = exp2f(wrow[k] - m_star);
+        L += w * lrow[k];
+        wrow[k] = w;
       }
       const float inv = L > 0.f ? 1.f / L : 0.f;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) z[e] *= inv;
-      if (c0 == 0 && lse) lse[((size_t)seq * n_blocks + b) * h + head] = L > 0.f ? (m_star + log2f(L)) * kLn2 : -INFINITY;
+      for (int k = 0; k < active; ++k) wrow[k] *= inv;
+      if (lse) lse[((size_t)seq * n_blocks + b) * h + head] = L > 0.f ? (m_star + log2f(L)) * kLn2 : -INFINITY;
     }
-    bf16x8 packed;
+    if (b == 0) act[sl] = active;
+  }
+  __syncthreads();
+
+  // ---- phase 1b: item = (sequence slot, 8 consecutive latent channels)
+  const int items_per_row = R / 8;
+  const int n_items = 32 * items_per_row;
+  for (int base = tid; base < n_items; base += 4 * 256) {
+    float z[4][8];
+    const float* pz[4];
+    const float* wk[4];
+    int na[4], sl[4], r0[4], kmax = 0;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) packed[e] = (__bf16)z[e];
-    *(bf16x8*)(zt + sl * zpitch + r0) = packed;
+    for (int u = 0; u < 4; ++u) {
+      const int item = base + u * 256;
+      sl[u] = min(item, n_items - 1) / items_per_row;
+      r0[u] = (min(item, n_items - 1) % items_per_row) * 8;
+      const int b = r0[u] / d_cb, c0 = r0[u] % d_cb;
+      const int seq = min(m0 + sl[u], batch - 1);
+      na[u] = item < n_items ? act[sl[u]] : 0;
+      kmax = max(kmax, na[u]);
+      pz[u] = part_z + ((((size_t)seq * n_blocks + b) * n_splits) * h + head) * d_cb + c0;
+      wk[u] = wtab + sl[u] * units_per_seq + b * n_splits;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) z[u][e] = 0.f;
+    }
+    const size_t z_stride = (size_t)h * d_cb;
+    for (int k0 = 0; k0 < kmax; k0 += 4) {   // 4 chunks x 4 items = up to 32 loads in flight
+      f32x4 lo[4][4], hi[4][4];
+      float w[4][4];
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int k = k0 + kk;
+          const bool on = k < na[u];
+          const f32x4* src = (const f32x4*)(pz[u] + (on ? k : 0) * z_stride);
+          w[kk][u] = on ? wk[u][k] : 0.f;
+          if (on) { lo[kk][u] = src[0]; hi[kk][u] = src[1]; }
+          else { lo[kk][u] = f32x4{0.f, 0.f, 0.f, 0.f}; hi[kk][u] = lo[kk][u]; }
+        }
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            z[u][e] += w[kk][u] * lo[kk][u][e];
+            z[u][4 + e] += w[kk][u] * hi[kk][u][e];
+          }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (base + u * 256 < n_items) {
+        bf16x8 packed;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) packed[e] = (__bf16)z[u][e];
+        *(bf16x8*)(zt + sl[u] * zpitch + r0[u]) = packed;
+      }
+    }
   }
 
   // ---- phase 2 ----
   f32x16 acc = opaque_zero();
-  const size_t ldw = (size_t)h * kDh;
   // transpose-read offsets: the 16 lanes of a block fetch 4 consecutive rows x 16 output columns
-  unsigned tr_off[2][2];
+  unsigned tr_off[2];
   {
     const int k = (lane & 15) >> 2, seg = lane & 3, hb = (lane >> 4) & 1;
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-      for (int half = 0; half < 2; ++half) {
-        const int row = 16 * ks + 8 * g + 4 * half + k;
-        const int cc = 4 * wave + 2 * hb + (seg >> 1);
-        tr_off[ks][half] = row * 256 + ((cc ^ swz(row & 7)) << 4) + ((seg & 1) << 3);
-      }
-  }
-  for (int kc = 0; kc < R; kc += 32) {
-    __syncthreads();   // phase 1 done / previous chunk consumed
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int ch = tid + i * 256;           // 512 chunks of 16 bytes: row = ch / 16, chunk = ch % 16
-      const int row = ch >> 4, cc = ch & 15;
-      const bf16x8 v = *(const bf16x8*)(w_uv + (size_t)(kc + row) * ldw + (size_t)head * kDh + cc * 8);
-      *(bf16x8*)(wt + row * 256 + ((cc ^ swz(row & 7)) << 4)) = v;
+    for (int half = 0; half < 2; ++half) {
+      const int row = 8 * g + 4 * half + k;                 // + 16 per MFMA k-step (same swizzle: row & 7)
+      const int cc = 4 * wave + 2 * hb + (seg >> 1);
+      tr_off[half] = row * 256 + ((cc ^ swz(row & 7)) << 4) + ((seg & 1) << 3);
     }
-    __syncthreads();
+  }
+  for (int pass0 = 0; pass0 < R; pass0 += kWRowsRegs) {
+    if (pass0 > 0) fetch_w(pass0);
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-      const bf16x8 a = *(const bf16x8*)(zt + c32 * zpitch + kc + ks * 16 + g * 8);
-      const short4v lo = lds_tr16(wt + tr_off[ks][0]);
-      const short4v hi = lds_tr16(wt + tr_off[ks][1]);
-      const bf16x8 bm = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bm, acc, 0, 0, 0);
+    for (int part = 0; part < kWRowsRegs / kWRowsLds; ++part) {
+      const int row_base = pass0 + part * kWRowsLds;
+      if (row_base >= R) break;
+      __syncthreads();   // phase 1 done / previous rows consumed
+#pragma unroll
+      for (int i = 0; i < kWRowsLds / 16; ++i) {
+        const int row = (tid >> 4) + 16 * i, cc = tid & 15;
+        if (row_base + row < R)
+          *(bf16x8*)(wt + row * 256 + ((cc ^ swz(row & 7)) << 4)) = wreg[part * (kWRowsLds / 16) + i];
+      }
+      __syncthreads();
+      const int rows = min(kWRowsLds, R - row_base);
+      for (int ks = 0; ks < rows / 16; ++ks) {
+        const bf16x8 a = *(const bf16x8*)(zt + c32 * zpitch + row_base + ks * 16 + g * 8);
+        const short4v lo = lds_tr16(wt + ks * 16 * 256 + tr_off[0]);
+        const short4v hi = lds_tr16(wt + ks * 16 * 256 + tr_off[1]);
+        const bf16x8 bm = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bm, acc, 0, 0, 0);
+      }
     }
   }
   const int j = wave * 32 + c32;
@@ -188,18 +273,20 @@ int launch_absorb_q_mfma(int batch, int h, int d_h, int n_blocks, int d_cb, cons
 }
 
 bool merge_upproj_mfma_supported(const DecodeArgs& a) {
-  return a.dtype == MLRA_BF16 && a.d_h == kDh && a.d_cb % 32 == 0 && a.n_blocks * a.d_cb <= 1024;
+  return a.dtype == MLRA_BF16 && a.d_h == kDh && a.d_cb % 32 == 0 && a.n_blocks * a.d_cb <= 1024 &&
+         a.n_blocks * a.plan.n_splits <= 128;
 }
 
 int launch_merge_upproj_mfma(const DecodeArgs& a) {
   const int R = a.n_blocks * a.d_cb;
-  const size_t lds = (size_t)32 * (R + 8) * 2 + 32 * 256;
+  const size_t lds = (size_t)kWRowsLds * 256 + (size_t)32 * (R + 8) * 2 +
+                     (size_t)64 * a.n_blocks * a.plan.n_splits * sizeof(float) + 32 * sizeof(int);
   static bool configured = false;
   if (!configured) {
     if (hipFuncSetAttribute((const void*)merge_upproj_mfma_kernel<bf16_t>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            96 * 1024) != hipSuccess ||
+                            160 * 1024) != hipSuccess ||
         hipFuncSetAttribute((const void*)merge_upproj_mfma_kernel<float>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            96 * 1024) != hipSuccess)
+                            160 * 1024) != hipSuccess)
       return MLRA_ERR_LAUNCH;
     configured = true;
   }
