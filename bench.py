@@ -24,8 +24,8 @@ sys.path.insert(0, ROOT)
 def _args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="C3", choices=["C2", "C3", "C4", "C5"])
     ap.add_argument("--copies", type=int, default=0, help="cache copies to rotate over (0 = enough for ~3 GB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -67,6 +67,20 @@ def _cpu_baseline(inp, max_seconds=25.0):
                       f"{dt:.1f} s of fp64 numpy, scaled to the whole batch by token count"}, np.stack(outs)
 
 
+def _measured_traffic(workload):
+    """HBM bytes per launch of the decode kernel from the committed rocprofv3 counter summary (FETCH_SIZE and
+    WRITE_SIZE runs, scaled by a plain copy of known size), or None if no summary covers this workload."""
+    path = os.path.join(ROOT, "profiles", f"decode_step_{workload}_counters.md")
+    try:
+        for line in open(path):
+            cells = [c.strip() for c in line.strip().strip("|").split("|")]
+            if len(cells) == 7 and cells[0].startswith("decode_mfma_kernel"):
+                return float(cells[6])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     a = _args()
     if a.gpus != 1:
@@ -95,7 +109,7 @@ def main():
         return t.to(dev)
 
     cache_bytes = inp.latent_pool.nbytes + inp.rope_pool.nbytes
-    copies = a.copies or max(2, min(16, int(np.ceil(3.0e9 / cache_bytes))))
+    copies = a.copies or max(2, min(32, int(np.ceil(3.0e9 / cache_bytes))))
     lat0, rope0 = up(inp.latent_pool, wl.dtype), up(inp.rope_pool, wl.dtype)
     page_table, seq_lens = up(inp.page_table), up(inp.seq_lens)
     caches = [mlra.Cache(lat0, rope0, page_table, seq_lens)]
@@ -178,7 +192,7 @@ def main():
         "decode_attn_tflops": flops / (float(np.median(dec)) * 1e-6) / 1e12,
         "kernels_us": {"decode_main": main_ms * 1e3, "merge_upproj": epi_ms * 1e3, "calls": calls},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": rf.HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / rf.HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / rf.HBM_PEAK_GBS, "traffic": _measured_traffic(a.workload),
                      "kernel": "mlra decode main kernel", "algorithmic_bytes": kernel_bytes,
                      "mfma_tflops": (flops - wl.batch * wl.h * 2.0 * wl.n_blocks * wl.d_cb * wl.d_h)
                      / (main_ms * 1e-3) / 1e12 if main_ms > 0 else 0.0},

@@ -22,10 +22,10 @@ COPY_KIB = float(1 << 20)
 
 
 def _find(root, suffix):
-    hits = sorted(glob.glob(os.path.join(root, "**", "*" + suffix), recursive=True))
+    hits = sorted(glob.glob(os.path.join(root, "**", "*" + suffix), recursive=True), key=os.path.getmtime)
     if not hits:
         raise SystemExit(f"no *{suffix} under {root}")
-    return hits[0]
+    return hits[-1]   # the newest run, if the directory was reused
 
 
 def _short(name):
