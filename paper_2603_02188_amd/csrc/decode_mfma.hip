@@ -219,15 +219,20 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
   // and the lane 32 away holds the other 16.  max4 folds four more rows into a running maximum;
   // cross_max finishes both head tiles at once with two half-wave swaps (v_permlane32_swap exchanges
   // the upper half of its first operand with the lower half of its second).
-  auto max4 = [&](float mx, const f32x16& sv, int r) {
-    return fmaxf(fmaxf(fmaxf(mx, sv[r]), fmaxf(sv[r + 1], sv[r + 2])), sv[r + 3]);
+  // (v_max3 through asm: the library fmaxf would first canonicalise every operand, one more
+  // instruction each.  Its operands are score accumulators whose MFMAs retired several MFMAs earlier.)
+  auto max3 = [&](float a, float b, float c) {
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
   };
+  auto max4 = [&](float mx, const f32x16& sv, int r) { return max3(max3(mx, sv[r], sv[r + 1]), sv[r + 2], sv[r + 3]); };
   auto swap_halves = [&](float& a, float& b) {
     asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
   };
   auto cross_max = [&](float& mx0, float& mx1) {
     swap_halves(mx0, mx1);            // mx0 = {tile 0 lower, tile 1 lower}, mx1 = {tile 0 upper, tile 1 upper}
-    mx0 = fmaxf(mx0, mx1);            // lanes 0..31: column maxima of head tile 0, lanes 32..63: of head tile 1
+    mx0 = max3(mx0, mx1, mx1);        // lanes 0..31: column maxima of head tile 0, lanes 32..63: of head tile 1
     mx1 = mx0;
     swap_halves(mx0, mx1);            // mx0 = tile 0 maxima in both halves, mx1 = tile 1 maxima in both halves
   };
@@ -289,6 +294,9 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
       sa1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[1][ks], sa1, 0, 0, 0);
       if (ks == 1) asm volatile("" : : "v"(ka[0]));   // see the main loop
     }
+    // the maxima read the accumulators through asm, which the compiler's MFMA hazard bookkeeping does
+    // not see: let the last score MFMA retire first
+    asm volatile("s_nop 15\n\ts_nop 15" : "+v"(sa0), "+v"(sa1));
     float mx0, mx1;
     col_max2(sa0, sa1, mx0, mx1);
     m_run[0] = mx0 * sc;

@@ -99,9 +99,7 @@ static int decode_common(const mlra_cache* c, int batch, int h, int d_h, const v
   a.dtype = c->dtype;
   a.stream = (hipStream_t)stream;
   timing_mark(0, a.stream);
-  int st = decode_split_supported(a)  ? launch_decode_split(a)
-           : decode_mfma_supported(a) ? launch_decode_mfma(a)
-                                      : launch_decode_generic(a);
+  int st = decode_mfma_supported(a) ? launch_decode_mfma(a) : launch_decode_generic(a);
   if (st != MLRA_OK) return st;
   timing_mark(1, a.stream);
   st = merge_upproj_mfma_supported(a) ? launch_merge_upproj_mfma(a) : launch_merge_upproj_generic(a);

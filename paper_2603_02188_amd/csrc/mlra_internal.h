@@ -68,8 +68,6 @@ int launch_decode_generic(const DecodeArgs& a);
 int launch_merge_upproj_generic(const DecodeArgs& a);
 
 // Fast paths (bf16, MFMA); the *_supported predicates are false outside the shapes they were written for.
-bool decode_split_supported(const DecodeArgs& a);
-int launch_decode_split(const DecodeArgs& a);
 bool decode_mfma_supported(const DecodeArgs& a);
 int launch_decode_mfma(const DecodeArgs& a);
 bool absorb_q_mfma_supported(int d_h, int d_cb, int dtype);
