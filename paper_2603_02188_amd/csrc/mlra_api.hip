@@ -221,7 +221,15 @@ int gqa_decode_attn(const void* k_pool, const void* v_pool, const int32_t* page_
   if (h % g != 0 || h > 65535 || batch > 65535 || d_h > 1024) return MLRA_ERR_SHAPE;
   if ((long)max_pages_per_seq * page_size > 0x7fffffffL) return MLRA_ERR_SHAPE;
   GqaArgs a;
-  a.plan = plan_splits(batch, 1, max_pages_per_seq * page_size);
+  a.page_size = page_size;
+  a.h = h;
+  a.g = g;
+  a.d_h = d_h;
+  a.dtype = dtype;
+  // the MFMA kernel runs one workgroup per (sequence, KV head, chunk), the generic one splits further
+  a.plan = plan_splits(batch, g, max_pages_per_seq * page_size);
+  const bool use_mfma = gqa_mfma_supported(a);
+  if (!use_mfma) a.plan = plan_splits(batch, 1, max_pages_per_seq * page_size);
   const size_t units = (size_t)batch * a.plan.n_splits;
   const size_t need = align_up(units * h * d_h * sizeof(float), 256) + align_up(units * h * 2 * sizeof(float), 256);
   if (!workspace || workspace_bytes < need || ((uintptr_t)workspace) % 256 != 0) return MLRA_ERR_WORKSPACE;
@@ -243,7 +251,7 @@ int gqa_decode_attn(const void* k_pool, const void* v_pool, const int32_t* page_
   a.out = out;
   a.out_dtype = out_dtype;
   a.stream = (hipStream_t)stream;
-  int st = launch_gqa_generic(a);
+  int st = use_mfma ? launch_gqa_mfma(a) : launch_gqa_generic(a);
   if (st != MLRA_OK) return st;
   return launch_gqa_merge(a);
 }

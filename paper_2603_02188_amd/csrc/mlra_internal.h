@@ -92,6 +92,8 @@ struct GqaArgs {
   hipStream_t stream;
 };
 int launch_gqa_generic(const GqaArgs& a);
+bool gqa_mfma_supported(const GqaArgs& a);
+int launch_gqa_mfma(const GqaArgs& a);
 int launch_gqa_merge(const GqaArgs& a);
 
 static inline int check_launch() { return hipGetLastError() == hipSuccess ? MLRA_OK : MLRA_ERR_LAUNCH; }
