@@ -30,6 +30,8 @@ def _args():
     ap.add_argument("--copies", type=int, default=0, help="cache copies to rotate over (0 = enough for ~3 GB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--parity", action="store_true", help="also compare the GPU output with the oracle")
+    ap.add_argument("--baselines", action="store_true",
+                    help="C5 only: also time the GQA and MLA decode baselines on the same lengths and page table")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain 1 GiB device copies (reference dispatches for rocprofv3 byte counters)")
     return ap.parse_args()
@@ -79,6 +81,61 @@ def _measured_traffic(workload):
     except OSError:
         pass
     return None
+
+
+def _time_us(fn, iters):
+    import torch
+    fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / iters
+
+
+def _baselines(inp, mlra_decode_us):
+    """Decode-attention latency of the paper's comparison methods on the same batch (lengths, page table):
+    GQA with 8 KV heads (MFMA streaming kernel) and MLA with one 512-dim latent (generic fp32 kernel:
+    correct, not tuned, so its ratio says nothing about the method)."""
+    import torch
+    from paper_2603_02188_amd import binding as mlra
+    from paper_2603_02188_amd import inputs as gen
+    from paper_2603_02188_amd import roofline as rf
+    wl = inp.wl
+    dev = "cuda"
+
+    def up(x, bf16=True):
+        t = torch.from_numpy(np.ascontiguousarray(x))
+        return (t.view(torch.bfloat16) if bf16 and t.dtype == torch.uint16 else t).to(dev)
+
+    out = torch.empty((wl.batch, wl.h, wl.d_h), dtype=torch.bfloat16, device=dev)
+    gi = gen.make_gqa_inputs(wl, poison=False, seq_lens=inp.seq_lens)
+    kp, vp, q = up(gi.k_pool), up(gi.v_pool), up(gi.q)
+    pt, sl = up(gi.page_table, False), up(gi.seq_lens, False)
+    ws = torch.empty(mlra.gqa_decode_workspace_bytes(wl.batch, wl.h, wl.d_h, int(pt.shape[1]) * wl.page_size),
+                     dtype=torch.uint8, device=dev)
+    gqa_us = _time_us(lambda: mlra.gqa_decode_attn(kp, vp, pt, sl, q, gi.scale, out=out, workspace=ws), 20)
+    gqa_bytes = rf.gqa_bytes(inp.seq_lens, wl.h, wl.d_h, wl.g)
+    del kp, vp
+    inp1 = gen.as_single_latent(inp)
+    lat1, rope1 = up(inp1.latent_pool), up(inp1.rope_pool)
+    cache1 = mlra.Cache(lat1, rope1, up(inp1.page_table, False), up(inp1.seq_lens, False))
+    q_abs1 = mlra.mlra_absorb_q(up(inp1.q_nope), up(inp1.w_uk))
+    ws1 = torch.empty(mlra.mlra_decode_workspace_bytes(wl.batch, wl.h, 1, inp1.wl.d_cb, cache1.max_seq_len),
+                      dtype=torch.uint8, device=dev)
+    w_uv1, q_rope1 = up(inp1.w_uv), up(inp1.q_rope)
+    mla_us = _time_us(lambda: mlra.mla_decode_attn(cache1, q_abs1, q_rope1, w_uv1, wl.tau, out=out, workspace=ws1), 2)
+    return {"mlra4_decode_us": mlra_decode_us,
+            "gqa_decode_us": gqa_us, "gqa_over_mlra4": gqa_us / mlra_decode_us,
+            "gqa_gbps": gqa_bytes["total"] / (gqa_us * 1e-6) / 1e9,
+            "gqa_kernel": "MFMA streaming kernel",
+            "mla_decode_us": mla_us, "mla_over_mlra4": mla_us / mlra_decode_us,
+            "mla_kernel": "generic fp32 LDS kernel (correctness path, untuned)",
+            "paper_context": "H100, Section 4.3: MLRA-4 1.05-1.26x faster than GQA, about 2.8x faster than MLA "
+                             "(MLRA-4 measured as one 4-way-TP device's share)"}
 
 
 def main():
@@ -198,6 +255,11 @@ def main():
                      / (main_ms * 1e-3) / 1e12 if main_ms > 0 else 0.0},
         "input_gen_s": t_gen,
     }
+    if a.baselines:
+        if a.workload != "C5":
+            print("--baselines applies to workload C5 (the paged mixed batch)", file=sys.stderr)
+            sys.exit(2)
+        res["baselines"] = _baselines(inp, float(np.median(dec)))
     if not a.no_cpu_baseline:
         base, ref = _cpu_baseline(inp)
         res["cpu_baseline"] = base

@@ -20,6 +20,22 @@ namespace {
 
 using namespace mfma_tile;
 
+// Sequence ids sorted by length, longest first (rank sort; ties keep index order).  Used when a launch has
+// more workgroups than the chip runs at once: workgroups are dispatched in id order, so handing out
+// the long sequences first is the longest-processing-time rule and keeps the last round short.
+__global__ __launch_bounds__(256) void seq_order_kernel(const int32_t* __restrict__ seq_lens,
+                                                        int32_t* __restrict__ order, int batch) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= batch) return;
+  const int n = seq_lens[i];
+  int rank = 0;
+  for (int j = 0; j < batch; ++j) {
+    const int nj = seq_lens[j];
+    rank += (nj > n || (nj == n && j < i)) ? 1 : 0;
+  }
+  order[rank] = i;
+}
+
 template <int STAGES>
 __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
@@ -41,7 +57,8 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
     su = full_units + wg / fam;
     member = wg % fam;
   }
-  const int split = su % p.n_splits, seq = su / p.n_splits;
+  const int split = su % p.n_splits;
+  const int seq = p.seq_order ? p.seq_order[su / p.n_splits] : su / p.n_splits;
   const int blk = member / n_hg, hgrp = member % n_hg;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int hw = wave & 1, tw = wave >> 1, g = lane >> 5, c32 = lane & 31;
@@ -528,6 +545,12 @@ int launch_decode_mfma(const DecodeArgs& a) {
   const int n_hg = (a.h + kHeadsWG - 1) / kHeadsWG;
   const long long n_wg = (long long)a.plan.n_splits * a.n_blocks * n_hg * a.batch;
   if (n_wg <= 0 || n_wg > 0x7fffffffLL) return MLRA_ERR_SHAPE;
+  // more than one round of workgroups (one per CU at a time): longest sequences first
+  p.seq_order = nullptr;
+  if (n_wg > device_cu_count() && a.batch > 1 && a.batch <= 8192 && a.seq_order) {
+    seq_order_kernel<<<(a.batch + 255) / 256, 256, 0, a.stream>>>(a.seq_lens, a.seq_order, a.batch);
+    p.seq_order = a.seq_order;
+  }
   decode_mfma_kernel<kStages><<<dim3((unsigned)n_wg), 256, lds, a.stream>>>(p);
   return check_launch();
 }

@@ -29,6 +29,7 @@ struct MfmaParams {
   const bf16_t* rope;
   const int32_t* page_table;
   const int32_t* seq_lens;
+  const int32_t* seq_order;   // sequence ids in dispatch order, or null for 0, 1, 2, ...
   const bf16_t* q_abs;
   const bf16_t* q_rope;
   float* part_z;

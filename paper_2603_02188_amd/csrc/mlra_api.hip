@@ -53,7 +53,8 @@ static bool valid_dtype(int d) { return d == MLRA_BF16 || d == MLRA_F32; }
 
 static size_t decode_ws_bytes(int batch, int h, int n_blocks, int d_cb, const SplitPlan& p) {
   const size_t units = (size_t)batch * n_blocks * p.n_splits;
-  return align_up(units * h * d_cb * sizeof(float), 256) + align_up(units * h * 2 * sizeof(float), 256);
+  return align_up(units * h * d_cb * sizeof(float), 256) + align_up(units * h * 2 * sizeof(float), 256) +
+         align_up((size_t)batch * sizeof(int32_t), 256);
 }
 
 static int decode_common(const mlra_cache* c, int batch, int h, int d_h, const void* q_abs, const void* q_rope,
@@ -76,6 +77,7 @@ static int decode_common(const mlra_cache* c, int batch, int h, int d_h, const v
   const size_t units = (size_t)batch * c->n_blocks * a.plan.n_splits;
   a.part_z = (float*)workspace;
   a.part_ml = (float*)((char*)workspace + align_up(units * h * c->d_cb * sizeof(float), 256));
+  a.seq_order = (int32_t*)((char*)a.part_ml + align_up(units * h * 2 * sizeof(float), 256));
   a.latent = c->latent;
   a.rope = c->rope;
   a.page_table = c->page_table;

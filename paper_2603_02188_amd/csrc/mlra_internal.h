@@ -55,6 +55,7 @@ struct DecodeArgs {
   float* lse;
   float* part_z;   // [batch][n_blocks][n_splits][h][d_cb]
   float* part_ml;  // [batch][n_blocks][n_splits][h][2]  (running max, running sum)
+  int32_t* seq_order;  // [batch] sequence ids, longest first (workspace); filled by the MFMA launcher when used
   SplitPlan plan;
   int dtype;
   hipStream_t stream;
