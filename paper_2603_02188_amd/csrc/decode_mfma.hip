@@ -511,6 +511,14 @@ constexpr int kStages = 6;
 
 }  // namespace
 
+// Fills a.seq_order (workspace) with the sequence ids, longest first.  MLRA_ERR_SHAPE (and nothing
+// enqueued) when the batch is outside what the O(batch^2) rank sort is meant for.
+int launch_seq_order(const DecodeArgs& a) {
+  if (!a.seq_order || a.batch <= 1 || a.batch > 8192) return MLRA_ERR_SHAPE;
+  seq_order_kernel<<<(a.batch + 255) / 256, 256, 0, a.stream>>>(a.seq_lens, a.seq_order, a.batch);
+  return check_launch();
+}
+
 bool decode_mfma_supported(const DecodeArgs& a) {
   return a.dtype == MLRA_BF16 && a.d_cb == kDcb && a.d_r == kDr && a.page_size % kTile == 0 &&
          a.plan.chunk_tokens % kTile == 0;
@@ -547,10 +555,7 @@ int launch_decode_mfma(const DecodeArgs& a) {
   if (n_wg <= 0 || n_wg > 0x7fffffffLL) return MLRA_ERR_SHAPE;
   // more than one round of workgroups (one per CU at a time): longest sequences first
   p.seq_order = nullptr;
-  if (n_wg > device_cu_count() && a.batch > 1 && a.batch <= 8192 && a.seq_order) {
-    seq_order_kernel<<<(a.batch + 255) / 256, 256, 0, a.stream>>>(a.seq_lens, a.seq_order, a.batch);
-    p.seq_order = a.seq_order;
-  }
+  if (n_wg > device_cu_count() && launch_seq_order(a) == MLRA_OK) p.seq_order = a.seq_order;
   decode_mfma_kernel<kStages><<<dim3((unsigned)n_wg), 256, lds, a.stream>>>(p);
   return check_launch();
 }

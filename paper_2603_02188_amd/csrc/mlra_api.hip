@@ -31,6 +31,15 @@ int device_cu_count() {
 // Enough workgroups to cover every CU once when the batch alone cannot (the decode kernel runs one
 // workgroup per CU, and each workgroup pays a fixed start-up and write-out cost), never chunks shorter
 // than 128 tokens (a partial costs as much traffic as ~170 cached tokens of one block).
+SplitPlan plan_splits(int batch, int n_blocks, int max_seq_len);
+
+// Workgroups per (sequence, chunk): the MLRA kernels run one per latent block, the MLA kernel (one
+// 512-dim latent) one per 64 heads.
+static SplitPlan plan_decode(int batch, int h, int n_blocks, int d_cb, int max_seq_len) {
+  const int groups = (n_blocks == 1 && d_cb == 512) ? (h + 63) / 64 : n_blocks;
+  return plan_splits(batch, groups, max_seq_len);
+}
+
 SplitPlan plan_splits(int batch, int n_blocks, int max_seq_len) {
   const int kMinChunk = 128, kTile = 64;
   const long units = (long)batch * n_blocks;
@@ -70,7 +79,7 @@ static int decode_common(const mlra_cache* c, int batch, int h, int d_h, const v
   if ((long)c->n_blocks * c->d_cb > 8192 || h > 65535 || batch > 65535) return MLRA_ERR_SHAPE;
   const int max_seq_len = c->max_pages_per_seq * c->page_size;
   DecodeArgs a;
-  a.plan = plan_splits(batch, c->n_blocks, max_seq_len);
+  a.plan = plan_decode(batch, h, c->n_blocks, c->d_cb, max_seq_len);
   const size_t need = decode_ws_bytes(batch, h, c->n_blocks, c->d_cb, a.plan);
   if (!workspace || workspace_bytes < need) return MLRA_ERR_WORKSPACE;
   if (((uintptr_t)workspace) % 256 != 0) return MLRA_ERR_WORKSPACE;
@@ -101,7 +110,9 @@ static int decode_common(const mlra_cache* c, int batch, int h, int d_h, const v
   a.dtype = c->dtype;
   a.stream = (hipStream_t)stream;
   timing_mark(0, a.stream);
-  int st = decode_mfma_supported(a) ? launch_decode_mfma(a) : launch_decode_generic(a);
+  int st = decode_mfma_supported(a) ? launch_decode_mfma(a)
+           : mla_mfma_supported(a)  ? launch_mla_mfma(a)
+                                    : launch_decode_generic(a);
   if (st != MLRA_OK) return st;
   timing_mark(1, a.stream);
   st = merge_upproj_mfma_supported(a) ? launch_merge_upproj_mfma(a) : launch_merge_upproj_generic(a);
@@ -152,7 +163,7 @@ int mlra_absorb_q(int32_t batch, int32_t h, int32_t d_h, int32_t n_blocks, int32
 
 size_t mlra_decode_workspace_bytes(int32_t batch, int32_t h, int32_t n_blocks, int32_t d_cb, int32_t max_seq_len) {
   if (batch <= 0 || h <= 0 || n_blocks <= 0 || d_cb <= 0 || max_seq_len <= 0) return 0;
-  return decode_ws_bytes(batch, h, n_blocks, d_cb, plan_splits(batch, n_blocks, max_seq_len));
+  return decode_ws_bytes(batch, h, n_blocks, d_cb, plan_decode(batch, h, n_blocks, d_cb, max_seq_len));
 }
 
 int mlra_decode_attn(const mlra_cache* cache, int32_t batch, int32_t h, int32_t d_h, const void* q_abs,

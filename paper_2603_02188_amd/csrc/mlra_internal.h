@@ -69,6 +69,9 @@ int launch_decode_generic(const DecodeArgs& a);
 int launch_merge_upproj_generic(const DecodeArgs& a);
 
 // Fast paths (bf16, MFMA); the *_supported predicates are false outside the shapes they were written for.
+int launch_seq_order(const DecodeArgs& a);
+bool mla_mfma_supported(const DecodeArgs& a);
+int launch_mla_mfma(const DecodeArgs& a);
 bool decode_mfma_supported(const DecodeArgs& a);
 int launch_decode_mfma(const DecodeArgs& a);
 bool absorb_q_mfma_supported(int d_h, int d_cb, int dtype);
