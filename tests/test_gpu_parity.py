@@ -190,6 +190,71 @@ def test_gqa_baseline(dtype, tol):
     assert err <= tol and np.all(out[0] == 0)
 
 
+def _mla_reference(inp):
+    wl = inp.wl
+    v = oracle_views(inp)
+    rows = []
+    for b in range(wl.batch):
+        n = int(v["seq_lens"][b])
+        if n == 0:
+            rows.append(np.zeros((wl.h, wl.d_h)))
+            continue
+        rows.append(orc.mla_decode(v["q_nope"][b], v["q_rope"][b],
+                                   *orc.gather_sequence(v["latent_pool"], v["rope_pool"], v["page_table"][b], n),
+                                   v["w_uk"].reshape(-1, wl.h * wl.d_h), v["w_uv"].reshape(-1, wl.h * wl.d_h), wl.tau))
+    return np.stack(rows)
+
+
+@pytest.mark.parametrize("h,lens,page_size", [
+    (128, [0, 1, 31, 32, 33, 700], 64),          # empty, single token, around one 32-token tile
+    (64, [95, 96, 97, 2050], 32),                # one head group; page = tile
+    (96, [5000, 17], 256),                       # ragged head group; context split into chunks
+])
+def test_mla_baseline_edge_shapes(h, lens, page_size):
+    lens = np.array(lens, dtype=np.int32)
+    wl = gen.WORKLOADS["C5"].scaled(batch=len(lens), n_min=0, n_max=int(lens.max()), h=h, page_size=page_size)
+    inp = gen.as_single_latent(gen.make_decode_inputs(wl, seq_lens=lens))
+    cache = device_cache(inp)
+    q_nope, q_rope, w_uk, w_uv = device_queries_weights(inp)
+    q_abs = mlra.mlra_absorb_q(q_nope, w_uk)
+    out = host(mlra.mla_decode_attn(cache, q_abs, q_rope, w_uv, wl.tau, out_dtype=torch.float32))
+    ref = _mla_reference(inp)
+    err = max_rel_err(out, ref)
+    _say(f"[case] MLA baseline h={h} lens={lens.tolist()} page={page_size} max rel err {err:.3e}")
+    assert np.isfinite(out).all() and err <= 1e-2
+    for b in np.flatnonzero(lens == 0):
+        assert np.all(out[b] == 0)
+
+
+@pytest.mark.parametrize("h,g,lens,page_size", [
+    (128, 8, [1, 31, 32, 33, 127, 129, 900], 64),    # 16 query heads per KV head
+    (128, 4, [64, 65, 2000], 32),                    # 32 per KV head; page = sub-tile
+    (24, 8, [300, 1], 128),                          # 3 per KV head: mostly padding columns
+])
+def test_gqa_baseline_edge_shapes(h, g, lens, page_size):
+    lens = np.array(lens, dtype=np.int32)
+    wl = gen.WORKLOADS["C5"].scaled(batch=len(lens), n_min=1, n_max=int(lens.max()), h=h, g=g, page_size=page_size)
+    gi = gen.make_gqa_inputs(wl, seq_lens=lens)
+    out = host(mlra.gqa_decode_attn(to_device(gi.k_pool, "bf16"), to_device(gi.v_pool, "bf16"),
+                                    to_device(gi.page_table), to_device(gi.seq_lens), to_device(gi.q, "bf16"),
+                                    gi.scale, out_dtype=torch.float32))
+    ref = orc.gqa_decode_batch(gen.to_f64(gi.k_pool, "bf16"), gen.to_f64(gi.v_pool, "bf16"), gi.page_table,
+                               gi.seq_lens, gen.to_f64(gi.q, "bf16"), gi.scale)
+    err = max_rel_err(out, ref)
+    _say(f"[case] GQA baseline h={h} g={g} lens={lens.tolist()} page={page_size} max rel err {err:.3e}")
+    assert np.isfinite(out).all() and err <= 1e-2
+
+
+def test_longest_first_order_with_ties_and_empty_sequences():
+    # more workgroups than CUs (80 sequences x 4 blocks), equal lengths and empty sequences in the batch
+    lens = np.array(([0, 64, 64, 1000, 1, 513, 513, 130] * 10), dtype=np.int32)
+    wl = gen.WORKLOADS["C5"].scaled(batch=len(lens), n_min=0, n_max=1000)
+    inp = gen.make_decode_inputs(wl, seq_lens=lens)
+    out = _check_mlra(inp)
+    for b in np.flatnonzero(lens == 0):
+        assert np.all(out[b] == 0)
+
+
 def test_workspace_too_small_is_refused_on_device_pointers():
     wl = gen.WORKLOADS["C1"]
     inp = gen.make_decode_inputs(wl)
