@@ -36,6 +36,58 @@ __global__ __launch_bounds__(256) void seq_order_kernel(const int32_t* __restric
   order[rank] = i;
 }
 
+// Chunk lengths that follow the sequence lengths.  With uniform chunks a ragged batch leaves workgroups
+// idle (a sequence half as long as the longest uses half of its chunk slots); here sequence i gets
+// S_i ~ target * n_i / sum(n) chunks of ceil(n_i / S_i) tokens (rounded up to the tile, at least
+// min_chunk), so that about `target` chunks per block are active in total and they are equally long.
+// unit_tab lists the active (sequence, chunk) pairs, packed as sequence * 1024 + chunk, and -1 after
+// them: workgroup ids go round-robin over the XCDs, so the active ones must be contiguous to spread
+// evenly (scattered, they leave some XCDs with more work than CUs and others idle).
+__global__ __launch_bounds__(256) void plan_chunks_kernel(const int32_t* __restrict__ seq_lens,
+                                                          int32_t* __restrict__ chunk_tab,
+                                                          int32_t* __restrict__ unit_tab, int batch, int target,
+                                                          int max_slots, int min_chunk) {
+  __shared__ float part[256];
+  __shared__ int n_active;
+  float sum = 0.f;
+  for (int i = threadIdx.x; i < batch; i += 256) sum += (float)seq_lens[i];
+  part[threadIdx.x] = sum;
+  __syncthreads();
+  for (int s = 128; s > 0; s >>= 1) {
+    if (threadIdx.x < s) part[threadIdx.x] += part[threadIdx.x + s];
+    __syncthreads();
+  }
+  const float total = part[0];
+  for (int i = threadIdx.x; i < batch; i += 256) {
+    const int n = seq_lens[i];
+    int s_i = total > 0.f ? (int)((float)target * (float)n / total + 0.5f) : 1;
+    s_i = min(max(s_i, 1), max_slots);
+    int chunk = (n + s_i - 1) / s_i;
+    chunk = max(min_chunk, (chunk + kTile - 1) / kTile * kTile);
+    chunk_tab[i] = chunk;      // ceil(n / chunk) <= s_i <= max_slots
+  }
+  __syncthreads();
+  // exclusive scan of the active chunk counts: 256 contiguous segments of sequences, one per thread
+  __shared__ int seg_sum[256];
+  const int per = (batch + 255) / 256, lo = min(batch, (int)threadIdx.x * per), hi = min(batch, lo + per);
+  int mine = 0;
+  for (int i = lo; i < hi; ++i) mine += (seq_lens[i] + chunk_tab[i] - 1) / chunk_tab[i];
+  seg_sum[threadIdx.x] = mine;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int run = 0;
+    for (int t = 0; t < 256; ++t) { const int v = seg_sum[t]; seg_sum[t] = run; run += v; }
+    n_active = run;
+  }
+  __syncthreads();
+  int u = seg_sum[threadIdx.x];
+  for (int i = lo; i < hi; ++i) {
+    const int active = (seq_lens[i] + chunk_tab[i] - 1) / chunk_tab[i];
+    for (int k = 0; k < active; ++k) unit_tab[u++] = i * 1024 + k;
+  }
+  for (int u = n_active + threadIdx.x; u < batch * max_slots; u += 256) unit_tab[u] = -1;
+}
+
 template <int STAGES>
 __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
@@ -57,8 +109,18 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
     su = full_units + wg / fam;
     member = wg % fam;
   }
-  const int split = su % p.n_splits;
-  const int seq = p.seq_order ? p.seq_order[su / p.n_splits] : su / p.n_splits;
+  int split, seq, chunk_len;
+  if (p.unit_tab) {            // chunk lengths follow the sequence lengths: active units listed first
+    const int code = p.unit_tab[su];
+    if (code < 0) return;
+    seq = code >> 10;
+    split = code & 1023;
+    chunk_len = p.chunk_tab[seq];
+  } else {
+    split = su % p.n_splits;
+    seq = p.seq_order ? p.seq_order[su / p.n_splits] : su / p.n_splits;
+    chunk_len = p.chunk;
+  }
   const int blk = member / n_hg, hgrp = member % n_hg;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int hw = wave & 1, tw = wave >> 1, g = lane >> 5, c32 = lane & 31;
@@ -83,7 +145,7 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
       asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=a"(qreg[nt][8 + ks]) : "v"(qr), "n"(ks * 32) : "memory");
   }
 
-  const int t0 = split * p.chunk;
+  const int t0 = split * chunk_len;
   // page id of the first tile, fetched before the sequence length is known (the index is in range for
   // any length)
   typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
@@ -92,7 +154,7 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
   int issue_page = pt_row[min(issue_page_idx, p.max_pages - 1)];
   const int n = ((const_i32_ptr)p.seq_lens)[seq];
   if (t0 >= n) return;
-  const int t1 = min(n, t0 + p.chunk);
+  const int t1 = min(n, t0 + chunk_len);
   const int ntiles = (t1 - t0 + kTile - 1) / kTile;
   const int nvalid_last = t1 - t0 - (ntiles - 1) * kTile;
 
@@ -511,6 +573,15 @@ constexpr int kStages = 6;
 
 }  // namespace
 
+// Fills a.chunk_tab (workspace) with per-sequence chunk lengths, see plan_chunks_kernel.
+int launch_plan_chunks(const DecodeArgs& a) {
+  if (!a.chunk_tab || !a.unit_tab || a.plan.target_chunks <= 0) return MLRA_ERR_SHAPE;
+  if (a.plan.n_splits > 1023 || a.batch > 2048) return MLRA_ERR_SHAPE;
+  plan_chunks_kernel<<<1, 256, 0, a.stream>>>(a.seq_lens, a.chunk_tab, a.unit_tab, a.batch, a.plan.target_chunks,
+                                              a.plan.n_splits, 128);
+  return check_launch();
+}
+
 // Fills a.seq_order (workspace) with the sequence ids, longest first.  MLRA_ERR_SHAPE (and nothing
 // enqueued) when the batch is outside what the O(batch^2) rank sort is meant for.
 int launch_seq_order(const DecodeArgs& a) {
@@ -555,7 +626,9 @@ int launch_decode_mfma(const DecodeArgs& a) {
   if (n_wg <= 0 || n_wg > 0x7fffffffLL) return MLRA_ERR_SHAPE;
   // more than one round of workgroups (one per CU at a time): longest sequences first
   p.seq_order = nullptr;
-  if (n_wg > device_cu_count() && launch_seq_order(a) == MLRA_OK) p.seq_order = a.seq_order;
+  p.chunk_tab = a.balanced ? a.chunk_tab : nullptr;
+  p.unit_tab = a.balanced ? a.unit_tab : nullptr;
+  if (!a.balanced && n_wg > device_cu_count() && launch_seq_order(a) == MLRA_OK) p.seq_order = a.seq_order;
   decode_mfma_kernel<kStages><<<dim3((unsigned)n_wg), 256, lds, a.stream>>>(p);
   return check_launch();
 }

@@ -30,6 +30,8 @@ struct MfmaParams {
   const int32_t* page_table;
   const int32_t* seq_lens;
   const int32_t* seq_order;   // sequence ids in dispatch order, or null for 0, 1, 2, ...
+  const int32_t* chunk_tab;   // per-sequence chunk length, or null for the uniform `chunk`
+  const int32_t* unit_tab;    // active (sequence, chunk) pairs, sequence * 1024 + chunk, then -1 (with chunk_tab)
   const bf16_t* q_abs;
   const bf16_t* q_rope;
   float* part_z;

@@ -308,6 +308,8 @@ int launch_mla_mfma(const DecodeArgs& a) {
   p.page_table = a.page_table;
   p.seq_lens = a.seq_lens;
   p.seq_order = nullptr;   // set below when the launch needs more than one round of workgroups
+  p.chunk_tab = nullptr;
+  p.unit_tab = nullptr;
   p.q_abs = (const bf16_t*)a.q_abs;
   p.q_rope = (const bf16_t*)a.q_rope;
   p.part_z = a.part_z;

@@ -37,7 +37,16 @@ SplitPlan plan_splits(int batch, int n_blocks, int max_seq_len);
 // 512-dim latent) one per 64 heads.
 static SplitPlan plan_decode(int batch, int h, int n_blocks, int d_cb, int max_seq_len) {
   const int groups = (n_blocks == 1 && d_cb == 512) ? (h + 63) / 64 : n_blocks;
-  return plan_splits(batch, groups, max_seq_len);
+  SplitPlan p = plan_splits(batch, groups, max_seq_len);
+  // Split mode on the MFMA MLRA shape with long chunks: twice the chunk slots, so that long sequences of
+  // a ragged batch can take more chunks than short ones (the decode entry decides per call whether it
+  // uses them).  The planning kernel and the round of idle slots cost a few microseconds, which only
+  // chunks of 64 tiles or more (about 70 us of work) make negligible.
+  if (d_cb == 128 && p.n_splits > 1 && p.chunk_tokens >= 4096 && 2 * p.n_splits * n_blocks <= 128) {
+    p.target_chunks = p.n_splits * batch;
+    p.n_splits *= 2;
+  }
+  return p;
 }
 
 SplitPlan plan_splits(int batch, int n_blocks, int max_seq_len) {
@@ -55,6 +64,7 @@ SplitPlan plan_splits(int batch, int n_blocks, int max_seq_len) {
   p.chunk_tokens = (int)chunk;
   p.n_splits = (int)((max_seq_len + chunk - 1) / chunk);
   if (p.n_splits < 1) p.n_splits = 1;
+  p.target_chunks = 0;
   return p;
 }
 
@@ -63,7 +73,8 @@ static bool valid_dtype(int d) { return d == MLRA_BF16 || d == MLRA_F32; }
 static size_t decode_ws_bytes(int batch, int h, int n_blocks, int d_cb, const SplitPlan& p) {
   const size_t units = (size_t)batch * n_blocks * p.n_splits;
   return align_up(units * h * d_cb * sizeof(float), 256) + align_up(units * h * 2 * sizeof(float), 256) +
-         align_up((size_t)batch * sizeof(int32_t), 256);
+         2 * align_up((size_t)batch * sizeof(int32_t), 256) +
+         align_up((size_t)batch * p.n_splits * sizeof(int32_t), 256);
 }
 
 static int decode_common(const mlra_cache* c, int batch, int h, int d_h, const void* q_abs, const void* q_rope,
@@ -87,6 +98,9 @@ static int decode_common(const mlra_cache* c, int batch, int h, int d_h, const v
   a.part_z = (float*)workspace;
   a.part_ml = (float*)((char*)workspace + align_up(units * h * c->d_cb * sizeof(float), 256));
   a.seq_order = (int32_t*)((char*)a.part_ml + align_up(units * h * 2 * sizeof(float), 256));
+  a.chunk_tab = (int32_t*)((char*)a.seq_order + align_up((size_t)batch * sizeof(int32_t), 256));
+  a.unit_tab = (int32_t*)((char*)a.chunk_tab + align_up((size_t)batch * sizeof(int32_t), 256));
+  a.balanced = false;
   a.latent = c->latent;
   a.rope = c->rope;
   a.page_table = c->page_table;
@@ -110,6 +124,9 @@ static int decode_common(const mlra_cache* c, int batch, int h, int d_h, const v
   a.dtype = c->dtype;
   a.stream = (hipStream_t)stream;
   timing_mark(0, a.stream);
+  // chunk lengths that follow the sequence lengths need both MFMA kernels (they read the table)
+  if (a.plan.target_chunks > 0 && decode_mfma_supported(a) && merge_upproj_mfma_supported(a))
+    a.balanced = launch_plan_chunks(a) == MLRA_OK;
   int st = decode_mfma_supported(a) ? launch_decode_mfma(a)
            : mla_mfma_supported(a)  ? launch_mla_mfma(a)
                                     : launch_decode_generic(a);

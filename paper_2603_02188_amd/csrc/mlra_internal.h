@@ -29,8 +29,10 @@ __device__ __forceinline__ void store_f32(bf16_t* p, size_t i, float v) { p[i] =
 // ---- context split plan -------------------------------------------------------------------------
 // Context is cut into n_splits chunks of chunk_tokens (a multiple of 64) per (sequence, block).
 struct SplitPlan {
-  int n_splits;
-  int chunk_tokens;
+  int n_splits;       // partial slots per (sequence, block) = grid extent over chunks
+  int chunk_tokens;   // uniform chunk length
+  int target_chunks;  // > 0: chunk lengths may follow the sequence lengths so that about this many chunks
+                      // per block are active in total (see launch_plan_chunks); 0: uniform chunks only
 };
 
 int device_cu_count();
@@ -56,6 +58,9 @@ struct DecodeArgs {
   float* part_z;   // [batch][n_blocks][n_splits][h][d_cb]
   float* part_ml;  // [batch][n_blocks][n_splits][h][2]  (running max, running sum)
   int32_t* seq_order;  // [batch] sequence ids, longest first (workspace); filled by the MFMA launcher when used
+  int32_t* chunk_tab;  // [batch] per-sequence chunk length (workspace); filled by launch_plan_chunks when used
+  int32_t* unit_tab;   // [batch * n_splits] active (sequence, chunk) pairs, then -1 (workspace); same
+  bool balanced;       // chunk lengths follow the sequence lengths (chunk_tab) instead of plan.chunk_tokens
   SplitPlan plan;
   int dtype;
   hipStream_t stream;
@@ -70,6 +75,7 @@ int launch_merge_upproj_generic(const DecodeArgs& a);
 
 // Fast paths (bf16, MFMA); the *_supported predicates are false outside the shapes they were written for.
 int launch_seq_order(const DecodeArgs& a);
+int launch_plan_chunks(const DecodeArgs& a);
 bool mla_mfma_supported(const DecodeArgs& a);
 int launch_mla_mfma(const DecodeArgs& a);
 bool decode_mfma_supported(const DecodeArgs& a);

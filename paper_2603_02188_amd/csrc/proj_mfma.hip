@@ -94,7 +94,7 @@ template <typename TO>
 __global__ __launch_bounds__(256) void merge_upproj_mfma_kernel(
     const float* __restrict__ part_z, const float* __restrict__ part_ml, const int32_t* __restrict__ seq_lens,
     const bf16_t* __restrict__ w_uv, TO* __restrict__ out, float* __restrict__ lse, int batch, int h, int n_blocks,
-    int d_cb, int n_splits, int chunk, float out_scale) {
+    int d_cb, int n_splits, int chunk, const int32_t* __restrict__ chunk_tab, float out_scale) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   const int R = n_blocks * d_cb;
   const int zpitch = R + 8;                               // bf16 elements per z row (+16 B against conflicts)
@@ -124,7 +124,8 @@ __global__ __launch_bounds__(256) void merge_upproj_mfma_kernel(
     const int sl = t / units_per_seq, seq = m0 + sl, k = t % n_splits;
     float2 ml = make_float2(kNegBig, 0.f);
     if (seq < batch) {
-      const int active = min(n_splits, (seq_lens[seq] + chunk - 1) / chunk);
+      const int ch = chunk_tab ? chunk_tab[seq] : chunk;
+      const int active = min(n_splits, (seq_lens[seq] + ch - 1) / ch);
       if (k < active) ml = *(const float2*)(part_ml + (((size_t)seq * units_per_seq + t % units_per_seq) * h + head) * 2);
     }
     wtab[t] = ml.x;
@@ -137,7 +138,8 @@ __global__ __launch_bounds__(256) void merge_upproj_mfma_kernel(
     const float* lrow = ltab + sl * units_per_seq + b * n_splits;
     int active = 0;
     if (seq < batch) {
-      active = min(n_splits, (seq_lens[seq] + chunk - 1) / chunk);
+      const int ch = chunk_tab ? chunk_tab[seq] : chunk;
+      active = min(n_splits, (seq_lens[seq] + ch - 1) / ch);
       float m_star = kNegBig;
       for (int k = 0; k < active; ++k) m_star = fmaxf(m_star, wrow[k]);
       float L = 0.f;
@@ -294,11 +296,11 @@ int launch_merge_upproj_mfma(const DecodeArgs& a) {
   if (a.out_dtype == MLRA_BF16)
     merge_upproj_mfma_kernel<bf16_t><<<grid, 256, lds, a.stream>>>(
         a.part_z, a.part_ml, a.seq_lens, (const bf16_t*)a.w_uv, (bf16_t*)a.out, a.lse, a.batch, a.h, a.n_blocks, a.d_cb,
-        a.plan.n_splits, a.plan.chunk_tokens, a.out_scale);
+        a.plan.n_splits, a.plan.chunk_tokens, a.balanced ? a.chunk_tab : nullptr, a.out_scale);
   else
     merge_upproj_mfma_kernel<float><<<grid, 256, lds, a.stream>>>(
         a.part_z, a.part_ml, a.seq_lens, (const bf16_t*)a.w_uv, (float*)a.out, a.lse, a.batch, a.h, a.n_blocks, a.d_cb,
-        a.plan.n_splits, a.plan.chunk_tokens, a.out_scale);
+        a.plan.n_splits, a.plan.chunk_tokens, a.balanced ? a.chunk_tab : nullptr, a.out_scale);
   return check_launch();
 }
 

@@ -255,6 +255,16 @@ def test_longest_first_order_with_ties_and_empty_sequences():
         assert np.all(out[b] == 0)
 
 
+def test_length_proportional_chunks_on_a_ragged_long_batch():
+    # split mode with chunks of 64 tiles or more: chunk lengths follow the sequence lengths (one sequence
+    # takes most of the chunk slots, one is shorter than a single chunk, one is empty)
+    lens = np.array([66000, 20000, 300, 0], dtype=np.int32)
+    wl = gen.WORKLOADS["C4"].scaled(batch=len(lens), n_min=0, n_max=int(lens.max()))
+    inp = gen.make_decode_inputs(wl, seq_lens=lens)
+    out = _check_mlra(inp)
+    assert np.all(out[3] == 0)
+
+
 def test_workspace_too_small_is_refused_on_device_pointers():
     wl = gen.WORKLOADS["C1"]
     inp = gen.make_decode_inputs(wl)
