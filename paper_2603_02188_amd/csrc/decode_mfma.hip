@@ -25,12 +25,15 @@ using namespace mfma_tile;
 // the long sequences first is the longest-processing-time rule and keeps the last round short.
 __global__ __launch_bounds__(256) void seq_order_kernel(const int32_t* __restrict__ seq_lens,
                                                         int32_t* __restrict__ order, int batch) {
+  extern __shared__ int32_t lens[];            // every length once, then the comparisons run out of LDS
+  for (int j = threadIdx.x; j < batch; j += 256) lens[j] = seq_lens[j];
+  __syncthreads();
   const int i = blockIdx.x * 256 + threadIdx.x;
   if (i >= batch) return;
-  const int n = seq_lens[i];
+  const int n = lens[i];
   int rank = 0;
   for (int j = 0; j < batch; ++j) {
-    const int nj = seq_lens[j];
+    const int nj = lens[j];
     rank += (nj > n || (nj == n && j < i)) ? 1 : 0;
   }
   order[rank] = i;
@@ -48,9 +51,16 @@ __global__ __launch_bounds__(256) void plan_chunks_kernel(const int32_t* __restr
                                                           int32_t* __restrict__ unit_tab, int batch, int target,
                                                           int max_slots, int min_chunk) {
   __shared__ float part[256];
+  __shared__ int seg_sum[256];
   __shared__ int n_active;
+  extern __shared__ int32_t tab[];             // [batch] lengths, [batch] chunk lengths
+  int32_t* lens = tab;
+  int32_t* chunks = tab + batch;
   float sum = 0.f;
-  for (int i = threadIdx.x; i < batch; i += 256) sum += (float)seq_lens[i];
+  for (int i = threadIdx.x; i < batch; i += 256) {
+    lens[i] = seq_lens[i];
+    sum += (float)lens[i];
+  }
   part[threadIdx.x] = sum;
   __syncthreads();
   for (int s = 128; s > 0; s >>= 1) {
@@ -59,19 +69,19 @@ __global__ __launch_bounds__(256) void plan_chunks_kernel(const int32_t* __restr
   }
   const float total = part[0];
   for (int i = threadIdx.x; i < batch; i += 256) {
-    const int n = seq_lens[i];
+    const int n = lens[i];
     int s_i = total > 0.f ? (int)((float)target * (float)n / total + 0.5f) : 1;
     s_i = min(max(s_i, 1), max_slots);
     int chunk = (n + s_i - 1) / s_i;
     chunk = max(min_chunk, (chunk + kTile - 1) / kTile * kTile);
-    chunk_tab[i] = chunk;      // ceil(n / chunk) <= s_i <= max_slots
+    chunks[i] = chunk;         // ceil(n / chunk) <= s_i <= max_slots
+    chunk_tab[i] = chunk;
   }
   __syncthreads();
   // exclusive scan of the active chunk counts: 256 contiguous segments of sequences, one per thread
-  __shared__ int seg_sum[256];
   const int per = (batch + 255) / 256, lo = min(batch, (int)threadIdx.x * per), hi = min(batch, lo + per);
   int mine = 0;
-  for (int i = lo; i < hi; ++i) mine += (seq_lens[i] + chunk_tab[i] - 1) / chunk_tab[i];
+  for (int i = lo; i < hi; ++i) mine += (lens[i] + chunks[i] - 1) / chunks[i];
   seg_sum[threadIdx.x] = mine;
   __syncthreads();
   if (threadIdx.x == 0) {
@@ -82,7 +92,7 @@ __global__ __launch_bounds__(256) void plan_chunks_kernel(const int32_t* __restr
   __syncthreads();
   int u = seg_sum[threadIdx.x];
   for (int i = lo; i < hi; ++i) {
-    const int active = (seq_lens[i] + chunk_tab[i] - 1) / chunk_tab[i];
+    const int active = (lens[i] + chunks[i] - 1) / chunks[i];
     for (int k = 0; k < active; ++k) unit_tab[u++] = i * 1024 + k;
   }
   for (int u = n_active + threadIdx.x; u < batch * max_slots; u += 256) unit_tab[u] = -1;
@@ -577,7 +587,7 @@ constexpr int kStages = 6;
 int launch_plan_chunks(const DecodeArgs& a) {
   if (!a.chunk_tab || !a.unit_tab || a.plan.target_chunks <= 0) return MLRA_ERR_SHAPE;
   if (a.plan.n_splits > 1023 || a.batch > 2048) return MLRA_ERR_SHAPE;
-  plan_chunks_kernel<<<1, 256, 0, a.stream>>>(a.seq_lens, a.chunk_tab, a.unit_tab, a.batch, a.plan.target_chunks,
+  plan_chunks_kernel<<<1, 256, 2 * a.batch * sizeof(int32_t), a.stream>>>(a.seq_lens, a.chunk_tab, a.unit_tab, a.batch, a.plan.target_chunks,
                                               a.plan.n_splits, 128);
   return check_launch();
 }
@@ -586,7 +596,8 @@ int launch_plan_chunks(const DecodeArgs& a) {
 // enqueued) when the batch is outside what the O(batch^2) rank sort is meant for.
 int launch_seq_order(const DecodeArgs& a) {
   if (!a.seq_order || a.batch <= 1 || a.batch > 8192) return MLRA_ERR_SHAPE;
-  seq_order_kernel<<<(a.batch + 255) / 256, 256, 0, a.stream>>>(a.seq_lens, a.seq_order, a.batch);
+  seq_order_kernel<<<(a.batch + 255) / 256, 256, a.batch * sizeof(int32_t), a.stream>>>(a.seq_lens, a.seq_order,
+                                                                                       a.batch);
   return check_launch();
 }
 
