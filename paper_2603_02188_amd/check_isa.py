@@ -1,8 +1,9 @@
 """Scans generated gfx950 assembly for MFMA register overlaps that the hardware does not allow.
 
-A multi-pass MFMA whose destination is not tied to its accumulator input (srcC is a constant) must
-not write registers it still reads as srcA / srcB.  The build runs this over every kernel's assembly
-and fails if such an instruction was emitted.
+An MFMA with a destination wider than four registers must not write registers it still reads as srcA /
+srcB (the narrow forms, 16x16 results of four registers, read their operands before the first write and
+may overlap).  The build runs this over every kernel's assembly and fails if such an instruction was
+emitted.
 """
 from __future__ import annotations
 
@@ -23,6 +24,8 @@ def find_overlaps(asm_text: str):
         if not m:
             continue
         dst = (m.group(1), int(m.group(2)), int(m.group(3)))
+        if dst[2] - dst[1] + 1 <= 4:
+            continue
         src_a = (m.group(4), int(m.group(5)), int(m.group(6)))
         src_b = (m.group(7), int(m.group(8)), int(m.group(9)))
         if _overlap(dst, src_a) or _overlap(dst, src_b):

@@ -272,7 +272,20 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
     }
   }
 
-  float m_run[2] = {kNegBig, kNegBig}, l_run[2] = {0.f, 0.f};
+  float m_run[2] = {kNegBig, kNegBig};
+  // Row sums l = sum_t P[t][head] come from the matrix pipe as well: one 16x16x32 MFMA per P^T operand
+  // with a 0/1 selector as A.  Read as a 16x16x32 B operand, lane (16 b + c) of a P^T register holds head
+  // c + 16 (b & 1), eight tokens; selector row 4 q has ones where (b & 1) == (q & 1), every other row is
+  // zero, so accumulator register 0 of lane (16 q + c) ends up with the sum over the operand's 16 tokens
+  // of that lane's own head, both token halves included.
+  f32x4 lacc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+  bf16x8 row_sel;
+  {
+    const int i = lane & 15, b = lane >> 4;
+    const __bf16 v = ((i & 3) == 0 && ((i >> 2) & 1) == (b & 1)) ? (__bf16)1.0f : (__bf16)0.0f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) row_sel[e] = v;
+  }
   f32x16 zacc[4][2];
 #pragma unroll
   for (int mt = 0; mt < 4; ++mt)
@@ -336,22 +349,22 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
     for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
       for (int i = 0; i < 16; ++i) zacc[mt][nt][i] *= alpha;
-    l_run[nt] *= alpha;
+    lacc[nt][0] *= alpha;
     m_run[nt] = m_new;
   };
-  // P^T = 2^(s*sc - m) for two consecutive accumulator rows of head tile nt (prob_exp), the row sum in
-  // fp32 (prob_sum) and the rounding to bf16 into the PV B operand (prob_pack): three pieces, so that
-  // they can sit behind different MFMAs.
+  // P^T = 2^(s*sc - m) for two consecutive accumulator rows of head tile nt (prob_exp) and the rounding
+  // to bf16 into the PV B operand (prob_pack): two pieces, so that they can sit behind different MFMAs.
   auto prob_exp = [&](int nt, const f32x16& sv, int r, float& p0, float& p1) {
     const float neg_m = -m_run[nt];
     p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[r], sc, neg_m));
     p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[r + 1], sc, neg_m));
     asm volatile("" : "+v"(p0), "+v"(p1));   // computed here, not sunk to the first use
   };
-  auto prob_sum = [&](int nt, float p0, float p1) {
-    l_run[nt] += p0;
-    l_run[nt] += p1;
-    asm volatile("" : "+v"(l_run[nt]));
+  // (asm, so that the sums and the selector live in accumulation registers while every other MFMA result
+  // stays in the ordinary file.  The operands were written by VALU instructions many cycles earlier; the
+  // next access to acc is the same instruction eight 32x32 MFMAs later, or the step's end.)
+  auto row_sum_mfma = [&](f32x4& acc, const bf16x8& pt) {
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "a"(row_sel), "v"(pt));
   };
   auto prob_pack = [&](int r, float p0, float p1, bf16x8 (&pb)[2]) {
     bf16x2 pp = {(__bf16)p0, (__bf16)p1};
@@ -419,8 +432,8 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
     bf16x8 va[2][4], pb0[2], pb1[2];
     __builtin_amdgcn_sched_barrier(0);
     // ---- block A: 24 score MFMAs.  MFMA i < 16 carries the exponentials of probability pair i (pairs
-    // 0..7: head tile 0, 8..15: head tile 1) and the row-sum update of pair i-1; MFMA 16+q carries the
-    // bf16 packing of pairs 2q, 2q+1 and the LDS transpose reads of V operand q.
+    // 0..7: head tile 0, 8..15: head tile 1); MFMA 16+q carries the bf16 packing of pairs 2q, 2q+1 and
+    // the LDS transpose reads of V operand q.
 #pragma unroll
     for (int i = 0; i < 16; ++i) { n0[i] = 0.f; n1[i] = 0.f; }
     float pr[32];
@@ -436,7 +449,6 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
         if (i < 8) prob_exp(0, c0, 2 * i, pr[2 * i], pr[2 * i + 1]);
         else prob_exp(1, c1, 2 * (i - 8), pr[2 * i], pr[2 * i + 1]);
       }
-      if (i >= 1 && i <= 16) prob_sum((i - 1) >> 3, pr[2 * (i - 1)], pr[2 * (i - 1) + 1]);
       if (i >= 16) {
         const int q = i - 16;
 #pragma unroll
@@ -456,6 +468,10 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
       const int ss = m >> 3, mt = (m >> 1) & 3;
       if ((m & 1) == 0) zacc[mt][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[ss][mt], pb0[ss], zacc[mt][0], 0, 0, 0);
       else zacc[mt][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[ss][mt], pb1[ss], zacc[mt][1], 0, 0, 0);
+      if (m == 0 || m == 8) {
+        row_sum_mfma(lacc[0], pb0[ss]);
+        row_sum_mfma(lacc[1], pb1[ss]);
+      }
       if (m == 1) {
         // this wave's LDS reads of V(j) have returned (so has everything older) before it tells the
         // others that the stage may be overwritten
@@ -466,7 +482,9 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
       }
       if (FAST && m >= 2 && m <= 4) { issue_full_part(2 * (m - 2)); issue_full_part(2 * (m - 2) + 1); }
       if (FAST && m == 5) issue_end();
-      if (m >= 4) load_k_part(st_k2, m - 4, ka);
+      // (the last K read is three MFMAs from the end of the step: the first wait of the next step, which
+      // covers every LDS read because a scalar load is in flight, then finds them all returned)
+      if (m >= 2 && m <= 13) load_k_part(st_k2, m - 2, ka);
       if (m == 6) mx0 = max4(max4(n0[0], n0, 0), n0, 4);
       if (m == 8) mx0 = max4(max4(mx0, n0, 8), n0, 12);
       if (m == 10) mx1 = max4(max4(n1[0], n1, 0), n1, 4);
@@ -499,8 +517,9 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
   }
 
   // ---- merge the two token halves of each head half through LDS, write the chunk's partial ----
+  float l_run[2];
 #pragma unroll
-  for (int nt = 0; nt < 2; ++nt) l_run[nt] += __shfl_xor(l_run[nt], 32);
+  for (int nt = 0; nt < 2; ++nt) l_run[nt] = lacc[nt][0];   // already summed over both token halves of the wave
   __builtin_amdgcn_s_barrier();     // every wave is past its last tile read: the stages can be reused
   float* mbuf = (float*)smem;                 // [4 waves][64 heads]
   float* lbuf = mbuf + 256;
