@@ -13,6 +13,10 @@ What each function follows (all citations are to the MLRA paper):
   * mlra_decode_absorbed    -- the three steps per block, block outputs summed (Eq. (5)),
     times the output rescale alpha_attn of Eq. (10).
   * mla_decode              -- the same with a single block of d_c channels (Section 2.1).
+  * mlra2_decode_unabsorbed -- Eq. (6) (MLRA-2) with the group map gamma(i) and the group matrices
+    W^(gamma),UK / W^(gamma),UV of Section 2.3 (GLA-2), for the single decode query.
+  * mlra2_absorb_q / mlra2_decode_absorbed -- the three absorbed steps applied to each of
+    the two branches of Eq. (6); each latent block serves the h/2 heads of its group.
   * gqa_decode              -- Appendix C, MQA/GQA: query head i reads KV head floor(i/r),
     r = h/g.
   * round_bf16 / append_kv / gather_sequence -- storage conventions of this build (the paper
@@ -22,7 +26,9 @@ What each function follows (all citations are to the MLRA paper):
 Pins: every function above is pinned in tests/test_oracle_pins.py against something other
 than itself (Eq. (2) identity, a library SDPA on materialised K/V, closed forms for n = 1,
 two tokens, zero queries and constant caches, split/merge and permutation invariances,
-brute-force Python loops on tiny inputs, hand-picked bf16 rounding cases).
+brute-force Python loops on tiny inputs, hand-picked bf16 rounding cases; for MLRA-2 a
+brute-force evaluation of Eq. (6), the GLA-2 value identity at n = 1, the head-group
+independence and a library SDPA per branch).
 The paper prints no numeric attention example, so there is no printed value to reproduce.
 """
 from __future__ import annotations
@@ -153,6 +159,93 @@ def mla_decode(q_nope, q_rope, C, KR, W_UK, W_UV, tau):
 
 
 # --------------------------------------------------------------------------------------
+# Eq. (6), MLRA-2.  Group map and group matrices as in Section 2.3 (GLA-2): head i belongs to
+# group gamma(i) = 0 for i < h/2, else 1, with in-group index i_bar = i - gamma(i) h/2; group
+# gamma owns latent blocks 2 gamma and 2 gamma + 1 and matrices W^(gamma) in R^{2 d_cb x (h/2) d_h};
+# W^(gamma)_(j),(i) = W^(gamma)[j d_cb:(j+1) d_cb, i_bar d_h:(i_bar+1) d_h].
+# --------------------------------------------------------------------------------------
+def gamma(i: int, h: int) -> int:
+    return 0 if i < h // 2 else 1
+
+
+def wg_block(W_g: np.ndarray, j: int, i_bar: int, d_cb: int, d_h: int) -> np.ndarray:
+    """W^(gamma)_(j),(i) from one group's matrix W_g [2*d_cb][(h/2)*d_h]."""
+    return W_g[j * d_cb:(j + 1) * d_cb, i_bar * d_h:(i_bar + 1) * d_h]
+
+
+def mlra2_decode_unabsorbed(q_nope, q_rope, C, KR, W_UK_g, W_UV_g, tau, out_scale=1.0):
+    """O_i = out_scale * sum_{j=0,1} Softmax(tau q^N_i (C_(2g+j) W^(g),UK_(j),(i))^T + tau q^R_i KR^T)
+                                      (C_(2g+j) W^(g),UV_(j),(i)),   g = gamma(i).
+
+    q_nope [h][d_h], q_rope [h][d_r], C [n][4*d_cb], KR [n][d_r], W_UK_g / W_UV_g [2][2*d_cb][(h/2)*d_h].
+    Returns O [h][d_h] (zeros when n == 0).
+    """
+    q_nope = np.asarray(q_nope, np.float64)
+    q_rope = np.asarray(q_rope, np.float64)
+    C = np.asarray(C, np.float64)
+    KR = np.asarray(KR, np.float64)
+    W_UK_g = np.asarray(W_UK_g, np.float64)
+    W_UV_g = np.asarray(W_UV_g, np.float64)
+    h, d_h = q_nope.shape
+    n, d_c = C.shape
+    d_cb = d_c // 4
+    O = np.zeros((h, d_h))
+    if n == 0:
+        return O
+    for i in range(h):
+        g = gamma(i, h)
+        i_bar = i - g * (h // 2)
+        acc = np.zeros(d_h)
+        for j in range(2):
+            C_b = c_block(C, 2 * g + j, d_cb)
+            K_bi = C_b @ wg_block(W_UK_g[g], j, i_bar, d_cb, d_h)              # [n][d_h]
+            V_bi = C_b @ wg_block(W_UV_g[g], j, i_bar, d_cb, d_h)
+            s = tau * (K_bi @ q_nope[i]) + tau * (KR @ q_rope[i])
+            acc = acc + softmax_1d(s) @ V_bi
+        O[i] = out_scale * acc
+    return O
+
+
+def mlra2_absorb_q(q_nope, W_UK_g):
+    """Step 1 on each branch of Eq. (6): q~_b[i_bar] = W^(g),UK_(j),(i) q^N_i for block b = 2g + j.
+    Returns [4][h/2][d_cb] (rows of block b are the heads of group b // 2 in order)."""
+    q_nope = np.asarray(q_nope, np.float64)
+    W_UK_g = np.asarray(W_UK_g, np.float64)
+    h, d_h = q_nope.shape
+    hg = h // 2
+    d_cb = W_UK_g.shape[1] // 2
+    out = np.zeros((4, hg, d_cb))
+    for g in range(2):
+        for j in range(2):
+            W = W_UK_g[g][j * d_cb:(j + 1) * d_cb].reshape(d_cb, hg, d_h)      # [c][i_bar][p]
+            out[2 * g + j] = np.einsum("hp,chp->hc", q_nope[g * hg:(g + 1) * hg], W)
+    return out
+
+
+def mlra2_decode_absorbed(q_nope, q_rope, C, KR, W_UK_g, W_UV_g, tau, out_scale=1.0, return_lse=False):
+    """Eq. (6) through the absorbed three-step form; branch j = 0 is added before j = 1.
+    lse is [4][h/2], indexed like mlra2_absorb_q's result."""
+    q_nope = np.asarray(q_nope, np.float64)
+    q_rope = np.asarray(q_rope, np.float64)
+    C = np.asarray(C, np.float64)
+    W_UV_g = np.asarray(W_UV_g, np.float64)
+    h, d_h = q_nope.shape
+    hg = h // 2
+    d_cb = C.shape[1] // 4
+    q_abs = mlra2_absorb_q(q_nope, W_UK_g)
+    O = np.zeros((h, d_h))
+    lse = np.zeros((4, hg))
+    for g in range(2):
+        heads = slice(g * hg, (g + 1) * hg)
+        for j in range(2):
+            b = 2 * g + j
+            Z_b, lse[b] = latent_attention(q_abs[b], q_rope[heads], c_block(C, b, d_cb), KR, tau)
+            O[heads] = O[heads] + up_project(Z_b, W_UV_g[g][j * d_cb:(j + 1) * d_cb], hg, d_h)
+    O = out_scale * O
+    return (O, lse) if return_lse else O
+
+
+# --------------------------------------------------------------------------------------
 # Appendix C, MQA/GQA
 # --------------------------------------------------------------------------------------
 def gqa_decode(q, K, V, scale):
@@ -268,6 +361,28 @@ def mlra_decode_batch(latent_pool, rope_pool, page_table, seq_lens, q_nope, q_ro
         C, KR = gather_sequence(latent_pool, rope_pool, page_table[b], int(seq_lens[b]))
         O[k], L[k] = mlra_decode_absorbed(q_nope[b], q_rope[b], C, KR, W_UK, W_UV, NB, tau,
                                           out_scale, return_lse=True)
+    return (O, L) if return_lse else O
+
+
+def mlra2_decode_batch(latent_pool, rope_pool, page_table, seq_lens, q_nope, q_rope, w_uk, w_uv,
+                       tau, out_scale=1.0, seqs=None, return_lse=False):
+    """Runs mlra2_decode_absorbed for the listed sequences (default: all).
+
+    w_uk / w_uv are [4][d_cb][(h/2)*d_h]: blocks 2g and 2g+1 stacked are group g's matrix
+    W^(g) of Section 2.3.  Returns O [len(seqs)][h][d_h] (and lse [len(seqs)][4][h/2]).
+    """
+    NB, d_cb = latent_pool.shape[1], latent_pool.shape[3]
+    assert NB == 4
+    h, d_h = q_nope.shape[1], q_nope.shape[2]
+    W_UK_g = np.asarray(w_uk, np.float64).reshape(2, 2 * d_cb, (h // 2) * d_h)
+    W_UV_g = np.asarray(w_uv, np.float64).reshape(2, 2 * d_cb, (h // 2) * d_h)
+    seqs = list(range(len(seq_lens))) if seqs is None else list(seqs)
+    O = np.zeros((len(seqs), h, d_h))
+    L = np.zeros((len(seqs), NB, h // 2))
+    for k, b in enumerate(seqs):
+        C, KR = gather_sequence(latent_pool, rope_pool, page_table[b], int(seq_lens[b]))
+        O[k], L[k] = mlra2_decode_absorbed(q_nope[b], q_rope[b], C, KR, W_UK_g, W_UV_g, tau,
+                                           out_scale, return_lse=True)
     return (O, L) if return_lse else O
 
 

@@ -349,3 +349,139 @@ def test_pins_detect_planted_mistakes(monkeypatch):
         monkeypatch.setattr(orc, name, bad)
         assert np.max(np.abs(run() - good)) > 1e-4, why
         monkeypatch.undo()
+
+
+# =========================================================================================
+# MLRA-2 (Eq. (6)): group map gamma(i), group matrices W^(gamma) of Section 2.3
+# =========================================================================================
+def _rand_case2(seed, n, h, d_h, d_cb, d_r):
+    rng = np.random.default_rng(seed)
+    return dict(
+        q_nope=rng.standard_normal((h, d_h)),
+        q_rope=rng.standard_normal((h, d_r)),
+        C=rng.standard_normal((n, 4 * d_cb)),
+        KR=rng.standard_normal((n, d_r)),
+        W_UK_g=rng.standard_normal((2, 2 * d_cb, (h // 2) * d_h)) / math.sqrt(d_cb),
+        W_UV_g=rng.standard_normal((2, 2 * d_cb, (h // 2) * d_h)) / math.sqrt(d_cb),
+        tau=1.0 / math.sqrt(d_h + d_r),
+    )
+
+
+def _m2_args(c):
+    return (c["q_nope"], c["q_rope"], c["C"], c["KR"], c["W_UK_g"], c["W_UV_g"], c["tau"])
+
+
+def test_mlra2_unabsorbed_vs_scalar_loops():
+    """Eq. (6) written out with scalar sums: head i uses latent blocks 2 gamma(i) and 2 gamma(i) + 1, rows
+    j d_cb.. of its group's matrices, columns i_bar d_h.. ."""
+    n, h, d_h, d_cb, d_r = 4, 4, 3, 2, 2
+    c = _rand_case2(61, n, h, d_h, d_cb, d_r)
+    qn, qr, C, KR, WK, WV, tau = _m2_args(c)
+    expect = [[0.0] * d_h for _ in range(h)]
+    for i in range(h):
+        grp = 0 if i < h // 2 else 1
+        ib = i - grp * (h // 2)
+        for j in range(2):
+            blk = 2 * grp + j
+            logits = []
+            for t in range(n):
+                s = 0.0
+                for p in range(d_h):
+                    k_tp = sum(C[t][blk * d_cb + cc] * WK[grp][j * d_cb + cc][ib * d_h + p] for cc in range(d_cb))
+                    s += qn[i][p] * k_tp
+                for u in range(d_r):
+                    s += qr[i][u] * KR[t][u]
+                logits.append(tau * s)
+            mx = max(logits)
+            w = [math.exp(x - mx) for x in logits]
+            tot = sum(w)
+            for p in range(d_h):
+                for t in range(n):
+                    v_tp = sum(C[t][blk * d_cb + cc] * WV[grp][j * d_cb + cc][ib * d_h + p] for cc in range(d_cb))
+                    expect[i][p] += w[t] / tot * v_tp
+    got = orc.mlra2_decode_unabsorbed(*_m2_args(c))
+    assert np.max(np.abs(got - np.array(expect))) <= 1e-12
+
+
+def test_mlra2_absorbed_equals_unabsorbed():
+    c = _rand_case2(62, 29, 6, 8, 8, 4)
+    a, lse = orc.mlra2_decode_absorbed(*_m2_args(c), return_lse=True)
+    u = orc.mlra2_decode_unabsorbed(*_m2_args(c))
+    assert np.max(np.abs(a - u)) <= 1e-10 * max(1.0, np.max(np.abs(u)))
+    assert lse.shape == (4, 3) and np.all(np.isfinite(lse))
+
+
+def test_mlra2_single_token_is_the_gla2_value():
+    """n = 1: every softmax is 1, so O_i = C_(2g) W^(g),UV_(0),(i) + C_(2g+1) W^(g),UV_(1),(i), which by
+    Eq. (4) is GLA-2's value row [C_(2g), C_(2g+1)] W^(g),UV_(:),(i)."""
+    h, d_h, d_cb, d_r = 6, 5, 4, 2
+    c = _rand_case2(63, 1, h, d_h, d_cb, d_r)
+    got = orc.mlra2_decode_unabsorbed(*_m2_args(c))
+    for i in range(h):
+        grp = i // (h // 2)
+        ib = i % (h // 2)
+        latent_g = c["C"][0, 2 * grp * d_cb:(2 * grp + 2) * d_cb]                     # [2 d_cb]
+        v = latent_g @ c["W_UV_g"][grp][:, ib * d_h:(ib + 1) * d_h]
+        assert np.max(np.abs(got[i] - v)) <= 1e-12
+
+
+def test_mlra2_branches_against_library_sdpa():
+    """Each branch is ordinary attention with keys [C_b W^UK | K^RoPE] and values C_b W^UV (Eq. (6))."""
+    n, h, d_h, d_cb, d_r = 23, 4, 8, 8, 4
+    c = _rand_case2(64, n, h, d_h, d_cb, d_r)
+    q = np.concatenate([c["q_nope"], c["q_rope"]], axis=1)                            # [h][d_h + d_r]
+    total = np.zeros((h, d_h))
+    for j in range(2):
+        K = np.zeros((h, n, d_h + d_r))
+        V = np.zeros((h, n, d_h))
+        for i in range(h):
+            grp, ib = i // (h // 2), i % (h // 2)
+            C_b = c["C"][:, (2 * grp + j) * d_cb:(2 * grp + j + 1) * d_cb]
+            K[i, :, :d_h] = C_b @ c["W_UK_g"][grp][j * d_cb:(j + 1) * d_cb, ib * d_h:(ib + 1) * d_h]
+            K[i, :, d_h:] = c["KR"]
+            V[i] = C_b @ c["W_UV_g"][grp][j * d_cb:(j + 1) * d_cb, ib * d_h:(ib + 1) * d_h]
+        total += _sdpa(q, K, V, c["tau"])
+    got = orc.mlra2_decode_unabsorbed(*_m2_args(c), out_scale=0.5)
+    assert np.max(np.abs(got - 0.5 * total)) <= 1e-10
+
+
+def test_mlra2_groups_do_not_interact():
+    """Heads of group 0 never see blocks 2, 3 or group 1's matrices, and vice versa."""
+    c = _rand_case2(65, 17, 4, 4, 4, 2)
+    base = orc.mlra2_decode_absorbed(*_m2_args(c))
+    d = dict(c)
+    d["C"] = c["C"].copy()
+    d["C"][:, 2 * 4:] = 7.0                                   # blocks 2 and 3
+    d["W_UK_g"] = c["W_UK_g"].copy(); d["W_UK_g"][1] *= -3.0
+    d["W_UV_g"] = c["W_UV_g"].copy(); d["W_UV_g"][1] += 1.0
+    other = orc.mlra2_decode_absorbed(*_m2_args(d))
+    assert np.array_equal(base[:2], other[:2])
+    assert not np.allclose(base[2:], other[2:])
+
+
+def test_mlra2_reduces_to_two_block_mlra_per_group():
+    """Group g alone is Eq. (5) with two branches: heads of the group, blocks 2g and 2g+1, W^(g)."""
+    n, h, d_h, d_cb, d_r = 13, 6, 4, 4, 2
+    c = _rand_case2(66, n, h, d_h, d_cb, d_r)
+    got = orc.mlra2_decode_absorbed(*_m2_args(c))
+    hg = h // 2
+    for grp in range(2):
+        sub = orc.mlra_decode_unabsorbed(c["q_nope"][grp * hg:(grp + 1) * hg], c["q_rope"][grp * hg:(grp + 1) * hg],
+                                         c["C"][:, 2 * grp * d_cb:(2 * grp + 2) * d_cb], c["KR"],
+                                         c["W_UK_g"][grp], c["W_UV_g"][grp], 2, c["tau"])
+        assert np.max(np.abs(got[grp * hg:(grp + 1) * hg] - sub)) <= 1e-10
+
+
+def test_mlra2_zero_query_gives_the_mean_value_and_empty_context_zero():
+    n, h, d_h, d_cb, d_r = 9, 4, 3, 4, 2
+    c = _rand_case2(67, n, h, d_h, d_cb, d_r)
+    c["q_nope"][:] = 0.0
+    c["q_rope"][:] = 0.0
+    got = orc.mlra2_decode_absorbed(*_m2_args(c))
+    for i in range(h):
+        grp, ib = i // (h // 2), i % (h // 2)
+        mean_latent = c["C"][:, 2 * grp * d_cb:(2 * grp + 2) * d_cb].mean(axis=0)
+        assert np.max(np.abs(got[i] - mean_latent @ c["W_UV_g"][grp][:, ib * d_h:(ib + 1) * d_h])) <= 1e-12
+    e = dict(c); e["C"] = c["C"][:0]; e["KR"] = c["KR"][:0]
+    out, lse = orc.mlra2_decode_absorbed(*_m2_args(e), return_lse=True)
+    assert np.all(out == 0.0) and np.all(np.isneginf(lse))
