@@ -116,6 +116,29 @@ MLRA_API int mla_decode_attn(const mlra_cache* cache, int32_t batch, int32_t h, 
                     const void* q_rope, const void* w_uv, float softmax_scale, void* out, int32_t out_dtype,
                     float* lse, void* workspace, size_t workspace_bytes, void* stream);
 
+/* MLRA-2 (Eq. (6)) on the same cache.  Heads are cut into two groups by the map gamma of Section 2.3
+ * (gamma(i) = 0 for i < h/2, else 1; i_bar = i - gamma(i) h/2) and the latent blocks likewise: group g
+ * owns blocks [g n_blocks/2, (g+1) n_blocks/2), i.e. blocks 2g and 2g+1 of the paper's four.  A block
+ * serves only the h/2 heads of its group and a head's output is the sum over its group's blocks:
+ *   out[s][i] = out_scale * sum_{b in group gamma(i)} Softmax(score_b) C_(b) W^UV_b,(i_bar)
+ * with score_b as in mlra_decode_attn.  Everything indexed by (block, head) therefore holds h/2 heads
+ * per block:
+ *   w_uk, w_uv [n_blocks][d_cb][(h/2)*d_h]   blocks 2g, 2g+1 stacked = the group matrix W^(g),UK / W^(g),UV
+ *                                            in R^{2 d_cb x (h/2) d_h}; head i in columns [i_bar d_h, +d_h)
+ *   q_abs      [batch][n_blocks][h/2][d_cb]  row i_bar of block b belongs to head i_bar + gamma h/2
+ *   lse        [batch][n_blocks][h/2]
+ *   q_nope [batch][h][d_h], q_rope [batch][h][d_r], out [batch][h][d_h] keep all h heads in order.
+ * n_blocks and h must be even.  With n_blocks = 2 (one block of 2 d_h channels per group) the same call
+ * computes GLA-2 (Eq. (3)).  mlra_append_kv is shared.  Argument conventions, workspace rules and error
+ * behaviour are those of mlra_absorb_q / mlra_decode_workspace_bytes / mlra_decode_attn. */
+MLRA_API int mlra2_absorb_q(int32_t batch, int32_t h, int32_t d_h, int32_t n_blocks, int32_t d_cb,
+                   const void* q_nope, const void* w_uk, void* q_abs, int32_t dtype, void* stream);
+MLRA_API size_t mlra2_decode_workspace_bytes(int32_t batch, int32_t h, int32_t n_blocks, int32_t d_cb,
+                                    int32_t max_seq_len);
+MLRA_API int mlra2_decode_attn(const mlra_cache* cache, int32_t batch, int32_t h, int32_t d_h, const void* q_abs,
+                      const void* q_rope, const void* w_uv, float softmax_scale, float out_scale, void* out,
+                      int32_t out_dtype, float* lse, void* workspace, size_t workspace_bytes, void* stream);
+
 /* Workspace bytes for gqa_decode_attn (0 on invalid sizes). */
 MLRA_API size_t gqa_decode_workspace_bytes(int32_t batch, int32_t h, int32_t d_h, int32_t max_seq_len);
 

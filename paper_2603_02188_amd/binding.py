@@ -20,7 +20,8 @@ _lib: Optional[ctypes.CDLL] = None
 MLRA_BF16, MLRA_F32 = 0, 1
 
 EXPORTS = ("mlra_strerror", "mlra_append_kv", "mlra_absorb_q", "mlra_decode_workspace_bytes",
-           "mlra_decode_attn", "mla_decode_attn", "gqa_decode_workspace_bytes", "gqa_decode_attn", "mlra_kernel_timing_begin",
+           "mlra_decode_attn", "mla_decode_attn", "mlra2_absorb_q", "mlra2_decode_workspace_bytes",
+           "mlra2_decode_attn", "gqa_decode_workspace_bytes", "gqa_decode_attn", "mlra_kernel_timing_begin",
            "mlra_kernel_timing_end")
 
 
@@ -57,6 +58,12 @@ def load_library() -> ctypes.CDLL:
     lib.mlra_decode_workspace_bytes.argtypes = [i32, i32, i32, i32, i32]
     lib.mlra_decode_attn.restype = ctypes.c_int
     lib.mlra_decode_attn.argtypes = [cp, i32, i32, i32, vp, vp, vp, f32, f32, vp, i32, vp, vp, sz, vp]
+    lib.mlra2_absorb_q.restype = ctypes.c_int
+    lib.mlra2_absorb_q.argtypes = lib.mlra_absorb_q.argtypes
+    lib.mlra2_decode_workspace_bytes.restype = sz
+    lib.mlra2_decode_workspace_bytes.argtypes = lib.mlra_decode_workspace_bytes.argtypes
+    lib.mlra2_decode_attn.restype = ctypes.c_int
+    lib.mlra2_decode_attn.argtypes = lib.mlra_decode_attn.argtypes
     lib.mla_decode_attn.restype = ctypes.c_int
     lib.mla_decode_attn.argtypes = [cp, i32, i32, i32, vp, vp, vp, f32, vp, i32, vp, vp, sz, vp]
     lib.gqa_decode_workspace_bytes.restype = sz
@@ -188,6 +195,48 @@ def mla_decode_attn(cache: Cache, q_abs: torch.Tensor, q_rope: torch.Tensor, w_u
                     workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
     return _decode("mla_decode_attn", cache, q_abs, q_rope, w_uv, softmax_scale, 1.0, out, out_dtype, lse,
                    workspace, stream)
+
+
+def mlra2_absorb_q(q_nope: torch.Tensor, w_uk: torch.Tensor, q_abs: Optional[torch.Tensor] = None,
+                   stream=None) -> torch.Tensor:
+    """MLRA-2: w_uk [n_blocks][d_cb][(h/2)*d_h] -> q_abs [batch][n_blocks][h/2][d_cb]."""
+    lib = load_library()
+    batch, h, d_h = q_nope.shape
+    n_blocks, d_cb, hd = w_uk.shape
+    assert h % 2 == 0 and hd == (h // 2) * d_h and w_uk.dtype == q_nope.dtype
+    if q_abs is None:
+        q_abs = torch.empty((batch, n_blocks, h // 2, d_cb), dtype=q_nope.dtype, device=q_nope.device)
+    _check(lib.mlra2_absorb_q(batch, h, d_h, n_blocks, d_cb, _ptr(q_nope), _ptr(w_uk), _ptr(q_abs),
+                              _dt(q_nope.dtype), _stream(stream)), "mlra2_absorb_q")
+    return q_abs
+
+
+def mlra2_decode_workspace_bytes(batch: int, h: int, n_blocks: int, d_cb: int, max_seq_len: int) -> int:
+    return int(load_library().mlra2_decode_workspace_bytes(batch, h, n_blocks, d_cb, max_seq_len))
+
+
+def mlra2_decode_attn(cache: Cache, q_abs: torch.Tensor, q_rope: torch.Tensor, w_uv: torch.Tensor,
+                      softmax_scale: float, out_scale: float = 1.0, out: Optional[torch.Tensor] = None,
+                      out_dtype: Optional[torch.dtype] = None, lse: Optional[torch.Tensor] = None,
+                      workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """MLRA-2: q_abs [batch][n_blocks][h/2][d_cb], q_rope [batch][h][d_r], w_uv [n_blocks][d_cb][(h/2)*d_h],
+    lse [batch][n_blocks][h/2]; returns out [batch][h][d_h]."""
+    lib = load_library()
+    cs = cache.struct()
+    batch, n_blocks, hb, d_cb = q_abs.shape
+    h = 2 * hb
+    d_h = w_uv.shape[2] // hb
+    assert w_uv.shape == (n_blocks, d_cb, hb * d_h) and q_rope.shape[:2] == (batch, h)
+    if out is None:
+        out = torch.empty((batch, h, d_h), dtype=out_dtype or q_abs.dtype, device=q_abs.device)
+    if workspace is None:
+        need = mlra2_decode_workspace_bytes(batch, h, n_blocks, d_cb, cache.max_seq_len)
+        workspace = torch.empty(need, dtype=torch.uint8, device=q_abs.device)
+    _check(lib.mlra2_decode_attn(ctypes.byref(cs), batch, h, d_h, _ptr(q_abs), _ptr(q_rope), _ptr(w_uv),
+                                 float(softmax_scale), float(out_scale), _ptr(out), _dt(out.dtype), _ptr(lse),
+                                 _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
+           "mlra2_decode_attn")
+    return out
 
 
 def gqa_decode_workspace_bytes(batch: int, h: int, d_h: int, max_seq_len: int) -> int:

@@ -146,7 +146,8 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
   for (int nt = 0; nt < 2; ++nt) {
     const int head = min(hgrp * kHeadsWG + hw * 64 + nt * 32 + c32, p.h - 1);
     const bf16_t* qa = p.q_abs + (((size_t)seq * p.n_blocks + blk) * p.h + head) * kDcb + g * 8;
-    const bf16_t* qr = p.q_rope + ((size_t)seq * p.h + head) * kDr + g * 8;
+    const int rope_head = (blk / (p.n_blocks / p.groups)) * p.h + head;   // the head's row among all heads
+    const bf16_t* qr = p.q_rope + ((size_t)seq * p.h * p.groups + rope_head) * kDr + g * 8;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks)
       asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=a"(qreg[nt][ks]) : "v"(qa), "n"(ks * 32) : "memory");
@@ -647,6 +648,7 @@ int launch_decode_mfma(const DecodeArgs& a) {
   p.max_pages = a.max_pages;
   p.n_blocks = a.n_blocks;
   p.h = a.h;
+  p.groups = a.groups;
   p.n_splits = a.plan.n_splits;
   p.chunk = a.plan.chunk_tokens;
   p.batch = a.batch;

@@ -65,10 +65,12 @@ int launch_append_kv(const mlra_cache* c, int batch, const void* c_kv_new, const
 // ------------------------------------------------------------------------------------------------
 template <typename T>
 __global__ void absorb_q_generic_kernel(const T* q_nope, const T* w_uk, T* q_abs, int h, int d_h, int n_blocks,
-                                        int d_cb) {
+                                        int groups, int d_cb) {
   extern __shared__ float qs[];
   const int head = blockIdx.x, b = blockIdx.y, s = blockIdx.z;
-  for (int p = threadIdx.x; p < d_h; p += blockDim.x) qs[p] = load_f32(q_nope, ((size_t)s * h + head) * d_h + p);
+  const int q_head = (b / (n_blocks / groups)) * h + head;   // Eq. (6): block b serves the heads of its group
+  for (int p = threadIdx.x; p < d_h; p += blockDim.x)
+    qs[p] = load_f32(q_nope, ((size_t)s * h * groups + q_head) * d_h + p);
   __syncthreads();
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64, nwaves = blockDim.x / 64;
   for (int c = wave; c < d_cb; c += nwaves) {
@@ -80,16 +82,16 @@ __global__ void absorb_q_generic_kernel(const T* q_nope, const T* w_uk, T* q_abs
   }
 }
 
-int launch_absorb_q_generic(int batch, int h, int d_h, int n_blocks, int d_cb, const void* q_nope, const void* w_uk,
-                            void* q_abs, int dtype, hipStream_t stream) {
+int launch_absorb_q_generic(int batch, int h, int d_h, int n_blocks, int groups, int d_cb, const void* q_nope,
+                            const void* w_uk, void* q_abs, int dtype, hipStream_t stream) {
   dim3 grid(h, n_blocks, batch);
   const size_t lds = (size_t)d_h * sizeof(float);
   if (dtype == MLRA_BF16)
     absorb_q_generic_kernel<bf16_t><<<grid, 256, lds, stream>>>((const bf16_t*)q_nope, (const bf16_t*)w_uk,
-                                                                (bf16_t*)q_abs, h, d_h, n_blocks, d_cb);
+                                                                (bf16_t*)q_abs, h, d_h, n_blocks, groups, d_cb);
   else
     absorb_q_generic_kernel<float><<<grid, 256, lds, stream>>>((const float*)q_nope, (const float*)w_uk,
-                                                               (float*)q_abs, h, d_h, n_blocks, d_cb);
+                                                               (float*)q_abs, h, d_h, n_blocks, groups, d_cb);
   return check_launch();
 }
 
@@ -104,7 +106,7 @@ __global__ __launch_bounds__(256) void decode_generic_kernel(
     const T* __restrict__ latent, const T* __restrict__ rope, const int32_t* __restrict__ page_table,
     const int32_t* __restrict__ seq_lens, int page_size, int max_pages, int n_blocks, int d_cb, int d_r, int h,
     const T* __restrict__ q_abs, const T* __restrict__ q_rope, float scale_log2, float* __restrict__ part_z,
-    float* __restrict__ part_ml, int n_splits, int chunk, int HG, int TT) {
+    float* __restrict__ part_ml, int n_splits, int chunk, int HG, int TT, int groups) {
   extern __shared__ float smem[];
   const int D = d_cb + d_r, DP = D + 1;
   float* qs = smem;                 // [HG][D]
@@ -126,12 +128,13 @@ __global__ __launch_bounds__(256) void decode_generic_kernel(
   const int head0 = hg * HG;
   const int nh = min(HG, h - head0);
   const int tid = threadIdx.x;
+  const int rope_head0 = (b / (n_blocks / groups)) * h;   // first head of this block's group in q_rope
 
   for (int idx = tid; idx < nh * D; idx += 256) {
     const int hh = idx / D, k = idx % D;
     const int head = head0 + hh;
     qs[hh * D + k] = k < d_cb ? load_f32(q_abs, (((size_t)s * n_blocks + b) * h + head) * d_cb + k)
-                              : load_f32(q_rope, ((size_t)s * h + head) * d_r + (k - d_cb));
+                              : load_f32(q_rope, ((size_t)s * h * groups + rope_head0 + head) * d_r + (k - d_cb));
   }
   for (int idx = tid; idx < HG * d_cb; idx += 256) zs[idx] = 0.f;
   if (tid < HG) { ms[tid] = kNegBig; ls[tid] = 0.f; al[tid] = 1.f; }
@@ -214,12 +217,12 @@ int launch_decode_generic(const DecodeArgs& a) {
     decode_generic_kernel<bf16_t><<<grid, 256, lds_bytes(TT), a.stream>>>(
         (const bf16_t*)a.latent, (const bf16_t*)a.rope, a.page_table, a.seq_lens, a.page_size, a.max_pages,
         a.n_blocks, a.d_cb, a.d_r, a.h, (const bf16_t*)a.q_abs, (const bf16_t*)a.q_rope, scale_log2, a.part_z,
-        a.part_ml, a.plan.n_splits, a.plan.chunk_tokens, HG, TT);
+        a.part_ml, a.plan.n_splits, a.plan.chunk_tokens, HG, TT, a.groups);
   else
     decode_generic_kernel<float><<<grid, 256, lds_bytes(TT), a.stream>>>(
         (const float*)a.latent, (const float*)a.rope, a.page_table, a.seq_lens, a.page_size, a.max_pages,
         a.n_blocks, a.d_cb, a.d_r, a.h, (const float*)a.q_abs, (const float*)a.q_rope, scale_log2, a.part_z,
-        a.part_ml, a.plan.n_splits, a.plan.chunk_tokens, HG, TT);
+        a.part_ml, a.plan.n_splits, a.plan.chunk_tokens, HG, TT, a.groups);
   return check_launch();
 }
 
@@ -232,13 +235,17 @@ template <typename T, typename TO>
 __global__ __launch_bounds__(256) void merge_upproj_generic_kernel(
     const float* __restrict__ part_z, const float* __restrict__ part_ml, const int32_t* __restrict__ seq_lens,
     const T* __restrict__ w_uv, TO* __restrict__ out, float* __restrict__ lse, int h, int d_h, int n_blocks,
-    int d_cb, int n_splits, int chunk, float out_scale) {
-  extern __shared__ float zs[];  // [n_blocks*d_cb]
-  const int head = blockIdx.x, s = blockIdx.y;
+    int d_cb, int n_splits, int chunk, float out_scale, int groups) {
+  extern __shared__ float zs[];  // [bpg*d_cb]
+  // output head blockIdx.x = grp * h + head; its branches are the bpg blocks of group grp (Eq. (6);
+  // one group of all blocks is Eq. (5))
+  const int head = blockIdx.x % h, grp = blockIdx.x / h, s = blockIdx.y;
+  const int bpg = n_blocks / groups, b0 = grp * bpg;
   const int n = seq_lens[s];
   const int active = min(n_splits, (n + chunk - 1) / chunk);
   const int tid = threadIdx.x;
-  for (int b = 0; b < n_blocks; ++b) {
+  for (int bb = 0; bb < bpg; ++bb) {
+    const int b = b0 + bb;
     const size_t unit0 = ((size_t)s * n_blocks + b) * n_splits;
     float m_star = kNegBig;
     for (int k = 0; k < active; ++k) m_star = fmaxf(m_star, part_ml[((unit0 + k) * h + head) * 2]);
@@ -254,27 +261,28 @@ __global__ __launch_bounds__(256) void merge_upproj_generic_kernel(
         const float w = exp2f(part_ml[((unit0 + k) * h + head) * 2] - m_star);
         z += w * part_z[((unit0 + k) * h + head) * d_cb + c];
       }
-      zs[b * d_cb + c] = z * inv;
+      zs[bb * d_cb + c] = z * inv;
     }
     if (tid == 0 && lse) lse[((size_t)s * n_blocks + b) * h + head] = L > 0.f ? (m_star + log2f(L)) * kLn2 : -INFINITY;
   }
   __syncthreads();
-  const int d_c = n_blocks * d_cb;
+  const int d_cg = bpg * d_cb;
   const size_t ld = (size_t)h * d_h;
   for (int j = tid; j < d_h; j += 256) {
     float acc = 0.f;
-    for (int r = 0; r < d_c; ++r) acc += zs[r] * load_f32(w_uv, (size_t)r * ld + (size_t)head * d_h + j);
-    store_f32(out, ((size_t)s * h + head) * d_h + j, acc * out_scale);
+    for (int r = 0; r < d_cg; ++r)
+      acc += zs[r] * load_f32(w_uv, ((size_t)b0 * d_cb + r) * ld + (size_t)head * d_h + j);
+    store_f32(out, ((size_t)s * h * groups + blockIdx.x) * d_h + j, acc * out_scale);
   }
 }
 
 int launch_merge_upproj_generic(const DecodeArgs& a) {
-  dim3 grid(a.h, a.batch);
-  const size_t lds = (size_t)a.n_blocks * a.d_cb * sizeof(float);
+  dim3 grid(a.h * a.groups, a.batch);
+  const size_t lds = (size_t)a.n_blocks / a.groups * a.d_cb * sizeof(float);
 #define MLRA_MERGE(T, TO)                                                                                       \
   merge_upproj_generic_kernel<T, TO><<<grid, 256, lds, a.stream>>>(                                             \
       a.part_z, a.part_ml, a.seq_lens, (const T*)a.w_uv, (TO*)a.out, a.lse, a.h, a.d_h, a.n_blocks, a.d_cb,     \
-      a.plan.n_splits, a.plan.chunk_tokens, a.out_scale)
+      a.plan.n_splits, a.plan.chunk_tokens, a.out_scale, a.groups)
   if (a.dtype == MLRA_BF16 && a.out_dtype == MLRA_BF16) MLRA_MERGE(bf16_t, bf16_t);
   else if (a.dtype == MLRA_BF16) MLRA_MERGE(bf16_t, float);
   else if (a.out_dtype == MLRA_BF16) MLRA_MERGE(float, bf16_t);

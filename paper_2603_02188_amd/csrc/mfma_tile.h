@@ -37,6 +37,8 @@ struct MfmaParams {
   float* part_z;
   float* part_ml;
   int page_size, max_pages, n_blocks, h, n_splits, chunk, batch;
+  int groups;                 // head groups (Eq. (6)): block b serves the h heads of group b / (n_blocks / groups);
+                              // q_rope holds groups * h heads.  1 = every block serves every head (Eq. (5))
   float scale_log2;
 };
 

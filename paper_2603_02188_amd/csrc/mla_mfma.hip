@@ -318,6 +318,7 @@ int launch_mla_mfma(const DecodeArgs& a) {
   p.max_pages = a.max_pages;
   p.n_blocks = 1;
   p.h = a.h;
+  p.groups = a.groups;
   p.n_splits = a.plan.n_splits;
   p.chunk = a.plan.chunk_tokens;
   p.batch = a.batch;

@@ -77,9 +77,10 @@ static size_t decode_ws_bytes(int batch, int h, int n_blocks, int d_cb, const Sp
          align_up((size_t)batch * p.n_splits * sizeof(int32_t), 256);
 }
 
-static int decode_common(const mlra_cache* c, int batch, int h, int d_h, const void* q_abs, const void* q_rope,
-                         const void* w_uv, float softmax_scale, float out_scale, void* out, int out_dtype,
-                         float* lse, void* workspace, size_t workspace_bytes, void* stream) {
+// h: heads served by one block (all heads when groups == 1, the heads of one group otherwise)
+static int decode_common(const mlra_cache* c, int batch, int h, int groups, int d_h, const void* q_abs,
+                         const void* q_rope, const void* w_uv, float softmax_scale, float out_scale, void* out,
+                         int out_dtype, float* lse, void* workspace, size_t workspace_bytes, void* stream) {
   if (!c || !q_abs || !q_rope || !w_uv || !out) return MLRA_ERR_NULL;
   if (!c->latent || !c->rope || !c->page_table || !c->seq_lens) return MLRA_ERR_NULL;
   if (!valid_dtype(c->dtype) || !valid_dtype(out_dtype)) return MLRA_ERR_DTYPE;
@@ -87,7 +88,8 @@ static int decode_common(const mlra_cache* c, int batch, int h, int d_h, const v
       c->max_pages_per_seq <= 0 || c->num_pages <= 0)
     return MLRA_ERR_SHAPE;
   if ((long)c->max_pages_per_seq * c->page_size > 0x7fffffffL) return MLRA_ERR_SHAPE;
-  if ((long)c->n_blocks * c->d_cb > 8192 || h > 65535 || batch > 65535) return MLRA_ERR_SHAPE;
+  if ((long)c->n_blocks * c->d_cb > 8192 || h * groups > 65535 || batch > 65535) return MLRA_ERR_SHAPE;
+  if (c->n_blocks % groups != 0) return MLRA_ERR_SHAPE;
   const int max_seq_len = c->max_pages_per_seq * c->page_size;
   DecodeArgs a;
   a.plan = plan_decode(batch, h, c->n_blocks, c->d_cb, max_seq_len);
@@ -112,6 +114,7 @@ static int decode_common(const mlra_cache* c, int batch, int h, int d_h, const v
   a.d_r = c->d_r;
   a.batch = batch;
   a.h = h;
+  a.groups = groups;
   a.d_h = d_h;
   a.q_abs = q_abs;
   a.q_rope = q_rope;
@@ -174,8 +177,8 @@ int mlra_absorb_q(int32_t batch, int32_t h, int32_t d_h, int32_t n_blocks, int32
   if (batch <= 0 || h <= 0 || d_h <= 0 || n_blocks <= 0 || d_cb <= 0) return MLRA_ERR_SHAPE;
   if (h > 65535 || batch > 65535 || n_blocks > 65535 || d_h > 8192) return MLRA_ERR_SHAPE;
   if (absorb_q_mfma_supported(d_h, d_cb, dtype))
-    return launch_absorb_q_mfma(batch, h, d_h, n_blocks, d_cb, q_nope, w_uk, q_abs, (hipStream_t)stream);
-  return launch_absorb_q_generic(batch, h, d_h, n_blocks, d_cb, q_nope, w_uk, q_abs, dtype, (hipStream_t)stream);
+    return launch_absorb_q_mfma(batch, h, d_h, n_blocks, 1, d_cb, q_nope, w_uk, q_abs, (hipStream_t)stream);
+  return launch_absorb_q_generic(batch, h, d_h, n_blocks, 1, d_cb, q_nope, w_uk, q_abs, dtype, (hipStream_t)stream);
 }
 
 size_t mlra_decode_workspace_bytes(int32_t batch, int32_t h, int32_t n_blocks, int32_t d_cb, int32_t max_seq_len) {
@@ -186,15 +189,43 @@ size_t mlra_decode_workspace_bytes(int32_t batch, int32_t h, int32_t n_blocks, i
 int mlra_decode_attn(const mlra_cache* cache, int32_t batch, int32_t h, int32_t d_h, const void* q_abs,
                      const void* q_rope, const void* w_uv, float softmax_scale, float out_scale, void* out,
                      int32_t out_dtype, float* lse, void* workspace, size_t workspace_bytes, void* stream) {
-  return decode_common(cache, batch, h, d_h, q_abs, q_rope, w_uv, softmax_scale, out_scale, out, out_dtype, lse,
+  return decode_common(cache, batch, h, 1, d_h, q_abs, q_rope, w_uv, softmax_scale, out_scale, out, out_dtype, lse,
                        workspace, workspace_bytes, stream);
+}
+
+int mlra2_absorb_q(int32_t batch, int32_t h, int32_t d_h, int32_t n_blocks, int32_t d_cb, const void* q_nope,
+                   const void* w_uk, void* q_abs, int32_t dtype, void* stream) {
+  if (!q_nope || !w_uk || !q_abs) return MLRA_ERR_NULL;
+  if (!valid_dtype(dtype)) return MLRA_ERR_DTYPE;
+  if (batch <= 0 || h <= 0 || d_h <= 0 || n_blocks <= 0 || d_cb <= 0) return MLRA_ERR_SHAPE;
+  if (h % 2 != 0 || n_blocks % 2 != 0) return MLRA_ERR_SHAPE;
+  if (h > 65535 || batch > 65535 || n_blocks > 65535 || d_h > 8192) return MLRA_ERR_SHAPE;
+  if (absorb_q_mfma_supported(d_h, d_cb, dtype))
+    return launch_absorb_q_mfma(batch, h / 2, d_h, n_blocks, 2, d_cb, q_nope, w_uk, q_abs, (hipStream_t)stream);
+  return launch_absorb_q_generic(batch, h / 2, d_h, n_blocks, 2, d_cb, q_nope, w_uk, q_abs, dtype,
+                                 (hipStream_t)stream);
+}
+
+size_t mlra2_decode_workspace_bytes(int32_t batch, int32_t h, int32_t n_blocks, int32_t d_cb, int32_t max_seq_len) {
+  if (batch <= 0 || h <= 0 || n_blocks <= 0 || d_cb <= 0 || max_seq_len <= 0) return 0;
+  if (h % 2 != 0 || n_blocks % 2 != 0) return 0;
+  return decode_ws_bytes(batch, h / 2, n_blocks, d_cb, plan_decode(batch, h / 2, n_blocks, d_cb, max_seq_len));
+}
+
+int mlra2_decode_attn(const mlra_cache* cache, int32_t batch, int32_t h, int32_t d_h, const void* q_abs,
+                      const void* q_rope, const void* w_uv, float softmax_scale, float out_scale, void* out,
+                      int32_t out_dtype, float* lse, void* workspace, size_t workspace_bytes, void* stream) {
+  if (h <= 0 || h % 2 != 0) return MLRA_ERR_SHAPE;
+  if (cache && cache->n_blocks % 2 != 0) return MLRA_ERR_SHAPE;
+  return decode_common(cache, batch, h / 2, 2, d_h, q_abs, q_rope, w_uv, softmax_scale, out_scale, out, out_dtype,
+                       lse, workspace, workspace_bytes, stream);
 }
 
 int mla_decode_attn(const mlra_cache* cache, int32_t batch, int32_t h, int32_t d_h, const void* q_abs,
                     const void* q_rope, const void* w_uv, float softmax_scale, void* out, int32_t out_dtype,
                     float* lse, void* workspace, size_t workspace_bytes, void* stream) {
   if (cache && cache->n_blocks != 1) return MLRA_ERR_SHAPE;
-  return decode_common(cache, batch, h, d_h, q_abs, q_rope, w_uv, softmax_scale, 1.0f, out, out_dtype, lse,
+  return decode_common(cache, batch, h, 1, d_h, q_abs, q_rope, w_uv, softmax_scale, 1.0f, out, out_dtype, lse,
                        workspace, workspace_bytes, stream);
 }
 

@@ -47,7 +47,9 @@ struct DecodeArgs {
   const int32_t* page_table;
   const int32_t* seq_lens;
   int page_size, max_pages, n_blocks, d_cb, d_r;
-  int batch, h, d_h;
+  int batch, h, d_h;   // h: heads served by one block (all heads, or the heads of one group)
+  int groups;          // 1: every block serves every head (Eq. (5)); 2: block b serves the heads of group
+                       //    b / (n_blocks / 2) only (Eq. (6)); q_rope and out then hold groups * h heads
   const void* q_abs;
   const void* q_rope;
   const void* w_uv;
@@ -68,7 +70,8 @@ struct DecodeArgs {
 
 int launch_append_kv(const mlra_cache* c, int batch, const void* c_kv_new, const void* k_rope_new, int src_dtype,
                      const int32_t* positions, hipStream_t stream);
-int launch_absorb_q_generic(int batch, int h, int d_h, int n_blocks, int d_cb, const void* q_nope,
+// (h: heads per block; q_nope holds groups * h heads, block b reads those of group b / (n_blocks / groups))
+int launch_absorb_q_generic(int batch, int h, int d_h, int n_blocks, int groups, int d_cb, const void* q_nope,
                             const void* w_uk, void* q_abs, int dtype, hipStream_t stream);
 int launch_decode_generic(const DecodeArgs& a);
 int launch_merge_upproj_generic(const DecodeArgs& a);
@@ -81,8 +84,8 @@ int launch_mla_mfma(const DecodeArgs& a);
 bool decode_mfma_supported(const DecodeArgs& a);
 int launch_decode_mfma(const DecodeArgs& a);
 bool absorb_q_mfma_supported(int d_h, int d_cb, int dtype);
-int launch_absorb_q_mfma(int batch, int h, int d_h, int n_blocks, int d_cb, const void* q_nope, const void* w_uk,
-                         void* q_abs, hipStream_t stream);
+int launch_absorb_q_mfma(int batch, int h, int d_h, int n_blocks, int groups, int d_cb, const void* q_nope,
+                         const void* w_uk, void* q_abs, hipStream_t stream);
 bool merge_upproj_mfma_supported(const DecodeArgs& a);
 int launch_merge_upproj_mfma(const DecodeArgs& a);
 

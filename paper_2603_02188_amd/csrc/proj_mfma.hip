@@ -46,8 +46,10 @@ __device__ __forceinline__ short4v lds_tr16(const void* p) {
 __global__ __launch_bounds__(256) void absorb_q_mfma_kernel(const bf16_t* __restrict__ q_nope,
                                                             const bf16_t* __restrict__ w_uk,
                                                             bf16_t* __restrict__ q_abs, int batch, int h,
-                                                            int n_blocks, int d_cb) {
+                                                            int n_blocks, int groups, int d_cb) {
+  // h: heads per block; q_nope holds groups * h heads and block b reads those of its group (Eq. (6))
   const int head = blockIdx.x, b = blockIdx.y;
+  const int q_head = (b / (n_blocks / groups)) * h + head, q_heads = h * groups;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, g = lane >> 5, c32 = lane & 31;
   const size_t ldw = (size_t)h * kDh;
   for (int ct = wave; ct * 32 < d_cb; ct += 4) {
@@ -58,7 +60,7 @@ __global__ __launch_bounds__(256) void absorb_q_mfma_kernel(const bf16_t* __rest
     for (int ks = 0; ks < 8; ++ks) breg[ks] = *(const bf16x8*)(wrow + ks * 16);
     for (int m0 = 0; m0 < batch; m0 += 32) {
       const int seq = min(m0 + c32, batch - 1);
-      const bf16_t* qrow = q_nope + ((size_t)seq * h + head) * kDh + g * 8;
+      const bf16_t* qrow = q_nope + ((size_t)seq * q_heads + q_head) * kDh + g * 8;
       f32x16 acc = opaque_zero();
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
@@ -93,9 +95,12 @@ constexpr int kWRowsRegs = 512;   // W^UV rows prefetched into registers at a ti
 template <typename TO>
 __global__ __launch_bounds__(256) void merge_upproj_mfma_kernel(
     const float* __restrict__ part_z, const float* __restrict__ part_ml, const int32_t* __restrict__ seq_lens,
-    const bf16_t* __restrict__ w_uv, TO* __restrict__ out, float* __restrict__ lse, int batch, int h, int n_blocks,
+    const bf16_t* __restrict__ w_uv, TO* __restrict__ out, float* __restrict__ lse, int batch, int h, int nb_total,
     int d_cb, int n_splits, int chunk, const int32_t* __restrict__ chunk_tab, float out_scale) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  // blockIdx.z = head group (Eq. (6)); one group of all blocks is Eq. (5).  h: heads per block; this
+  // workgroup's head is h * group + head in out, and its branches are blocks [b0, b0 + n_blocks).
+  const int n_blocks = nb_total / gridDim.z, b0 = blockIdx.z * n_blocks;
   const int R = n_blocks * d_cb;
   const int zpitch = R + 8;                               // bf16 elements per z row (+16 B against conflicts)
   const int units_per_seq = n_blocks * n_splits;
@@ -110,7 +115,7 @@ __global__ __launch_bounds__(256) void merge_upproj_mfma_kernel(
 
   // ---- phase 0: thread t owns 16-byte chunk t % 16 of rows t / 16 + 16 i
   bf16x8 wreg[kWRowsRegs / 16];
-  const bf16_t* wsrc = w_uv + (size_t)(tid >> 4) * ldw + (size_t)head * kDh + (tid & 15) * 8;
+  const bf16_t* wsrc = w_uv + ((size_t)b0 * d_cb + (tid >> 4)) * ldw + (size_t)head * kDh + (tid & 15) * 8;
   auto fetch_w = [&](int row0) {
 #pragma unroll
     for (int i = 0; i < kWRowsRegs / 16; ++i)
@@ -126,7 +131,8 @@ __global__ __launch_bounds__(256) void merge_upproj_mfma_kernel(
     if (seq < batch) {
       const int ch = chunk_tab ? chunk_tab[seq] : chunk;
       const int active = min(n_splits, (seq_lens[seq] + ch - 1) / ch);
-      if (k < active) ml = *(const float2*)(part_ml + (((size_t)seq * units_per_seq + t % units_per_seq) * h + head) * 2);
+      if (k < active)
+        ml = *(const float2*)(part_ml + ((((size_t)seq * nb_total + b0) * n_splits + t % units_per_seq) * h + head) * 2);
     }
     wtab[t] = ml.x;
     ltab[t] = ml.y;
@@ -150,7 +156,7 @@ __global__ __launch_bounds__(256) void merge_upproj_mfma_kernel(
       }
       const float inv = L > 0.f ? 1.f / L : 0.f;
       for (int k = 0; k < active; ++k) wrow[k] *= inv;
-      if (lse) lse[((size_t)seq * n_blocks + b) * h + head] = L > 0.f ? (m_star + log2f(L)) * kLn2 : -INFINITY;
+      if (lse) lse[((size_t)seq * nb_total + b0 + b) * h + head] = L > 0.f ? (m_star + log2f(L)) * kLn2 : -INFINITY;
     }
     if (b == 0) act[sl] = active;
   }
@@ -173,7 +179,7 @@ __global__ __launch_bounds__(256) void merge_upproj_mfma_kernel(
       const int seq = min(m0 + sl[u], batch - 1);
       na[u] = item < n_items ? act[sl[u]] : 0;
       kmax = max(kmax, na[u]);
-      pz[u] = part_z + ((((size_t)seq * n_blocks + b) * n_splits) * h + head) * d_cb + c0;
+      pz[u] = part_z + ((((size_t)seq * nb_total + b0 + b) * n_splits) * h + head) * d_cb + c0;
       wk[u] = wtab + sl[u] * units_per_seq + b * n_splits;
 #pragma unroll
       for (int e = 0; e < 8; ++e) z[u][e] = 0.f;
@@ -255,7 +261,7 @@ __global__ __launch_bounds__(256) void merge_upproj_mfma_kernel(
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
     const int s = m0 + (r >> 2) * 8 + g * 4 + (r & 3);
-    if (s < batch) store_f32(out, ((size_t)s * h + head) * kDh + j, acc[r] * out_scale);
+    if (s < batch) store_f32(out, ((size_t)s * h * gridDim.z + blockIdx.z * h + head) * kDh + j, acc[r] * out_scale);
   }
 }
 
@@ -265,24 +271,24 @@ bool absorb_q_mfma_supported(int d_h, int d_cb, int dtype) {
   return dtype == MLRA_BF16 && d_h == kDh && d_cb % 32 == 0;
 }
 
-int launch_absorb_q_mfma(int batch, int h, int d_h, int n_blocks, int d_cb, const void* q_nope, const void* w_uk,
-                         void* q_abs, hipStream_t stream) {
+int launch_absorb_q_mfma(int batch, int h, int d_h, int n_blocks, int groups, int d_cb, const void* q_nope,
+                         const void* w_uk, void* q_abs, hipStream_t stream) {
   (void)d_h;
   dim3 grid(h, n_blocks);
   absorb_q_mfma_kernel<<<grid, 256, 0, stream>>>((const bf16_t*)q_nope, (const bf16_t*)w_uk, (bf16_t*)q_abs, batch, h,
-                                                 n_blocks, d_cb);
+                                                 n_blocks, groups, d_cb);
   return check_launch();
 }
 
 bool merge_upproj_mfma_supported(const DecodeArgs& a) {
-  return a.dtype == MLRA_BF16 && a.d_h == kDh && a.d_cb % 32 == 0 && a.n_blocks * a.d_cb <= 1024 &&
-         a.n_blocks * a.plan.n_splits <= 128;
+  return a.dtype == MLRA_BF16 && a.d_h == kDh && a.d_cb % 32 == 0 && a.n_blocks / a.groups * a.d_cb <= 1024 &&
+         a.n_blocks / a.groups * a.plan.n_splits <= 128;
 }
 
 int launch_merge_upproj_mfma(const DecodeArgs& a) {
-  const int R = a.n_blocks * a.d_cb;
+  const int bpg = a.n_blocks / a.groups, R = bpg * a.d_cb;
   const size_t lds = (size_t)kWRowsLds * 256 + (size_t)32 * (R + 8) * 2 +
-                     (size_t)64 * a.n_blocks * a.plan.n_splits * sizeof(float) + 32 * sizeof(int);
+                     (size_t)64 * bpg * a.plan.n_splits * sizeof(float) + 32 * sizeof(int);
   static bool configured = false;
   if (!configured) {
     if (hipFuncSetAttribute((const void*)merge_upproj_mfma_kernel<bf16_t>, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -292,7 +298,7 @@ int launch_merge_upproj_mfma(const DecodeArgs& a) {
       return MLRA_ERR_LAUNCH;
     configured = true;
   }
-  dim3 grid(a.h, (a.batch + 31) / 32);
+  dim3 grid(a.h, (a.batch + 31) / 32, a.groups);
   if (a.out_dtype == MLRA_BF16)
     merge_upproj_mfma_kernel<bf16_t><<<grid, 256, lds, a.stream>>>(
         a.part_z, a.part_ml, a.seq_lens, (const bf16_t*)a.w_uv, (bf16_t*)a.out, a.lse, a.batch, a.h, a.n_blocks, a.d_cb,

@@ -88,6 +88,8 @@ class Workload:
     shuffle_pages: bool = False
     spare_frac: float = 0.0
     g: int = 8            # KV heads of the GQA comparison
+    groups: int = 1       # head groups: 1 = every block serves all h heads (MLRA-4, Eq. (5));
+                          # 2 = MLRA-2 (Eq. (6)): block b serves the h/2 heads of group b // (n_blocks/2)
 
     @property
     def tau(self) -> float:
@@ -115,6 +117,9 @@ WORKLOADS: Dict[str, Workload] = {
     "C5": Workload("C5-paged-mixed-bf16", 5, batch=128, n_min=512, n_max=8192, n_blocks=4,
                    d_cb=128, d_r=64, h=128, d_h=128, dtype="bf16", shuffle_pages=True,
                    spare_frac=0.10),
+    # MLRA-2 (Eq. (6)) on the shape of C3: same cache, each block serves 64 of the 128 heads
+    "M2": Workload("M2-mlra2-bf16", 6, batch=64, n_min=8192, n_max=8192, n_blocks=4,
+                   d_cb=128, d_r=64, h=128, d_h=128, dtype="bf16", groups=2),
 }
 
 
@@ -132,8 +137,8 @@ class DecodeInputs:
     seq_lens: np.ndarray      # [B] int32
     q_nope: np.ndarray        # [B][h][d_h]
     q_rope: np.ndarray        # [B][h][d_r]
-    w_uk: np.ndarray          # [NB][d_cb][h*d_h]
-    w_uv: np.ndarray          # [NB][d_cb][h*d_h]
+    w_uk: np.ndarray          # [NB][d_cb][(h/groups)*d_h]
+    w_uv: np.ndarray          # [NB][d_cb][(h/groups)*d_h]
     c_kv_new: np.ndarray      # [B][NB*d_cb] float32, the newest token's unrounded latent
     k_rope_new: np.ndarray    # [B][d_r]     float32, the newest token's unrounded RoPE key
     positions: np.ndarray     # [B] int32 = seq_lens - 1
@@ -185,13 +190,15 @@ def draw_sequence_rows(wl: Workload, b: int, n: int):
 
 
 def draw_queries_weights(wl: Workload):
-    """q_nope, q_rope ~ N(0,1); W^UK, W^UV ~ N(0, variance 1/d_cb), all rounded to wl.dtype."""
+    """q_nope, q_rope ~ N(0,1); W^UK, W^UV ~ N(0, variance 1/d_cb), all rounded to wl.dtype.
+    With head groups (MLRA-2) a block's weight rows have columns for the heads of its group only."""
     rng = np.random.default_rng([wl.seed, 0xD44])
     q_nope = rng.standard_normal((wl.batch, wl.h, wl.d_h), dtype=np.float32)
     q_rope = rng.standard_normal((wl.batch, wl.h, wl.d_r), dtype=np.float32)
     std = np.float32(1.0 / np.sqrt(wl.d_cb))
-    w_uk = rng.standard_normal((wl.n_blocks, wl.d_cb, wl.h * wl.d_h), dtype=np.float32) * std
-    w_uv = rng.standard_normal((wl.n_blocks, wl.d_cb, wl.h * wl.d_h), dtype=np.float32) * std
+    cols = (wl.h // wl.groups) * wl.d_h
+    w_uk = rng.standard_normal((wl.n_blocks, wl.d_cb, cols), dtype=np.float32) * std
+    w_uv = rng.standard_normal((wl.n_blocks, wl.d_cb, cols), dtype=np.float32) * std
     return (to_storage(q_nope, wl.dtype), to_storage(q_rope, wl.dtype),
             to_storage(w_uk, wl.dtype), to_storage(w_uv, wl.dtype))
 

@@ -58,6 +58,17 @@ def test_null_and_shape_errors_are_reported_on_the_host():
     # MLA entry point insists on a single latent block
     assert lib.mla_decode_attn(ctypes.byref(cs2), 1, 8, 64, one, one, one, 0.1, one, 1, null, one, 1 << 30,
                                null) == -2
+    # MLRA-2 wants an even number of heads and of blocks
+    assert lib.mlra2_absorb_q(1, 7, 64, 4, 64, one, one, one, 1, null) == -2
+    assert lib.mlra2_absorb_q(1, 8, 64, 3, 64, one, one, one, 1, null) == -2
+    assert lib.mlra2_absorb_q(1, 8, 64, 4, 64, null, one, one, 1, null) == -1
+    assert lib.mlra2_decode_attn(ctypes.byref(cs2), 1, 7, 64, one, one, one, 0.1, 1.0, one, 1, null, one, 1 << 30,
+                                 null) == -2
+    cs3 = mlra._CacheStruct(256, 256, 256, 256, 4, 64, 4, 3, 64, 32, 1)
+    assert lib.mlra2_decode_attn(ctypes.byref(cs3), 1, 8, 64, one, one, one, 0.1, 1.0, one, 1, null, one, 1 << 30,
+                                 null) == -2
+    assert lib.mlra2_decode_attn(ctypes.byref(cs2), 1, 8, 64, one, one, one, 0.1, 1.0, one, 1, null, null, 0,
+                                 null) == -4
     assert lib.gqa_decode_attn(one, one, one, one, 4, 64, 4, 1, 8, 3, 64, 0, one, 0.1, one, 1, one, 1 << 30,
                                null) == -2   # h % g != 0
     assert lib.gqa_decode_attn(null, one, one, one, 4, 64, 4, 1, 8, 2, 64, 0, one, 0.1, one, 1, one, 1 << 30,
@@ -72,6 +83,10 @@ def test_workspace_sizing():
     big = mlra.mlra_decode_workspace_bytes(64, 128, 4, 128, 8192)
     assert big >= 64 * 4 * 128 * (128 + 2) * 4 and big % 256 == 0
     assert mlra.gqa_decode_workspace_bytes(2, 16, 128, 4096) >= 2 * 16 * 130 * 4
+    # MLRA-2: each block holds partials for h/2 heads
+    assert mlra.mlra2_decode_workspace_bytes(1, 7, 4, 64, 256) == 0
+    m2 = mlra.mlra2_decode_workspace_bytes(64, 128, 4, 128, 8192)
+    assert 64 * 4 * 64 * (128 + 2) * 4 <= m2 < big
 
 
 def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
