@@ -1,10 +1,10 @@
 #!/usr/bin/env python3
 """Benchmark of the MLRA-4 decode hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C3|C2|C4|C5] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C3|C2|C4|C5|M2] [--no-cpu-baseline]
 
 One "step" = mlra_append_kv + mlra_absorb_q + mlra_decode_attn over one batch of synthetic,
-seeded inputs that are already resident in HBM.  Successive steps read different copies of the
+seeded inputs that are already resident in HBM (workload M2: the MLRA-2 entry points, Eq. (6)).  Successive steps read different copies of the
 cache so that the 256 MB Infinity Cache cannot serve the reads.  Prints ONE JSON line.
 """
 from __future__ import annotations
@@ -26,7 +26,7 @@ def _args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="C3", choices=["C2", "C3", "C4", "C5"])
+    ap.add_argument("--workload", default="C3", choices=["C2", "C3", "C4", "C5", "M2"])
     ap.add_argument("--copies", type=int, default=0, help="cache copies to rotate over (0 = enough for ~3 GB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--parity", action="store_true", help="also compare the GPU output with the oracle")
@@ -54,9 +54,9 @@ def _cpu_baseline(inp, max_seconds=25.0):
     done_tokens, done_seqs = 0, 0
     t0 = time.perf_counter()
     outs = []
+    decode_batch = orc.mlra2_decode_batch if wl.groups == 2 else orc.mlra_decode_batch
     for b in range(wl.batch):
-        outs.append(orc.mlra_decode_batch(lat, rope, inp.page_table, inp.seq_lens, qn, qr, wk, wv, wl.tau,
-                                          seqs=[b])[0])
+        outs.append(decode_batch(lat, rope, inp.page_table, inp.seq_lens, qn, qr, wk, wv, wl.tau, seqs=[b])[0])
         done_tokens += int(inp.seq_lens[b])
         done_seqs += 1
         if time.perf_counter() - t0 > max_seconds:
@@ -176,19 +176,23 @@ def main():
     q_nope, q_rope = up(inp.q_nope, wl.dtype), up(inp.q_rope, wl.dtype)
     w_uk, w_uv = up(inp.w_uk, wl.dtype), up(inp.w_uv, wl.dtype)
     c_new, k_new, positions = up(inp.c_kv_new), up(inp.k_rope_new), up(inp.positions)
-    q_abs = torch.empty((wl.batch, wl.n_blocks, wl.h, wl.d_cb), dtype=q_nope.dtype, device=dev)
+    q_abs = torch.empty((wl.batch, wl.n_blocks, wl.h // wl.groups, wl.d_cb), dtype=q_nope.dtype, device=dev)
     out = torch.empty((wl.batch, wl.h, wl.d_h), dtype=torch.bfloat16, device=dev)
-    ws_bytes = mlra.mlra_decode_workspace_bytes(wl.batch, wl.h, wl.n_blocks, wl.d_cb, caches[0].max_seq_len)
+    if wl.groups == 2:   # MLRA-2 (Eq. (6))
+        absorb_q, decode_attn, ws_query = mlra.mlra2_absorb_q, mlra.mlra2_decode_attn, mlra.mlra2_decode_workspace_bytes
+    else:
+        absorb_q, decode_attn, ws_query = mlra.mlra_absorb_q, mlra.mlra_decode_attn, mlra.mlra_decode_workspace_bytes
+    ws_bytes = ws_query(wl.batch, wl.h, wl.n_blocks, wl.d_cb, caches[0].max_seq_len)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
 
     def step(i):
         c = caches[i % copies]
         mlra.mlra_append_kv(c, c_new, k_new, positions)
-        mlra.mlra_absorb_q(q_nope, w_uk, q_abs)
-        mlra.mlra_decode_attn(c, q_abs, q_rope, w_uv, wl.tau, 1.0, out=out, workspace=ws)
+        absorb_q(q_nope, w_uk, q_abs)
+        decode_attn(c, q_abs, q_rope, w_uv, wl.tau, 1.0, out=out, workspace=ws)
 
     def decode_only(i):
-        mlra.mlra_decode_attn(caches[i % copies], q_abs, q_rope, w_uv, wl.tau, 1.0, out=out, workspace=ws)
+        decode_attn(caches[i % copies], q_abs, q_rope, w_uv, wl.tau, 1.0, out=out, workspace=ws)
 
     if a.copy_calibration:
         # a plain copy of known size: 2^30 bytes read, 2^30 bytes written per dispatch
@@ -225,22 +229,23 @@ def main():
     torch.cuda.synchronize()
     dec = np.array([e0.elapsed_time(e1) for e0, e1 in evs]) * 1e3
 
-    bytes_decode = rf.decode_bytes(inp.seq_lens, wl.h, wl.d_h, wl.n_blocks, wl.d_cb, wl.d_r)
-    bytes_step = (bytes_decode["total"] + rf.absorb_bytes(wl.batch, wl.h, wl.d_h, wl.n_blocks, wl.d_cb)
+    bytes_decode = rf.decode_bytes(inp.seq_lens, wl.h, wl.d_h, wl.n_blocks, wl.d_cb, wl.d_r, groups=wl.groups)
+    bytes_step = (bytes_decode["total"] + rf.absorb_bytes(wl.batch, wl.h, wl.d_h, wl.n_blocks, wl.d_cb, groups=wl.groups)
                   + rf.append_bytes(wl.batch, wl.n_blocks, wl.d_cb, wl.d_r))
-    flops = rf.decode_flops(inp.seq_lens, wl.h, wl.d_h, wl.n_blocks, wl.d_cb, wl.d_r)
+    flops = rf.decode_flops(inp.seq_lens, wl.h, wl.d_h, wl.n_blocks, wl.d_cb, wl.d_r, groups=wl.groups)
     # dominant kernel: the context-streaming decode kernel; its algorithmic bytes are the cache rows of
     # every valid token plus the absorbed / RoPE queries (W^UV and the output belong to the epilogue)
     kernel_bytes = bytes_decode["cache"] + bytes_decode["q_abs"] + bytes_decode["q_rope"]
     achieved = kernel_bytes / (main_ms * 1e-3) / 1e9 if main_ms > 0 else 0.0
 
     res = {
-        "metric": "decode attention us/step, MLRA-4 bf16 (append_kv + absorb_q + decode_attn)",
+        "metric": "decode attention us/step, %s bf16 (append_kv + absorb_q + decode_attn)"
+                  % ("MLRA-2" if wl.groups == 2 else "MLRA-4"),
         "value": ms_per_step * 1e3, "unit": "us/step", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": wl.name, "batch": wl.batch, "context": [wl.n_min, wl.n_max], "n_blocks": wl.n_blocks,
-                   "d_cb": wl.d_cb, "d_r": wl.d_r, "h": wl.h, "d_h": wl.d_h, "page_size": wl.page_size,
+                   "d_cb": wl.d_cb, "d_r": wl.d_r, "h": wl.h, "d_h": wl.d_h, "head_groups": wl.groups, "page_size": wl.page_size,
                    "cache_copies_rotated": copies, "seed": wl.seed},
         "step_gbps": bytes_step / (ms_per_step * 1e-3) / 1e9,
         "step_frac_of_hbm_peak": bytes_step / (ms_per_step * 1e-3) / 1e9 / rf.HBM_PEAK_GBS,
@@ -252,7 +257,7 @@ def main():
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": rf.HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / rf.HBM_PEAK_GBS, "traffic": _measured_traffic(a.workload),
                      "kernel": "mlra decode main kernel", "algorithmic_bytes": kernel_bytes,
-                     "mfma_tflops": (flops - wl.batch * wl.h * 2.0 * wl.n_blocks * wl.d_cb * wl.d_h)
+                     "mfma_tflops": (flops - wl.batch * wl.h * 2.0 * (wl.n_blocks // wl.groups) * wl.d_cb * wl.d_h)
                      / (main_ms * 1e-3) / 1e12 if main_ms > 0 else 0.0},
         "input_gen_s": t_gen,
     }

@@ -11,6 +11,12 @@
 //     Z^T += V^T P^T (channels x heads); V^T comes from the row-major tile through LDS transpose reads.
 //   * Running max is updated lazily (only when it grows by more than 2^8), which is exact: the
 //     partial (m, l, z) stays self-consistent and the merge kernel normalises.
+//
+// PAIRED form, for blocks that serve 64 heads (MLRA-2, Eq. (6), at h = 128): one workgroup owns two
+// neighbouring latent blocks and 64 heads.  The head half hw of a wave becomes its block: wave (hw, tw)
+// runs block 2 pair + hw for all 64 heads on tokens [32 tw, +32).  Each wave does exactly the work it
+// does in the plain form; the tile in LDS holds both blocks' latent rows and the shared RoPE rows
+// (40 KiB per stage, four stages), so the RoPE rows are fetched once for the two branches.
 #include "mfma_tile.h"
 
 #include <type_traits>
@@ -98,15 +104,20 @@ __global__ __launch_bounds__(256) void plan_chunks_kernel(const int32_t* __restr
   for (int u = n_active + threadIdx.x; u < batch * max_slots; u += 256) unit_tab[u] = -1;
 }
 
-template <int STAGES>
+template <int STAGES, bool PAIRED>
 __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  constexpr int kBlocksWG = PAIRED ? 2 : 1;                 // latent blocks whose tiles share a stage
+  constexpr int kRopeOff = kBlocksWG * kLatBytes;           // RoPE tile behind the latent tile(s)
+  constexpr int kStageB = kRopeOff + kRopeBytes;            // 24 KiB, or 40 KiB
+  constexpr int kLoadsTile = 4 * kBlocksWG + 2;             // direct-to-LDS loads per wave and tile
+  constexpr int kHeadsPerWG = PAIRED ? 64 : kHeadsWG;
   // Workgroup -> (sequence, chunk, block, head group).  The workgroups of one (sequence, chunk) read the
   // same RoPE rows (and, across head groups, the same latent rows).  Workgroup ids go round-robin over
   // the 8 XCDs, each with its own L2, so the members of such a family are given ids 8 apart: they land
   // on one XCD at about the same time and all but the first read of a shared row hit in that L2.
-  const int n_hg = (p.h + kHeadsWG - 1) / kHeadsWG;
-  const int fam = p.n_blocks * n_hg;
+  const int n_hg = (p.h + kHeadsPerWG - 1) / kHeadsPerWG;
+  const int fam = p.n_blocks / kBlocksWG * n_hg;
   const int n_units = p.n_splits * p.batch;
   const int full_units = n_units & ~7;
   int wg = blockIdx.x, su, member;
@@ -131,9 +142,12 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
     seq = p.seq_order ? p.seq_order[su / p.n_splits] : su / p.n_splits;
     chunk_len = p.chunk;
   }
-  const int blk = member / n_hg, hgrp = member % n_hg;
+  const int hgrp = member % n_hg;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int hw = wave & 1, tw = wave >> 1, g = lane >> 5, c32 = lane & 31;
+  const int blk0 = member / n_hg * kBlocksWG;               // first (or only) block of this workgroup
+  const int blk = PAIRED ? blk0 + hw : blk0;                // this wave's block
+  const int wave_head0 = PAIRED ? hgrp * 64 : hgrp * kHeadsWG + hw * 64;   // this wave's first head
 
   // ---- absorbed + RoPE queries as MFMA B operands, resident in accumulation registers for the whole
   // chunk (MFMA reads its B operand from there directly, which leaves the architectural VGPRs to the
@@ -144,7 +158,7 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
   bf16x8 qreg[2][12];
 #pragma unroll
   for (int nt = 0; nt < 2; ++nt) {
-    const int head = min(hgrp * kHeadsWG + hw * 64 + nt * 32 + c32, p.h - 1);
+    const int head = min(wave_head0 + nt * 32 + c32, p.h - 1);
     const bf16_t* qa = p.q_abs + (((size_t)seq * p.n_blocks + blk) * p.h + head) * kDcb + g * 8;
     const int rope_head = (blk / (p.n_blocks / p.groups)) * p.h + head;   // the head's row among all heads
     const bf16_t* qr = p.q_rope + ((size_t)seq * p.h * p.groups + rope_head) * kDr + g * 8;
@@ -189,7 +203,8 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
   const unsigned wave_u = __builtin_amdgcn_readfirstlane(wave);
   const size_t lat_page_bytes = (size_t)p.n_blocks * p.page_size * (kDcb * 2);
   const size_t rope_page_bytes = (size_t)p.page_size * (kDr * 2);
-  const char* lat_blk = (const char*)p.latent + (size_t)blk * p.page_size * (kDcb * 2);
+  const size_t lat_plane_bytes = (size_t)p.page_size * (kDcb * 2);     // one block's rows inside a page
+  const char* lat_blk = (const char*)p.latent + (size_t)blk0 * lat_plane_bytes;
   int issue_slot = t0 % p.page_size;   // slot of the next tile to issue inside its page (tiles go in order)
   int issue_stage = 0;
 
@@ -205,34 +220,42 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
     // start of this tile's latent rows (block plane blk) and RoPE rows inside the page
     iss_lat = lat_blk + page * lat_page_bytes + (unsigned)issue_slot * (unsigned)(kDcb * 2);
     iss_rope = (const char*)p.rope + page * rope_page_bytes + (unsigned)issue_slot * (unsigned)(kDr * 2);
-    iss_stage = lds_base + issue_stage * kStageBytes;
+    iss_stage = lds_base + issue_stage * kStageB;
   };
-  // full tile: part 0..3 = latent loads, 4..5 = RoPE loads
+  // full tile: parts 0..3 = latent loads (PAIRED: 4..7 = the second block's), then two RoPE loads
   auto issue_full_part = [&](int part) {
-    if (part == 0) set_m0(iss_stage + wave_u * 4096);
-    if (part == 0) lds_dma16<0>(iss_lat + wave_u * 4096, lat_voff[0]);
-    if (part == 1) lds_dma16<1024>(iss_lat + wave_u * 4096, lat_voff[1]);
-    if (part == 2) lds_dma16<2048>(iss_lat + wave_u * 4096, lat_voff[2]);
-    if (part == 3) lds_dma16<3072>(iss_lat + wave_u * 4096, lat_voff[3]);
-    if (part == 4) set_m0(iss_stage + kLatBytes + wave_u * 2048);
-    if (part == 4) lds_dma16<0>(iss_rope + wave_u * 2048, rope_voff[0]);
-    if (part == 5) lds_dma16<1024>(iss_rope + wave_u * 2048, rope_voff[1]);
+    if (part < 4 * kBlocksWG) {
+      const int jb = part >> 2, q = part & 3;
+      const char* src = iss_lat + jb * lat_plane_bytes + wave_u * 4096;
+      if (q == 0) set_m0(iss_stage + jb * kLatBytes + wave_u * 4096);
+      if (q == 0) lds_dma16<0>(src, lat_voff[0]);
+      if (q == 1) lds_dma16<1024>(src, lat_voff[1]);
+      if (q == 2) lds_dma16<2048>(src, lat_voff[2]);
+      if (q == 3) lds_dma16<3072>(src, lat_voff[3]);
+    } else {
+      const int q = part - 4 * kBlocksWG;
+      if (q == 0) set_m0(iss_stage + kRopeOff + wave_u * 2048);
+      if (q == 0) lds_dma16<0>(iss_rope + wave_u * 2048, rope_voff[0]);
+      if (q == 1) lds_dma16<1024>(iss_rope + wave_u * 2048, rope_voff[1]);
+    }
   };
   // ragged end of the chunk: rows past it re-read its last row (finite values, weight 0 later).
   // Offsets are taken from the tile start so that they never go negative.
   auto issue_ragged = [&]() {
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int t = (wave * 4 + q) * 4 + (lane >> 4);          // 0..63
-      const unsigned row = (unsigned)min(t, iss_last);           // 0..last
-      set_m0(iss_stage + wave_u * 4096 + q * 1024);
-      lds_dma16<0>(iss_lat, row * (kDcb * 2) + (((lane & 15) ^ lat_swz(t)) << 4));
-    }
+    for (int jb = 0; jb < kBlocksWG; ++jb)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int t = (wave * 4 + q) * 4 + (lane >> 4);          // 0..63
+        const unsigned row = (unsigned)min(t, iss_last);           // 0..last
+        set_m0(iss_stage + jb * kLatBytes + wave_u * 4096 + q * 1024);
+        lds_dma16<0>(iss_lat + jb * lat_plane_bytes, row * (kDcb * 2) + (((lane & 15) ^ lat_swz(t)) << 4));
+      }
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
       const int t = (wave * 2 + q) * 8 + (lane >> 3);          // 0..63
       const unsigned row = (unsigned)min(t, iss_last);
-      set_m0(iss_stage + kLatBytes + wave_u * 2048 + q * 1024);
+      set_m0(iss_stage + kRopeOff + wave_u * 2048 + q * 1024);
       lds_dma16<0>(iss_rope, row * (kDr * 2) + (((lane & 7) ^ rope_swz(t)) << 4));
     }
   };
@@ -249,7 +272,7 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
     issue_begin(jj);
     if (iss_last == kTile - 1) {
 #pragma unroll
-      for (int part = 0; part < 6; ++part) issue_full_part(part);
+      for (int part = 0; part < kLoadsTile; ++part) issue_full_part(part);
     } else {
       issue_ragged();
     }
@@ -261,15 +284,16 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
   // by XORs with constants and by multiples of 2 KiB: four registers hold them all.  (Stage starts are
   // multiples of 8 KiB and the LDS buffer is 1 KiB aligned, so the XORs commute with adding them.) ----
   const int s_tok = tw * 32 + c32;
-  const unsigned k_lat_off = s_tok * (kDcb * 2) + ((g ^ lat_swz(s_tok)) << 4);                // ^ (ks << 5)
-  const unsigned k_rope_off = kLatBytes + s_tok * (kDr * 2) + ((g ^ rope_swz(s_tok)) << 4);   // ^ (ks << 5)
+  const unsigned own_lat = PAIRED ? hw * kLatBytes : 0;   // this wave's block inside a stage
+  const unsigned k_lat_off = own_lat + s_tok * (kDcb * 2) + ((g ^ lat_swz(s_tok)) << 4);      // ^ (ks << 5)
+  const unsigned k_rope_off = kRopeOff + s_tok * (kDr * 2) + ((g ^ rope_swz(s_tok)) << 4);    // ^ (ks << 5)
   unsigned v_off[2];                                                          // ^ (mt << 6), + 4096 ss
   {
     const int k = (lane & 15) >> 2, seg = lane & 3, hb = (lane >> 4) & 1;
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
       const int ta = tw * 32 + 8 * half + 4 * g + k;
-      v_off[half] = ta * (kDcb * 2) + (((2 * hb + (seg >> 1)) ^ lat_swz(ta)) << 4) + ((seg & 1) << 3);
+      v_off[half] = own_lat + ta * (kDcb * 2) + (((2 * hb + (seg >> 1)) ^ lat_swz(ta)) << 4) + ((seg & 1) << 3);
     }
   }
 
@@ -301,7 +325,7 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
   typedef const __attribute__((address_space(3))) unsigned char* lds_byte_ptr;
   // K operand ks (this wave's 32 token rows x 16 channels) of the tile in stage st
   auto load_k_part = [&](int st, int ks, bf16x8 (&ka)[12]) {
-    const unsigned base = lds_base + st * kStageBytes + (ks < 8 ? k_lat_off : k_rope_off);
+    const unsigned base = lds_base + st * kStageB + (ks < 8 ? k_lat_off : k_rope_off);
     ka[ks] = *(lds_bf16x8_ptr)(size_t)(base ^ ((ks & 7) << 5));
   };
   auto load_k = [&](int st, bf16x8 (&ka)[12]) {
@@ -310,8 +334,8 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
   };
   // transposed V operand (32 channels of tile mt x 16 of this wave's token rows) of the tile in stage st
   auto load_v_part = [&](int st, int ss, int mt, bf16x8 (&va)[2][4]) {
-    const unsigned lo_base = lds_base + st * kStageBytes + v_off[0];
-    const unsigned hi_base = lds_base + st * kStageBytes + v_off[1];
+    const unsigned lo_base = lds_base + st * kStageB + v_off[0];
+    const unsigned hi_base = lds_base + st * kStageB + v_off[1];
     const lds_byte_ptr lo_p = (lds_byte_ptr)(size_t)(lo_base ^ (mt << 6));
     const lds_byte_ptr hi_p = (lds_byte_ptr)(size_t)(hi_base ^ (mt << 6));
     const short4v lo = lds_tr16(lo_p + ss * 16 * (kDcb * 2));
@@ -382,8 +406,12 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
   };
 
   // ---- prologue: every stage gets a tile; scores and column maxima of tile 0; K operands of tile 1 ----
-  for (int jj = 0; jj < STAGES && jj < ntiles; ++jj) issue_tile(jj);
-  if (ntiles >= STAGES) wait_vmcnt<kLoadsPerTile * (STAGES - 2)>(); else wait_vmcnt<0>();
+  for (int jj = 0; jj < STAGES && jj < ntiles; ++jj) {
+    // (the 24 query loads and STAGES tiles must stay within the 63 loads the counter can hold)
+    if (24 + STAGES * kLoadsTile > 63 && jj == STAGES - 1) wait_vmcnt<(STAGES - 1) * kLoadsTile>();
+    issue_tile(jj);
+  }
+  if (ntiles >= STAGES) wait_vmcnt<kLoadsTile * (STAGES - 2)>(); else wait_vmcnt<0>();
   __builtin_amdgcn_s_barrier();   // tiles 0 and 1 landed for every wave
   f32x16 sa0, sa1, sb0, sb1;
   bf16x8 ka[12];
@@ -476,13 +504,13 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
       if (m == 1) {
         // this wave's LDS reads of V(j) have returned (so has everything older) before it tells the
         // others that the stage may be overwritten
-        if (FAST || j + STAGES - 1 <= ntiles - 1) wait_vm_lgkm<kLoadsPerTile * (STAGES - 3)>(); else wait_vm_lgkm<0>();
+        if (FAST || j + STAGES - 1 <= ntiles - 1) wait_vm_lgkm<kLoadsTile * (STAGES - 3)>(); else wait_vm_lgkm<0>();
         __builtin_amdgcn_s_barrier();
         if (FAST) issue_begin(j + STAGES);
         else if (j + STAGES < ntiles) issue_tile(j + STAGES);
       }
-      if (FAST && m >= 2 && m <= 4) { issue_full_part(2 * (m - 2)); issue_full_part(2 * (m - 2) + 1); }
-      if (FAST && m == 5) issue_end();
+      if (FAST && m >= 2 && m < 2 + kLoadsTile / 2) { issue_full_part(2 * (m - 2)); issue_full_part(2 * (m - 2) + 1); }
+      if (FAST && m == 2 + kLoadsTile / 2) issue_end();
       // (the last K read is three MFMAs from the end of the step: the first wait of the next step, which
       // covers every LDS read because a scalar load is in flight, then finds them all returned)
       if (m >= 2 && m <= 13) load_k_part(st_k2, m - 2, ka);
@@ -580,17 +608,21 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
         }
   }
   __syncthreads();
-  const size_t unit = ((size_t)seq * p.n_blocks + blk) * p.n_splits + split;
-  const int head_base = hgrp * kHeadsWG;
+  // zbuf row hl = hw * 64 + (head inside the wave's 64): plain form, 128 heads of one block; PAIRED, 64
+  // heads of block blk0 then the same 64 heads of block blk0 + 1
   for (int idx = tid; idx < kHeadsWG * (kDcb / 4); idx += 256) {
     const int hl = idx / (kDcb / 4), f4 = idx % (kDcb / 4);
-    if (head_base + hl < p.h)
-      *(f32x4*)(p.part_z + (unit * p.h + head_base + hl) * kDcb + f4 * 4) = *(const f32x4*)(zbuf + hl * kZPitch + f4 * 4);
+    const int row_blk = PAIRED ? blk0 + (hl >> 6) : blk0;
+    const int row_head = PAIRED ? hgrp * 64 + (hl & 63) : hgrp * kHeadsWG + hl;
+    const size_t row_unit = ((size_t)seq * p.n_blocks + row_blk) * p.n_splits + split;
+    if (row_head < p.h)
+      *(f32x4*)(p.part_z + (row_unit * p.h + row_head) * kDcb + f4 * 4) = *(const f32x4*)(zbuf + hl * kZPitch + f4 * 4);
   }
+  const size_t unit = ((size_t)seq * p.n_blocks + blk) * p.n_splits + split;
   if (tw == 0 && g == 0) {
 #pragma unroll
     for (int nt = 0; nt < 2; ++nt) {
-      const int head = head_base + hw * 64 + nt * 32 + c32;
+      const int head = wave_head0 + nt * 32 + c32;
       if (head < p.h) {
         p.part_ml[(unit * p.h + head) * 2 + 0] = m_out[nt];
         p.part_ml[(unit * p.h + head) * 2 + 1] = l_out[nt];
@@ -599,7 +631,8 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
   }
 }
 
-constexpr int kStages = 6;
+constexpr int kStages = 6;         // plain form: 6 x 24 KiB
+constexpr int kStagesPaired = 4;   // PAIRED form: 4 x 40 KiB = all 160 KiB of LDS
 
 }  // namespace
 
@@ -626,12 +659,20 @@ bool decode_mfma_supported(const DecodeArgs& a) {
          a.plan.chunk_tokens % kTile == 0;
 }
 
+// Blocks that serve at most 64 heads in their last 128-head group leave half of the plain form's waves
+// idle; with an even number of blocks the PAIRED form runs two blocks per workgroup instead.
+bool decode_mfma_paired(int h, int n_blocks) { return n_blocks % 2 == 0 && (h - 1) % kHeadsWG < 64; }
+
 int launch_decode_mfma(const DecodeArgs& a) {
   static bool configured = false;
-  const int lds = kStages * kStageBytes;
+  const bool paired = decode_mfma_paired(a.h, a.n_blocks);
+  const int lds = paired ? kStagesPaired * (2 * kLatBytes + kRopeBytes) : kStages * kStageBytes;
   if (!configured) {
-    if (hipFuncSetAttribute((const void*)decode_mfma_kernel<kStages>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            lds) != hipSuccess)
+    if (hipFuncSetAttribute((const void*)decode_mfma_kernel<kStages, false>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, kStages * kStageBytes) != hipSuccess ||
+        hipFuncSetAttribute((const void*)decode_mfma_kernel<kStagesPaired, true>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize,
+                            kStagesPaired * (2 * kLatBytes + kRopeBytes)) != hipSuccess)
       return MLRA_ERR_LAUNCH;
     configured = true;
   }
@@ -653,15 +694,16 @@ int launch_decode_mfma(const DecodeArgs& a) {
   p.chunk = a.plan.chunk_tokens;
   p.batch = a.batch;
   p.scale_log2 = a.softmax_scale * 1.4426950408889634f;
-  const int n_hg = (a.h + kHeadsWG - 1) / kHeadsWG;
-  const long long n_wg = (long long)a.plan.n_splits * a.n_blocks * n_hg * a.batch;
+  const int n_hg = paired ? (a.h + 63) / 64 : (a.h + kHeadsWG - 1) / kHeadsWG;
+  const long long n_wg = (long long)a.plan.n_splits * (paired ? a.n_blocks / 2 : a.n_blocks) * n_hg * a.batch;
   if (n_wg <= 0 || n_wg > 0x7fffffffLL) return MLRA_ERR_SHAPE;
   // more than one round of workgroups (one per CU at a time): longest sequences first
   p.seq_order = nullptr;
   p.chunk_tab = a.balanced ? a.chunk_tab : nullptr;
   p.unit_tab = a.balanced ? a.unit_tab : nullptr;
   if (!a.balanced && n_wg > device_cu_count() && launch_seq_order(a) == MLRA_OK) p.seq_order = a.seq_order;
-  decode_mfma_kernel<kStages><<<dim3((unsigned)n_wg), 256, lds, a.stream>>>(p);
+  if (paired) decode_mfma_kernel<kStagesPaired, true><<<dim3((unsigned)n_wg), 256, lds, a.stream>>>(p);
+  else decode_mfma_kernel<kStages, false><<<dim3((unsigned)n_wg), 256, lds, a.stream>>>(p);
   return check_launch();
 }
 

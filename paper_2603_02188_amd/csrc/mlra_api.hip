@@ -36,7 +36,8 @@ SplitPlan plan_splits(int batch, int n_blocks, int max_seq_len);
 // Workgroups per (sequence, chunk): the MLRA kernels run one per latent block, the MLA kernel (one
 // 512-dim latent) one per 64 heads.
 static SplitPlan plan_decode(int batch, int h, int n_blocks, int d_cb, int max_seq_len) {
-  const int groups = (n_blocks == 1 && d_cb == 512) ? (h + 63) / 64 : n_blocks;
+  int groups = (n_blocks == 1 && d_cb == 512) ? (h + 63) / 64 : n_blocks;
+  if (d_cb == 128 && decode_mfma_paired(h, n_blocks)) groups = n_blocks / 2;   // two blocks per workgroup
   SplitPlan p = plan_splits(batch, groups, max_seq_len);
   // Split mode on the MFMA MLRA shape with long chunks: twice the chunk slots, so that long sequences of
   // a ragged batch can take more chunks than short ones (the decode entry decides per call whether it

@@ -82,6 +82,7 @@ int launch_plan_chunks(const DecodeArgs& a);
 bool mla_mfma_supported(const DecodeArgs& a);
 int launch_mla_mfma(const DecodeArgs& a);
 bool decode_mfma_supported(const DecodeArgs& a);
+bool decode_mfma_paired(int h, int n_blocks);   // two blocks x 64 heads per workgroup instead of one x 128
 int launch_decode_mfma(const DecodeArgs& a);
 bool absorb_q_mfma_supported(int d_h, int d_cb, int dtype);
 int launch_absorb_q_mfma(int batch, int h, int d_h, int n_blocks, int groups, int d_cb, const void* q_nope,

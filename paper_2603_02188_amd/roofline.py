@@ -60,24 +60,26 @@ def arithmetic_intensity(method: str, h: int, d_h: int = 128, g: int = 8,
 
 
 def decode_bytes(seq_lens: Sequence[int], h: int, d_h: int, n_blocks: int, d_cb: int, d_r: int,
-                 elt: int = 2, out_elt: int = 2) -> dict:
+                 elt: int = 2, out_elt: int = 2, groups: int = 1) -> dict:
     """Bytes mlra_decode_attn must move once: the latent cache and the RoPE key of every valid
     token, the absorbed and RoPE queries, W^UV and the output.  Split-K partials, page-table
-    reads and RoPE re-reads are overhead and deliberately not counted."""
+    reads and RoPE re-reads are overhead and deliberately not counted.  With head groups
+    (MLRA-2, Eq. (6)) a block serves h/groups heads."""
     B = len(seq_lens)
     tokens = int(sum(int(n) for n in seq_lens))
     cache = tokens * (n_blocks * d_cb + d_r) * elt
-    q_abs = B * n_blocks * h * d_cb * elt
+    q_abs = B * n_blocks * (h // groups) * d_cb * elt
     q_rope = B * h * d_r * elt
-    w_uv = n_blocks * d_cb * h * d_h * elt
+    w_uv = n_blocks * d_cb * (h // groups) * d_h * elt
     out = B * h * d_h * out_elt
     return {"tokens": tokens, "cache": cache, "q_abs": q_abs, "q_rope": q_rope, "w_uv": w_uv,
             "out": out, "total": cache + q_abs + q_rope + w_uv + out}
 
 
-def absorb_bytes(batch: int, h: int, d_h: int, n_blocks: int, d_cb: int, elt: int = 2) -> int:
+def absorb_bytes(batch: int, h: int, d_h: int, n_blocks: int, d_cb: int, elt: int = 2, groups: int = 1) -> int:
     """Bytes of Step 1 (read q_nope and W^UK once, write the absorbed queries)."""
-    return (batch * h * d_h + n_blocks * d_cb * h * d_h + batch * n_blocks * h * d_cb) * elt
+    hb = h // groups
+    return (batch * h * d_h + n_blocks * d_cb * hb * d_h + batch * n_blocks * hb * d_cb) * elt
 
 
 def append_bytes(batch: int, n_blocks: int, d_cb: int, d_r: int, src_elt: int = 4, elt: int = 2) -> int:
@@ -85,14 +87,16 @@ def append_bytes(batch: int, n_blocks: int, d_cb: int, d_r: int, src_elt: int = 
 
 
 def decode_flops(seq_lens: Sequence[int], h: int, d_h: int, n_blocks: int, d_cb: int, d_r: int,
-                 share_rope_score: bool = False) -> float:
+                 share_rope_score: bool = False, groups: int = 1) -> float:
     """Flops of Steps 2 and 3 per decode step: per token, head and block 2 d_cb (latent score)
     + 2 d_cb (PV) + 2 d_r (RoPE score; once per token and head if shared across blocks),
-    i.e. Table 2's 4 n h d_c/4 + 2 n h d_h^R per block; plus the Step-3 up-projection."""
+    i.e. Table 2's 4 n h d_c/4 + 2 n h d_h^R per block; plus the Step-3 up-projection.
+    With head groups a head has n_blocks/groups branches (Table 2, MLRA-2 row)."""
     tokens = float(sum(int(n) for n in seq_lens))
-    rope_terms = 1 if share_rope_score else n_blocks
-    step2 = tokens * h * (n_blocks * 4.0 * d_cb + rope_terms * 2.0 * d_r)
-    step3 = len(seq_lens) * h * 2.0 * n_blocks * d_cb * d_h
+    branches = n_blocks // groups
+    rope_terms = 1 if share_rope_score else branches
+    step2 = tokens * h * (branches * 4.0 * d_cb + rope_terms * 2.0 * d_r)
+    step3 = len(seq_lens) * h * 2.0 * branches * d_cb * d_h
     return step2 + step3
 
 
