@@ -5,6 +5,8 @@
 //      contraction over all n_blocks * d_cb latent channels)
 // Both are batched over sequences as the MFMA M dimension so that each weight element is read once
 // per workgroup, and both put the head index on the grid.
+#include <type_traits>
+
 #include "mlra_internal.h"
 
 namespace mlra {
@@ -162,63 +164,80 @@ __global__ __launch_bounds__(256) void merge_upproj_mfma_kernel(
   }
   __syncthreads();
 
-  // ---- phase 1b: item = (sequence slot, 8 consecutive latent channels)
+  // ---- phase 1b: item = (valid sequence slot, 8 consecutive latent channels).  A thread takes U items
+  // at a time and KK chunks of each per round trip, U * KK = 16 (32 loads in flight): many chunks (small
+  // batches) go one item per thread with sixteen chunks in flight, one or two chunks eight items per
+  // thread.
   const int items_per_row = R / 8;
-  const int n_items = 32 * items_per_row;
-  for (int base = tid; base < n_items; base += 4 * 256) {
-    float z[4][8];
-    const float* pz[4];
-    const float* wk[4];
-    int na[4], sl[4], r0[4], kmax = 0;
+  const int n_valid = min(32, batch - m0);
+  const int n_items = n_valid * items_per_row;
+  // rows of sequences past the batch feed MFMA rows that are never stored; they only have to be finite
+  for (int t = n_items + tid; t < 32 * items_per_row; t += 256) {
+    bf16x8 zero;
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int item = base + u * 256;
-      sl[u] = min(item, n_items - 1) / items_per_row;
-      r0[u] = (min(item, n_items - 1) % items_per_row) * 8;
-      const int b = r0[u] / d_cb, c0 = r0[u] % d_cb;
-      const int seq = min(m0 + sl[u], batch - 1);
-      na[u] = item < n_items ? act[sl[u]] : 0;
-      kmax = max(kmax, na[u]);
-      pz[u] = part_z + ((((size_t)seq * nb_total + b0 + b) * n_splits) * h + head) * d_cb + c0;
-      wk[u] = wtab + sl[u] * units_per_seq + b * n_splits;
+    for (int e = 0; e < 8; ++e) zero[e] = (__bf16)0.0f;
+    *(bf16x8*)(zt + (t / items_per_row) * zpitch + (t % items_per_row) * 8) = zero;
+  }
+  const size_t z_stride = (size_t)h * d_cb;
+  auto merge_items = [&](auto u_tag) {
+    constexpr int U = decltype(u_tag)::value, KK = 16 / U;
+    for (int base = tid; base < n_items; base += U * 256) {
+      float z[U][8];
+      const float* pz[U];
+      const float* wk[U];
+      int na[U], sl[U], r0[U], kmax = 0;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) z[u][e] = 0.f;
-    }
-    const size_t z_stride = (size_t)h * d_cb;
-    for (int k0 = 0; k0 < kmax; k0 += 4) {   // 4 chunks x 4 items = up to 32 loads in flight
-      f32x4 lo[4][4], hi[4][4];
-      float w[4][4];
+      for (int u = 0; u < U; ++u) {
+        const int item = base + u * 256;
+        sl[u] = min(item, n_items - 1) / items_per_row;
+        r0[u] = (min(item, n_items - 1) % items_per_row) * 8;
+        const int b = r0[u] / d_cb, c0 = r0[u] % d_cb;
+        na[u] = item < n_items ? act[sl[u]] : 0;
+        kmax = max(kmax, na[u]);
+        pz[u] = part_z + ((((size_t)(m0 + sl[u]) * nb_total + b0 + b) * n_splits) * h + head) * d_cb + c0;
+        wk[u] = wtab + sl[u] * units_per_seq + b * n_splits;
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk)
+        for (int e = 0; e < 8; ++e) z[u][e] = 0.f;
+      }
+      for (int k0 = 0; k0 < kmax; k0 += KK) {
+        f32x4 lo[KK][U], hi[KK][U];
+        float w[KK][U];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const int k = k0 + kk;
-          const bool on = k < na[u];
-          const f32x4* src = (const f32x4*)(pz[u] + (on ? k : 0) * z_stride);
-          w[kk][u] = on ? wk[u][k] : 0.f;
-          if (on) { lo[kk][u] = src[0]; hi[kk][u] = src[1]; }
-          else { lo[kk][u] = f32x4{0.f, 0.f, 0.f, 0.f}; hi[kk][u] = lo[kk][u]; }
-        }
+        for (int kk = 0; kk < KK; ++kk)
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk)
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            z[u][e] += w[kk][u] * lo[kk][u][e];
-            z[u][4 + e] += w[kk][u] * hi[kk][u][e];
+          for (int u = 0; u < U; ++u) {
+            const int k = k0 + kk;
+            const bool on = k < na[u];
+            const f32x4* src = (const f32x4*)(pz[u] + (on ? k : 0) * z_stride);
+            w[kk][u] = on ? wk[u][k] : 0.f;
+            if (on) { lo[kk][u] = src[0]; hi[kk][u] = src[1]; }
+            else { lo[kk][u] = f32x4{0.f, 0.f, 0.f, 0.f}; hi[kk][u] = lo[kk][u]; }
           }
-    }
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      if (base + u * 256 < n_items) {
-        bf16x8 packed;
+        for (int kk = 0; kk < KK; ++kk)
 #pragma unroll
-        for (int e = 0; e < 8; ++e) packed[e] = (__bf16)z[u][e];
-        *(bf16x8*)(zt + sl[u] * zpitch + r0[u]) = packed;
+          for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              z[u][e] += w[kk][u] * lo[kk][u][e];
+              z[u][4 + e] += w[kk][u] * hi[kk][u][e];
+            }
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        if (base + u * 256 < n_items) {
+          bf16x8 packed;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) packed[e] = (__bf16)z[u][e];
+          *(bf16x8*)(zt + sl[u] * zpitch + r0[u]) = packed;
+        }
       }
     }
-  }
+  };
+  if (n_splits > 8) merge_items(std::integral_constant<int, 1>{});
+  else if (n_splits > 4) merge_items(std::integral_constant<int, 2>{});
+  else if (n_splits > 2) merge_items(std::integral_constant<int, 4>{});
+  else merge_items(std::integral_constant<int, 8>{});
 
   // ---- phase 2 ----
   f32x16 acc = opaque_zero();
