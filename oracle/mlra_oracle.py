@@ -19,6 +19,11 @@ What each function follows (all citations are to the MLRA paper):
     the two branches of Eq. (6); each latent block serves the h/2 heads of its group.
   * gqa_decode              -- Appendix C, MQA/GQA: query head i reads KV head floor(i/r),
     r = h/g.
+  * rms_norm / rope / pre_attention -- the projections that produce one new token's queries
+    and cache row (Section 2.1 and Appendix B.1 "MLA": C^Q = alpha_q RMSNorm(H W^DQ), Q^NoPE = C^Q W^UQ,
+    Q^RoPE = RoPE(C^Q W^QR), C^KV = alpha_kv RMSNorm(H W^DKV), K^RoPE = RoPE(H W^KR); the scaling
+    factors are those of Eq. (9)); RoPE rotates the 2-D blocks [2l, 2l+1] by t theta_l as in the
+    proof of the paper's RoPE theorem (Appendix B).
   * round_bf16 / append_kv / gather_sequence -- storage conventions of this build (the paper
     is silent on dtype rounding and physical layout): round-to-nearest-even to bfloat16,
     and the paged pool layout [page][block][slot][channel].
@@ -266,6 +271,52 @@ def gqa_decode(q, K, V, scale):
         p = softmax_1d(scale * (K[:, j, :] @ q[i]))
         O[i] = p @ V[:, j, :]
     return O
+
+
+# --------------------------------------------------------------------------------------
+# Pre-attention of one new token per sequence (Section 2.1; Appendix B.1; Eq. (9))
+# --------------------------------------------------------------------------------------
+def rms_norm(x, gain=None, eps=0.0):
+    """RMSNorm over the last axis: x / sqrt(mean(x^2) + eps) * gain (the paper cites the standard
+    definition; gain and eps are this build's arguments, 1 and a small constant in the workloads)."""
+    x = np.asarray(x, np.float64)
+    y = x / np.sqrt(np.mean(x * x, axis=-1, keepdims=True) + eps)
+    return y if gain is None else y * np.asarray(gain, np.float64)
+
+
+def rope_angles(d_r: int, base: float) -> np.ndarray:
+    """theta_l = base^(-2l/d_r), l = 0..d_r/2-1 (the usual frequencies; the paper leaves them open)."""
+    return np.asarray(base, np.float64) ** (-2.0 * np.arange(d_r // 2) / d_r)
+
+
+def rope(x, t, base=10000.0):
+    """Rotates each 2-D block x[..., 2l:2l+2] by the angle t * theta_l (x R_t in the paper's
+    row-vector notation).  x [..., d_r], t scalar or broadcastable to x[..., 0]."""
+    x = np.asarray(x, np.float64)
+    d_r = x.shape[-1]
+    ang = np.asarray(t, np.float64)[..., None] * rope_angles(d_r, base)     # [..., d_r/2]
+    c, s = np.cos(ang), np.sin(ang)
+    even, odd = x[..., 0::2], x[..., 1::2]
+    out = np.empty_like(x)
+    out[..., 0::2] = even * c - odd * s
+    out[..., 1::2] = even * s + odd * c
+    return out
+
+
+def pre_attention(hidden, position, W_DQ, W_DKV, W_KR, W_UQ, W_QR, h, alpha_q, alpha_kv,
+                  gain_q=None, gain_kv=None, eps=0.0, rope_base=10000.0, round_cq=None):
+    """One token: hidden [d], position t.  Returns (c_kv [d_c], k_rope [d_r], q_nope [h][d_h],
+    q_rope [h][d_r]).  round_cq, if given, is applied to C^Q before the up-projections (the
+    storage rounding of the intermediate latent in a 16-bit pipeline; None = exact)."""
+    x = np.asarray(hidden, np.float64)
+    c_q = alpha_q * rms_norm(x @ np.asarray(W_DQ, np.float64), gain_q, eps)
+    if round_cq is not None:
+        c_q = round_cq(c_q)
+    c_kv = alpha_kv * rms_norm(x @ np.asarray(W_DKV, np.float64), gain_kv, eps)
+    k_rope = rope(x @ np.asarray(W_KR, np.float64), position, rope_base)
+    q_nope = (c_q @ np.asarray(W_UQ, np.float64)).reshape(h, -1)
+    q_rope = rope((c_q @ np.asarray(W_QR, np.float64)).reshape(h, -1), position, rope_base)
+    return c_kv, k_rope, q_nope, q_rope
 
 
 # --------------------------------------------------------------------------------------

@@ -485,3 +485,88 @@ def test_mlra2_zero_query_gives_the_mean_value_and_empty_context_zero():
     e = dict(c); e["C"] = c["C"][:0]; e["KR"] = c["KR"][:0]
     out, lse = orc.mlra2_decode_absorbed(*_m2_args(e), return_lse=True)
     assert np.all(out == 0.0) and np.all(np.isneginf(lse))
+
+
+# =========================================================================================
+# Pre-attention of the new token: RMSNorm, RoPE, projections (Section 2.1, Appendix B, Eq. (9))
+# =========================================================================================
+def test_rope_matches_the_complex_form_of_the_papers_theorem():
+    """<RoPE(q, tq), RoPE(k, tk)> = Re sum_l q_l conj(k_l) e^{i (tq - tk) theta_l} with q_l = q[2l] + i q[2l+1]
+    (proof of the RoPE theorem in Appendix B), hence translation invariance."""
+    rng = np.random.default_rng(71)
+    d_r, base = 16, 10000.0
+    q, k = rng.standard_normal(d_r), rng.standard_normal(d_r)
+    theta = base ** (-2.0 * np.arange(d_r // 2) / d_r)
+    qc, kc = q[0::2] + 1j * q[1::2], k[0::2] + 1j * k[1::2]
+    for tq, tk in [(0, 0), (5, 2), (1000, 993), (17, 4000)]:
+        lhs = float(orc.rope(q, tq, base) @ orc.rope(k, tk, base))
+        rhs = float(np.real(np.sum(qc * np.conj(kc) * np.exp(1j * (tq - tk) * theta))))
+        assert abs(lhs - rhs) <= 1e-9
+        shifted = float(orc.rope(q, tq + 321, base) @ orc.rope(k, tk + 321, base))
+        assert abs(lhs - shifted) <= 1e-9
+    # position 0 is the identity, the rotation preserves the norm, and blocks do not mix
+    assert np.array_equal(orc.rope(q, 0, base), q)
+    assert abs(np.linalg.norm(orc.rope(q, 77, base)) - np.linalg.norm(q)) <= 1e-12
+    e0 = np.zeros(d_r); e0[0] = 1.0
+    r = orc.rope(e0, 3, base)
+    assert abs(r[0] - math.cos(3.0)) <= 1e-12 and abs(r[1] - math.sin(3.0)) <= 1e-12 and np.all(r[2:] == 0.0)
+
+
+def test_rms_norm_against_library_and_invariants():
+    rng = np.random.default_rng(72)
+    x = rng.standard_normal((5, 48)) * 3.0
+    g = rng.standard_normal(48)
+    lib = torch.nn.functional.rms_norm(torch.from_numpy(x), (48,), torch.from_numpy(g), eps=1e-6).numpy()
+    assert np.max(np.abs(orc.rms_norm(x, g, 1e-6) - lib)) <= 1e-12
+    y = orc.rms_norm(x)
+    assert np.max(np.abs(np.sqrt(np.mean(y * y, axis=-1)) - 1.0)) <= 1e-12          # unit RMS
+    assert np.max(np.abs(orc.rms_norm(7.5 * x) - y)) <= 1e-12                       # scale invariance
+
+
+def test_pre_attention_scalar_loops_and_scaling():
+    """Appendix B.1 written out with scalar sums on a tiny case; alpha factors are those of Eq. (9)."""
+    rng = np.random.default_rng(73)
+    d, d_cq, d_c, d_r, h, d_h = 6, 4, 8, 4, 2, 3
+    x = rng.standard_normal(d)
+    W_DQ, W_DKV, W_KR = rng.standard_normal((d, d_cq)), rng.standard_normal((d, d_c)), rng.standard_normal((d, d_r))
+    W_UQ, W_QR = rng.standard_normal((d_cq, h * d_h)), rng.standard_normal((d_cq, h * d_r))
+    a_q, a_kv, t, base = math.sqrt(d / d_cq), math.sqrt(4 * d / d_c), 9, 100.0
+    c_kv, k_rope, q_nope, q_rope = orc.pre_attention(x, t, W_DQ, W_DKV, W_KR, W_UQ, W_QR, h, a_q, a_kv,
+                                                     rope_base=base)
+    def down(W, n):
+        return [sum(x[i] * W[i][j] for i in range(d)) for j in range(n)]
+    def norm(v):
+        ms = sum(e * e for e in v) / len(v)
+        return [e / math.sqrt(ms) for e in v]
+    def rot(v):
+        out = list(v)
+        for l in range(len(v) // 2):
+            th = t * base ** (-2.0 * l / len(v))
+            out[2 * l] = v[2 * l] * math.cos(th) - v[2 * l + 1] * math.sin(th)
+            out[2 * l + 1] = v[2 * l] * math.sin(th) + v[2 * l + 1] * math.cos(th)
+        return out
+    cq = [a_q * e for e in norm(down(W_DQ, d_cq))]
+    assert np.max(np.abs(c_kv - np.array([a_kv * e for e in norm(down(W_DKV, d_c))]))) <= 1e-12
+    assert np.max(np.abs(k_rope - np.array(rot(down(W_KR, d_r))))) <= 1e-12
+    for i in range(h):
+        qn = [sum(cq[c] * W_UQ[c][i * d_h + p] for c in range(d_cq)) for p in range(d_h)]
+        qr = rot([sum(cq[c] * W_QR[c][i * d_r + u] for c in range(d_cq)) for u in range(d_r)])
+        assert np.max(np.abs(q_nope[i] - np.array(qn))) <= 1e-12
+        assert np.max(np.abs(q_rope[i] - np.array(qr))) <= 1e-12
+    # after the Eq. (9) scaling the latents have RMS alpha (unit-RMS RMSNorm output times alpha)
+    assert abs(np.sqrt(np.mean(c_kv * c_kv)) - a_kv) <= 1e-12
+
+
+def test_pre_attention_scores_depend_on_relative_position_only():
+    """The RoPE part of the logit between a query made at position tq and a key made at position tk
+    depends on tq - tk only (semi-translation equivariance, Appendix B.1 remark)."""
+    rng = np.random.default_rng(74)
+    d, d_cq, d_c, d_r, h, d_h = 12, 6, 8, 8, 3, 4
+    Ws = [rng.standard_normal(s) for s in ((d, d_cq), (d, d_c), (d, d_r), (d_cq, h * d_h), (d_cq, h * d_r))]
+    xq, xk = rng.standard_normal(d), rng.standard_normal(d)
+    def logit(tq, tk):
+        _, _, _, q_rope = orc.pre_attention(xq, tq, *Ws, h, 1.3, 0.7)
+        _, k_rope, _, _ = orc.pre_attention(xk, tk, *Ws, h, 1.3, 0.7)
+        return q_rope @ k_rope
+    assert np.max(np.abs(logit(40, 33) - logit(1040, 1033))) <= 1e-9
+    assert np.max(np.abs(logit(40, 33) - logit(41, 33))) > 1e-6
