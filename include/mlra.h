@@ -139,6 +139,49 @@ MLRA_API int mlra2_decode_attn(const mlra_cache* cache, int32_t batch, int32_t h
                       const void* q_rope, const void* w_uv, float softmax_scale, float out_scale, void* out,
                       int32_t out_dtype, float* lse, void* workspace, size_t workspace_bytes, void* stream);
 
+/* Pre-attention of the newest token of every sequence (Section 2.1 and Appendix B.1, which MLRA keeps from
+ * MLA; scaling factors of Eq. (9)).  With x = hidden[s] and t = positions[s]:
+ *   C^Q  = alpha_q  RMSNorm(x W^DQ)      q_nope[s][i] = (C^Q W^UQ)[i d_h : (i+1) d_h]
+ *   C^KV = alpha_kv RMSNorm(x W^DKV)     q_rope[s][i] = RoPE((C^Q W^QR)[i d_r : (i+1) d_r], t)
+ *   K^RoPE = RoPE(x W^KR, t)
+ * and C^KV (cut into the cache's n_blocks channel blocks) and K^RoPE are stored at logical slot t of
+ * sequence s, exactly where mlra_append_kv would put them (t < 0: queries only, nothing is cached).
+ * RMSNorm(v) = gain * v / sqrt(mean(v^2) + eps) over the whole latent; gain pointers may be NULL (= 1).
+ * RoPE rotates the 2-D blocks [2l, 2l+1] by t * rope_base^(-2l/d_r) (Appendix B, proof of the RoPE
+ * theorem; the frequencies are the usual ones, the paper leaves them open).  C^Q is rounded to dtype
+ * before the up-projections; accumulation is fp32.  All matrices are row-major with the paper's shapes:
+ *   w_dq [d][d_cq], w_dkv [d][n_blocks*d_cb], w_kr [d][d_r], w_uq [d_cq][h*d_h], w_qr [d_cq][h*d_r],
+ *   gain_q [d_cq], gain_kv [n_blocks*d_cb]: device, element type dtype (as hidden, q_nope, q_rope).
+ * Follow with mlra_absorb_q (or mlra2_absorb_q) on q_nope and the decode entry point. */
+typedef struct mlra_pre_weights {
+  const void* w_dq;
+  const void* w_dkv;
+  const void* w_kr;
+  const void* w_uq;
+  const void* w_qr;
+  const void* gain_q;   /* may be NULL */
+  const void* gain_kv;  /* may be NULL */
+  int32_t d;            /* hidden size */
+  int32_t d_cq;         /* query latent dim d_c' */
+  int32_t h;
+  int32_t d_h;
+  int32_t dtype;        /* mlra_dtype of hidden, weights, gains, q_nope, q_rope */
+  float alpha_q;        /* Eq. (9): sqrt(d / d_c') */
+  float alpha_kv;       /* Eq. (9): sqrt(4 d / d_c) for MLRA */
+  float eps;
+  float rope_base;
+} mlra_pre_weights;
+
+/* Workspace bytes for mlra_pre_attention on the current device (0 on invalid sizes). */
+MLRA_API size_t mlra_pre_attention_workspace_bytes(int32_t batch, int32_t d, int32_t d_cq, int32_t n_blocks,
+                                          int32_t d_cb, int32_t d_r, int32_t h, int32_t d_h, int32_t dtype);
+/*   hidden [batch][d], positions [batch] int32 (device), q_nope [batch][h][d_h], q_rope [batch][h][d_r];
+ *   workspace: 256-byte aligned, contents overwritten.  Errors as for the other entry points; d_h and
+ *   d_r must be even and d_r <= 256. */
+MLRA_API int mlra_pre_attention(const mlra_cache* cache, const mlra_pre_weights* weights, int32_t batch,
+                       const void* hidden, const int32_t* positions, void* q_nope, void* q_rope,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
 /* Workspace bytes for gqa_decode_attn (0 on invalid sizes). */
 MLRA_API size_t gqa_decode_workspace_bytes(int32_t batch, int32_t h, int32_t d_h, int32_t max_seq_len);
 

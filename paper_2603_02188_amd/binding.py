@@ -21,7 +21,8 @@ MLRA_BF16, MLRA_F32 = 0, 1
 
 EXPORTS = ("mlra_strerror", "mlra_append_kv", "mlra_absorb_q", "mlra_decode_workspace_bytes",
            "mlra_decode_attn", "mla_decode_attn", "mlra2_absorb_q", "mlra2_decode_workspace_bytes",
-           "mlra2_decode_attn", "gqa_decode_workspace_bytes", "gqa_decode_attn", "mlra_kernel_timing_begin",
+           "mlra2_decode_attn", "mlra_pre_attention_workspace_bytes", "mlra_pre_attention",
+           "gqa_decode_workspace_bytes", "gqa_decode_attn", "mlra_kernel_timing_begin",
            "mlra_kernel_timing_end")
 
 
@@ -31,6 +32,15 @@ class _CacheStruct(ctypes.Structure):
                 ("num_pages", ctypes.c_int32), ("page_size", ctypes.c_int32),
                 ("max_pages_per_seq", ctypes.c_int32), ("n_blocks", ctypes.c_int32),
                 ("d_cb", ctypes.c_int32), ("d_r", ctypes.c_int32), ("dtype", ctypes.c_int32)]
+
+
+class _PreWeightsStruct(ctypes.Structure):
+    _fields_ = [("w_dq", ctypes.c_void_p), ("w_dkv", ctypes.c_void_p), ("w_kr", ctypes.c_void_p),
+                ("w_uq", ctypes.c_void_p), ("w_qr", ctypes.c_void_p), ("gain_q", ctypes.c_void_p),
+                ("gain_kv", ctypes.c_void_p), ("d", ctypes.c_int32), ("d_cq", ctypes.c_int32),
+                ("h", ctypes.c_int32), ("d_h", ctypes.c_int32), ("dtype", ctypes.c_int32),
+                ("alpha_q", ctypes.c_float), ("alpha_kv", ctypes.c_float), ("eps", ctypes.c_float),
+                ("rope_base", ctypes.c_float)]
 
 
 def library_path() -> str:
@@ -64,6 +74,10 @@ def load_library() -> ctypes.CDLL:
     lib.mlra2_decode_workspace_bytes.argtypes = lib.mlra_decode_workspace_bytes.argtypes
     lib.mlra2_decode_attn.restype = ctypes.c_int
     lib.mlra2_decode_attn.argtypes = lib.mlra_decode_attn.argtypes
+    lib.mlra_pre_attention_workspace_bytes.restype = sz
+    lib.mlra_pre_attention_workspace_bytes.argtypes = [i32] * 9
+    lib.mlra_pre_attention.restype = ctypes.c_int
+    lib.mlra_pre_attention.argtypes = [cp, ctypes.POINTER(_PreWeightsStruct), i32, vp, vp, vp, vp, vp, sz, vp]
     lib.mla_decode_attn.restype = ctypes.c_int
     lib.mla_decode_attn.argtypes = [cp, i32, i32, i32, vp, vp, vp, f32, vp, i32, vp, vp, sz, vp]
     lib.gqa_decode_workspace_bytes.restype = sz
@@ -237,6 +251,63 @@ def mlra2_decode_attn(cache: Cache, q_abs: torch.Tensor, q_rope: torch.Tensor, w
                                  _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
            "mlra2_decode_attn")
     return out
+
+
+@dataclass
+class PreWeights:
+    """Projection weights of the pre-attention (struct mlra_pre_weights): device tensors and scalars."""
+
+    w_dq: torch.Tensor       # [d][d_cq]
+    w_dkv: torch.Tensor      # [d][n_blocks*d_cb]
+    w_kr: torch.Tensor       # [d][d_r]
+    w_uq: torch.Tensor       # [d_cq][h*d_h]
+    w_qr: torch.Tensor       # [d_cq][h*d_r]
+    h: int
+    alpha_q: float
+    alpha_kv: float
+    gain_q: Optional[torch.Tensor] = None
+    gain_kv: Optional[torch.Tensor] = None
+    eps: float = 1e-6
+    rope_base: float = 10000.0
+
+    def struct(self) -> _PreWeightsStruct:
+        d, d_cq = self.w_dq.shape
+        d_h = self.w_uq.shape[1] // self.h
+        assert self.w_uq.shape == (d_cq, self.h * d_h) and self.w_dkv.shape[0] == d and self.w_kr.shape[0] == d
+        for t in (self.w_dkv, self.w_kr, self.w_uq, self.w_qr):
+            assert t.dtype == self.w_dq.dtype
+        gp = lambda t: None if t is None else t.data_ptr()
+        return _PreWeightsStruct(_ptr(self.w_dq), _ptr(self.w_dkv), _ptr(self.w_kr), _ptr(self.w_uq),
+                                 _ptr(self.w_qr), _ptr(self.gain_q), _ptr(self.gain_kv), d, d_cq, self.h, d_h,
+                                 _dt(self.w_dq.dtype), self.alpha_q, self.alpha_kv, self.eps, self.rope_base)
+
+
+def mlra_pre_attention_workspace_bytes(batch, d, d_cq, n_blocks, d_cb, d_r, h, d_h, dtype) -> int:
+    return int(load_library().mlra_pre_attention_workspace_bytes(batch, d, d_cq, n_blocks, d_cb, d_r, h, d_h,
+                                                                  _dt(dtype)))
+
+
+def mlra_pre_attention(cache: Cache, weights: PreWeights, hidden: torch.Tensor, positions: torch.Tensor,
+                       q_nope: Optional[torch.Tensor] = None, q_rope: Optional[torch.Tensor] = None,
+                       workspace: Optional[torch.Tensor] = None, stream=None):
+    """Projects the new token of every sequence, stores its cache row and returns (q_nope, q_rope)."""
+    lib = load_library()
+    cs, ws = cache.struct(), weights.struct()
+    batch, d = hidden.shape
+    assert d == ws.d and hidden.dtype == weights.w_dq.dtype and positions.dtype == torch.int32
+    if q_nope is None:
+        q_nope = torch.empty((batch, ws.h, ws.d_h), dtype=hidden.dtype, device=hidden.device)
+    if q_rope is None:
+        q_rope = torch.empty((batch, ws.h, cs.d_r), dtype=hidden.dtype, device=hidden.device)
+    if workspace is None:
+        need = mlra_pre_attention_workspace_bytes(batch, d, ws.d_cq, cs.n_blocks, cs.d_cb, cs.d_r, ws.h, ws.d_h,
+                                                  hidden.dtype)
+        workspace = torch.empty(need, dtype=torch.uint8, device=hidden.device)
+    _check(lib.mlra_pre_attention(ctypes.byref(cs), ctypes.byref(ws), batch, _ptr(hidden), _ptr(positions),
+                                  _ptr(q_nope), _ptr(q_rope), _ptr(workspace),
+                                  workspace.numel() * workspace.element_size(), _stream(stream)),
+           "mlra_pre_attention")
+    return q_nope, q_rope
 
 
 def gqa_decode_workspace_bytes(batch: int, h: int, d_h: int, max_seq_len: int) -> int:

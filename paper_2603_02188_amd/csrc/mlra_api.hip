@@ -42,8 +42,8 @@ static SplitPlan plan_decode(int batch, int h, int n_blocks, int d_cb, int max_s
   // Split mode on the MFMA MLRA shape with long chunks: twice the chunk slots, so that long sequences of
   // a ragged batch can take more chunks than short ones (the decode entry decides per call whether it
   // uses them).  The planning kernel and the round of idle slots cost a few microseconds, which only
-  // chunks of 64 tiles or more (about 70 us of work) make negligible.
-  if (d_cb == 128 && p.n_splits > 1 && p.chunk_tokens >= 4096 && 2 * p.n_splits * n_blocks <= 128) {
+  // chunks of 128 tiles or more (about 140 us of work) make negligible.
+  if (d_cb == 128 && p.n_splits > 1 && p.chunk_tokens >= 8192 && 2 * p.n_splits * n_blocks <= 128) {
     p.target_chunks = p.n_splits * batch;
     p.n_splits *= 2;
   }
@@ -220,6 +220,32 @@ int mlra2_decode_attn(const mlra_cache* cache, int32_t batch, int32_t h, int32_t
   if (cache && cache->n_blocks % 2 != 0) return MLRA_ERR_SHAPE;
   return decode_common(cache, batch, h / 2, 2, d_h, q_abs, q_rope, w_uv, softmax_scale, out_scale, out, out_dtype,
                        lse, workspace, workspace_bytes, stream);
+}
+
+size_t mlra_pre_attention_workspace_bytes(int32_t batch, int32_t d, int32_t d_cq, int32_t n_blocks, int32_t d_cb,
+                                          int32_t d_r, int32_t h, int32_t d_h, int32_t dtype) {
+  if (batch <= 0 || d <= 0 || d_cq <= 0 || n_blocks <= 0 || d_cb <= 0 || d_r <= 0 || h <= 0 || d_h <= 0) return 0;
+  if (!valid_dtype(dtype) || d_r % 2 != 0 || d_h % 2 != 0 || d_r > 256) return 0;
+  return pre_plan(dtype, batch, d, d_cq, n_blocks * d_cb, d_r, h, d_h).bytes;
+}
+
+int mlra_pre_attention(const mlra_cache* c, const mlra_pre_weights* w, int32_t batch, const void* hidden,
+                       const int32_t* positions, void* q_nope, void* q_rope, void* workspace,
+                       size_t workspace_bytes, void* stream) {
+  if (!c || !w || !hidden || !positions || !q_nope || !q_rope) return MLRA_ERR_NULL;
+  if (!c->latent || !c->rope || !c->page_table) return MLRA_ERR_NULL;
+  if (!w->w_dq || !w->w_dkv || !w->w_kr || !w->w_uq || !w->w_qr) return MLRA_ERR_NULL;
+  if (!valid_dtype(c->dtype) || !valid_dtype(w->dtype)) return MLRA_ERR_DTYPE;
+  if (batch <= 0 || batch > 65535 || w->d <= 0 || w->d_cq <= 0 || w->h <= 0 || w->d_h <= 0 || c->n_blocks <= 0 ||
+      c->d_cb <= 0 || c->d_r <= 0 || c->page_size <= 0 || c->max_pages_per_seq <= 0 || c->num_pages <= 0)
+    return MLRA_ERR_SHAPE;
+  if (c->d_r % 2 != 0 || w->d_h % 2 != 0 || c->d_r > 256) return MLRA_ERR_SHAPE;
+  if ((long)w->h * (w->d_h + c->d_r) > (1L << 24) || (long)w->d_cq + (long)c->n_blocks * c->d_cb > 12000)
+    return MLRA_ERR_SHAPE;
+  const size_t need = mlra_pre_attention_workspace_bytes(batch, w->d, w->d_cq, c->n_blocks, c->d_cb, c->d_r, w->h,
+                                                         w->d_h, w->dtype);
+  if (!workspace || workspace_bytes < need || ((uintptr_t)workspace) % 256 != 0) return MLRA_ERR_WORKSPACE;
+  return launch_pre_attention(c, w, batch, hidden, positions, q_nope, q_rope, workspace, (hipStream_t)stream);
 }
 
 int mla_decode_attn(const mlra_cache* cache, int32_t batch, int32_t h, int32_t d_h, const void* q_abs,

@@ -110,6 +110,26 @@ bool gqa_mfma_supported(const GqaArgs& a);
 int launch_gqa_mfma(const GqaArgs& a);
 int launch_gqa_merge(const GqaArgs& a);
 
+// ---- pre-attention of the new token (pre_attn.hip) ----------------------------------------------
+// Weight matrices that share their rows (the K dimension) and sit side by side in the output.
+struct GemmSegments {
+  const void* w[3];
+  int cols[3];      // columns of each matrix (= its leading dimension)
+  int out_col[3];   // first output column of each matrix
+  int count;
+};
+struct PrePlan {
+  int n1, n2;                 // output columns of the down- and of the up-projection
+  bool mfma1, mfma2;
+  int slices1, rows1;         // K slices of the down-projection and rows per slice
+  int slices2, rows2;
+  size_t off_part1, off_cq, off_cs, off_part2, bytes;   // workspace layout
+};
+PrePlan pre_plan(int dtype, int batch, int d, int d_cq, int d_c, int d_r, int h, int d_h);
+int launch_pre_attention(const mlra_cache* c, const mlra_pre_weights* w, int batch, const void* hidden,
+                         const int32_t* positions, void* q_nope, void* q_rope, void* workspace,
+                         hipStream_t stream);
+
 static inline int check_launch() { return hipGetLastError() == hipSuccess ? MLRA_OK : MLRA_ERR_LAUNCH; }
 
 }  // namespace mlra

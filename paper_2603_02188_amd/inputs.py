@@ -315,3 +315,53 @@ def make_gqa_inputs(wl: Workload, poison: bool = True,
     rng = np.random.default_rng([wl.seed, 0xF66])
     q = to_storage(rng.standard_normal((wl.batch, wl.h, dh), dtype=np.float32), wl.dtype)
     return GqaInputs(wl, k_pool, v_pool, table, seq_lens, q)
+
+
+@dataclass
+class PreInputs:
+    """The new token's hidden states and the projection weights of Appendix B.1 (MLA form, kept by MLRA)."""
+
+    wl: Workload
+    d: int                   # hidden size
+    d_cq: int                # query latent dim d_c'
+    hidden: np.ndarray       # [B][d]
+    w_dq: np.ndarray         # [d][d_cq]
+    w_dkv: np.ndarray        # [d][NB*d_cb]
+    w_kr: np.ndarray         # [d][d_r]
+    w_uq: np.ndarray         # [d_cq][h*d_h]
+    w_qr: np.ndarray         # [d_cq][h*d_r]
+    gain_q: np.ndarray       # [d_cq]
+    gain_kv: np.ndarray      # [NB*d_cb]
+    eps: float = 1e-6
+    rope_base: float = 10000.0
+
+    @property
+    def alpha_q(self) -> float:
+        """Eq. (9): sqrt(d / d_c')."""
+        return float(np.sqrt(self.d / self.d_cq))
+
+    @property
+    def alpha_kv(self) -> float:
+        """Eq. (9), MLRA: sqrt(4 d / d_c)."""
+        return float(np.sqrt(4.0 * self.d / (self.wl.n_blocks * self.wl.d_cb)))
+
+
+def make_pre_inputs(wl: Workload, d: int, d_cq: int, unit_gains: bool = False) -> PreInputs:
+    """hidden ~ N(0,1); every projection matrix ~ N(0, variance 1/d) (a common variance, as the paper's
+    variance analysis of Section 3.3 assumes: with the Eq. (9) scaling queries and keys then have about
+    unit variance); RMSNorm gains 1 + 0.1 N(0,1) (or exactly 1).  All rounded to wl.dtype."""
+    rng = np.random.default_rng([wl.seed, 0x977])
+    d_c = wl.n_blocks * wl.d_cb
+    std = np.float32(1.0 / np.sqrt(d))
+    def mat(r, c):
+        return to_storage(rng.standard_normal((r, c), dtype=np.float32) * std, wl.dtype)
+    hidden = to_storage(rng.standard_normal((wl.batch, d), dtype=np.float32), wl.dtype)
+    w_dq, w_dkv, w_kr = mat(d, d_cq), mat(d, d_c), mat(d, wl.d_r)
+    w_uq, w_qr = mat(d_cq, wl.h * wl.d_h), mat(d_cq, wl.h * wl.d_r)
+    if unit_gains:
+        gq, gkv = np.ones(d_cq, np.float32), np.ones(d_c, np.float32)
+    else:
+        gq = 1.0 + 0.1 * rng.standard_normal(d_cq, dtype=np.float32)
+        gkv = 1.0 + 0.1 * rng.standard_normal(d_c, dtype=np.float32)
+    return PreInputs(wl, d, d_cq, hidden, w_dq, w_dkv, w_kr, w_uq, w_qr, to_storage(gq, wl.dtype),
+                     to_storage(gkv, wl.dtype))

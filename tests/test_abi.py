@@ -86,7 +86,7 @@ def test_workspace_sizing():
     # MLRA-2: each block holds partials for h/2 heads
     assert mlra.mlra2_decode_workspace_bytes(1, 7, 4, 64, 256) == 0
     m2 = mlra.mlra2_decode_workspace_bytes(64, 128, 4, 128, 8192)
-    assert 64 * 4 * 64 * (128 + 2) * 4 <= m2 < big
+    assert 64 * 4 * 64 * (128 + 2) * 4 <= m2 <= big + 4096   # two chunks of 64 heads per (sequence, block)
 
 
 def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
