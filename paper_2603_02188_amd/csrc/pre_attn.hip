@@ -33,11 +33,17 @@ __device__ __forceinline__ short4v lds_tr16(const void* p) {
 
 // out_part[slice][m][col0 + j] = sum_{k in slice} A[m][k] W[k][j] for the workgroup's column tile.
 // Column tiles are numbered over the segments side by side; a segment narrower than its last tile is
-// padded with zero columns (never stored).
+// padded with zero columns (never stored).  Per 256-row chunk the weights (64 KiB) and the matching
+// 256 columns of the A rows (up to 128 rows, 64 KiB) sit in LDS; the next chunk of both is in flight in
+// registers while the current one is multiplied.
+constexpr int kAPitch = kRowsChunk * 2 + 16;   // bytes per A row in LDS (+16: rows start on different banks)
+
 __global__ __launch_bounds__(256) void skinny_gemm_mfma_kernel(const bf16_t* __restrict__ A, int lda, int M,
                                                                GemmSegments segs, int K, int rows_per_slice,
                                                                float* __restrict__ out_part, int ld_out) {
-  extern __shared__ __attribute__((aligned(1024))) unsigned char wt[];   // [256 rows][256 B], chunks swizzled
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  unsigned char* wt = smem;                            // [256 rows][256 B], 16-byte chunks swizzled
+  unsigned char* at = smem + kRowsChunk * 256;         // [32 * m_tiles rows][kAPitch]
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, c32 = lane & 31;
   // column tile -> segment
   int tile = blockIdx.x, seg = 0;
@@ -54,11 +60,15 @@ __global__ __launch_bounds__(256) void skinny_gemm_mfma_kernel(const bf16_t* __r
   const int m_base = blockIdx.z * (32 * kMaxMTiles);
   const int m_tiles = min(kMaxMTiles, (M - m_base + 31) / 32);
 
-  // thread t moves 16-byte chunk t % 16 (8 columns) of rows t / 16 + 16 i
+  // weights: thread t moves 16-byte chunk t % 16 (8 columns) of rows t / 16 + 16 i
   const int cc = tid & 15, r0 = tid >> 4;
   const bool col_ok = cc * 8 < n_valid;
-  bf16x8 wreg[kRowsChunk / 16];
-  auto fetch = [&](int k0) {
+  // A: thread t moves 16-byte chunk t % 32 (8 of the chunk's 256 columns) of rows t / 32 + 8 i
+  const int ac = tid & 31, ar0 = tid >> 5;
+  // two register sets: chunks c + 1 and c + 2 are in flight while chunk c is multiplied
+  bf16x8 wreg[2][kRowsChunk / 16];
+  bf16x8 areg[2][4 * kMaxMTiles];
+  auto fetch = [&](int k0, bf16x8 (&wr)[kRowsChunk / 16], bf16x8 (&ar)[4 * kMaxMTiles]) {
 #pragma unroll
     for (int i = 0; i < kRowsChunk / 16; ++i) {
       const int k = k0 + r0 + 16 * i;
@@ -66,14 +76,29 @@ __global__ __launch_bounds__(256) void skinny_gemm_mfma_kernel(const bf16_t* __r
 #pragma unroll
       for (int e = 0; e < 8; ++e) v[e] = (__bf16)0.0f;
       if (col_ok && k < k_end) v = *(const bf16x8*)(W + (size_t)k * ldw + n0 + cc * 8);
-      wreg[i] = v;
+      wr[i] = v;
+    }
+#pragma unroll
+    for (int i = 0; i < 4 * kMaxMTiles; ++i) {
+      const int m = ar0 + 8 * i;
+      bf16x8 v;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] = (__bf16)0.0f;
+      if (m < 32 * m_tiles && k0 + ac * 8 < k_end)
+        v = *(const bf16x8*)(A + (size_t)min(m_base + m, M - 1) * lda + k0 + ac * 8);
+      ar[i] = v;
     }
   };
-  auto stash = [&]() {
+  auto stash = [&](const bf16x8 (&wr)[kRowsChunk / 16], const bf16x8 (&ar)[4 * kMaxMTiles]) {
 #pragma unroll
     for (int i = 0; i < kRowsChunk / 16; ++i) {
       const int row = r0 + 16 * i;
-      *(bf16x8*)(wt + row * 256 + ((cc ^ swz(row & 7)) << 4)) = wreg[i];
+      *(bf16x8*)(wt + row * 256 + ((cc ^ swz(row & 7)) << 4)) = wr[i];
+    }
+#pragma unroll
+    for (int i = 0; i < 4 * kMaxMTiles; ++i) {
+      const int m = ar0 + 8 * i;
+      if (m < 32 * m_tiles) *(bf16x8*)(at + m * kAPitch + ac * 16) = ar[i];
     }
   };
   // transpose-read offsets: the 16 lanes of a block fetch 4 consecutive rows x 16 output columns
@@ -96,29 +121,36 @@ __global__ __launch_bounds__(256) void skinny_gemm_mfma_kernel(const bf16_t* __r
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[t][i] = z;
   }
-  const bf16_t* arow[kMaxMTiles];
-#pragma unroll
-  for (int t = 0; t < kMaxMTiles; ++t) arow[t] = A + (size_t)min(m_base + t * 32 + c32, M - 1) * lda + g * 8;
 
-  fetch(k_begin);
-  for (int k0 = k_begin; k0 < k_end; k0 += kRowsChunk) {
-    __syncthreads();            // the previous chunk has been consumed
-    stash();
-    __syncthreads();
-    if (k0 + kRowsChunk < k_end) fetch(k0 + kRowsChunk);   // in flight while this chunk is multiplied
+  auto multiply = [&](int k0) {
     const int steps = (min(kRowsChunk, k_end - k0) + 15) / 16;   // rows past k_end are zero in LDS
     for (int ks = 0; ks < steps; ++ks) {
       const short4v lo = lds_tr16(wt + ks * 16 * 256 + tr_off[0]);
       const short4v hi = lds_tr16(wt + ks * 16 * 256 + tr_off[1]);
       const bf16x8 bm = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-      // (K is a multiple of 16 for this kernel, so the 8 elements are inside the row)
 #pragma unroll
       for (int t = 0; t < kMaxMTiles; ++t) {
         if (t < m_tiles) {
-          const bf16x8 a = *(const bf16x8*)(arow[t] + k0 + ks * 16);
+          const bf16x8 a = *(const bf16x8*)(at + (t * 32 + c32) * kAPitch + ks * 32 + g * 16);
           acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bm, acc[t], 0, 0, 0);
         }
       }
+    }
+  };
+  fetch(k_begin, wreg[0], areg[0]);
+  if (k_begin + kRowsChunk < k_end) fetch(k_begin + kRowsChunk, wreg[1], areg[1]);
+  for (int k0 = k_begin; k0 < k_end; k0 += 2 * kRowsChunk) {
+    __syncthreads();            // the previous chunk has been consumed
+    stash(wreg[0], areg[0]);
+    __syncthreads();
+    if (k0 + 2 * kRowsChunk < k_end) fetch(k0 + 2 * kRowsChunk, wreg[0], areg[0]);
+    multiply(k0);
+    if (k0 + kRowsChunk < k_end) {
+      __syncthreads();
+      stash(wreg[1], areg[1]);
+      __syncthreads();
+      if (k0 + 3 * kRowsChunk < k_end) fetch(k0 + 3 * kRowsChunk, wreg[1], areg[1]);
+      multiply(k0 + kRowsChunk);
     }
   }
   const int j = wave * 32 + c32;
@@ -183,21 +215,48 @@ __global__ __launch_bounds__(256) void pre_finish_down_kernel(
   const int n1 = d_cq + d_c + d_r;
   const int pos = positions[s];
   float ss_q = 0.f, ss_kv = 0.f;
-  for (int j = tid; j < n1; j += 256) {
-    float v = 0.f;
-    for (int k = 0; k < n_slices; ++k) v += part[((size_t)k * batch + s) * n1 + j];
-    row[j] = v;
-    if (j < d_cq) ss_q += v * v;
-    else if (j < d_cq + d_c) ss_kv += v * v;
+  // eight columns per thread at a time, so that eight loads per slice are in flight (one column at a
+  // time would pay one memory round trip per slice and column)
+  for (int j0 = 0; j0 < n1; j0 += 8 * 256) {
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = 0.f;
+    for (int k = 0; k < n_slices; k += 4) {
+      float t[4][8];
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        const float* src = part + ((size_t)min(k + kk, n_slices - 1) * batch + s) * n1;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) t[kk][u] = src[min(j0 + u * 256 + tid, n1 - 1)];   // unconditional: all in flight
+      }
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] += (k + kk < n_slices) ? t[kk][u] : 0.f;   // slices summed in order
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int j = j0 + u * 256 + tid;
+      if (j < n1) {
+        row[j] = v[u];
+        if (j < d_cq) ss_q += v[u] * v[u];
+        else if (j < d_cq + d_c) ss_kv += v[u] * v[u];
+      }
+    }
   }
   ss_q = block_sum(ss_q, red);
   ss_kv = block_sum(ss_kv, red);
   const float rq = alpha_q * rsqrtf(ss_q / d_cq + eps), rkv = alpha_kv * rsqrtf(ss_kv / d_c + eps);
-  // cos / sin of position * theta_l, in double: positions reach 10^5 and the angle must be exact to ~1e-4
+  // cos / sin of position * theta_l.  Positions reach 10^5 and beyond, so the product and its reduction
+  // to [-pi, pi] are done in double (a float angle would be off by ~1e-2 rad there); the reduced angle is
+  // then accurate to ~1e-11 and float sine / cosine of it are good to a few ulp.
   if (tid < d_r / 2) {
     const double theta = exp2(-2.0 * tid / d_r * log2((double)rope_base));
-    double sn, cs;
-    sincos((double)max(pos, 0) * theta, &sn, &cs);
+    const double ang = (double)max(pos, 0) * theta;
+    const double two_pi = 6.283185307179586476925287;
+    const float red_ang = (float)(ang - two_pi * rint(ang / two_pi));
+    float sn, cs;
+    sincosf(red_ang, &sn, &cs);
     cs_sh[2 * tid] = (float)cs;
     cs_sh[2 * tid + 1] = (float)sn;
     cs_tab[((size_t)s * (d_r / 2) + tid) * 2 + 0] = (float)cs;   // for the query side (step 4)
@@ -266,14 +325,16 @@ int launch_gemm(int dtype, const void* A, int lda, int M, const GemmSegments& se
     static bool configured = false;
     if (!configured) {
       if (hipFuncSetAttribute((const void*)skinny_gemm_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                              kRowsChunk * 256) != hipSuccess)
+                              kRowsChunk * 256 + 32 * kMaxMTiles * kAPitch) != hipSuccess)
         return MLRA_ERR_LAUNCH;
       configured = true;
     }
     int tiles = 0;
     for (int i = 0; i < segs.count; ++i) tiles += (segs.cols[i] + kColsWG - 1) / kColsWG;
     dim3 grid(tiles, n_slices, (M + 32 * kMaxMTiles - 1) / (32 * kMaxMTiles));
-    skinny_gemm_mfma_kernel<<<grid, 256, kRowsChunk * 256, stream>>>((const bf16_t*)A, lda, M, segs, K,
+    const int a_rows = M < 32 * kMaxMTiles ? (M + 31) / 32 * 32 : 32 * kMaxMTiles;
+    const size_t lds = (size_t)kRowsChunk * 256 + (size_t)a_rows * kAPitch;
+    skinny_gemm_mfma_kernel<<<grid, 256, lds, stream>>>((const bf16_t*)A, lda, M, segs, K,
                                                                      rows_per_slice, part, ld_out);
   } else {
     dim3 grid((ld_out + 255) / 256, M);
