@@ -38,6 +38,7 @@ __device__ __forceinline__ short4v lds_tr16(const void* p) {
 // registers while the current one is multiplied.
 constexpr int kAPitch = kRowsChunk * 2 + 16;   // bytes per A row in LDS (+16: rows start on different banks)
 
+template <int MT>   // 32-row tiles of A per workgroup (1..kMaxMTiles)
 __global__ __launch_bounds__(256) void skinny_gemm_mfma_kernel(const bf16_t* __restrict__ A, int lda, int M,
                                                                GemmSegments segs, int K, int rows_per_slice,
                                                                float* __restrict__ out_part, int ld_out) {
@@ -57,8 +58,7 @@ __global__ __launch_bounds__(256) void skinny_gemm_mfma_kernel(const bf16_t* __r
   const int n_valid = min(kColsWG, ldw - n0);          // multiple of 8
   const int slice = blockIdx.y;
   const int k_begin = slice * rows_per_slice, k_end = min(K, k_begin + rows_per_slice);
-  const int m_base = blockIdx.z * (32 * kMaxMTiles);
-  const int m_tiles = min(kMaxMTiles, (M - m_base + 31) / 32);
+  const int m_base = blockIdx.z * (32 * MT);   // (rows past M repeat row M - 1 and are never stored)
 
   // weights: thread t moves 16-byte chunk t % 16 (8 columns) of rows t / 16 + 16 i
   const int cc = tid & 15, r0 = tid >> 4;
@@ -67,8 +67,8 @@ __global__ __launch_bounds__(256) void skinny_gemm_mfma_kernel(const bf16_t* __r
   const int ac = tid & 31, ar0 = tid >> 5;
   // two register sets: chunks c + 1 and c + 2 are in flight while chunk c is multiplied
   bf16x8 wreg[2][kRowsChunk / 16];
-  bf16x8 areg[2][4 * kMaxMTiles];
-  auto fetch = [&](int k0, bf16x8 (&wr)[kRowsChunk / 16], bf16x8 (&ar)[4 * kMaxMTiles]) {
+  bf16x8 areg[2][4 * MT];
+  auto fetch = [&](int k0, bf16x8 (&wr)[kRowsChunk / 16], bf16x8 (&ar)[4 * MT]) {
 #pragma unroll
     for (int i = 0; i < kRowsChunk / 16; ++i) {
       const int k = k0 + r0 + 16 * i;
@@ -79,27 +79,23 @@ __global__ __launch_bounds__(256) void skinny_gemm_mfma_kernel(const bf16_t* __r
       wr[i] = v;
     }
 #pragma unroll
-    for (int i = 0; i < 4 * kMaxMTiles; ++i) {
+    for (int i = 0; i < 4 * MT; ++i) {
       const int m = ar0 + 8 * i;
       bf16x8 v;
 #pragma unroll
       for (int e = 0; e < 8; ++e) v[e] = (__bf16)0.0f;
-      if (m < 32 * m_tiles && k0 + ac * 8 < k_end)
-        v = *(const bf16x8*)(A + (size_t)min(m_base + m, M - 1) * lda + k0 + ac * 8);
+      if (k0 + ac * 8 < k_end) v = *(const bf16x8*)(A + (size_t)min(m_base + m, M - 1) * lda + k0 + ac * 8);
       ar[i] = v;
     }
   };
-  auto stash = [&](const bf16x8 (&wr)[kRowsChunk / 16], const bf16x8 (&ar)[4 * kMaxMTiles]) {
+  auto stash = [&](const bf16x8 (&wr)[kRowsChunk / 16], const bf16x8 (&ar)[4 * MT]) {
 #pragma unroll
     for (int i = 0; i < kRowsChunk / 16; ++i) {
       const int row = r0 + 16 * i;
       *(bf16x8*)(wt + row * 256 + ((cc ^ swz(row & 7)) << 4)) = wr[i];
     }
 #pragma unroll
-    for (int i = 0; i < 4 * kMaxMTiles; ++i) {
-      const int m = ar0 + 8 * i;
-      if (m < 32 * m_tiles) *(bf16x8*)(at + m * kAPitch + ac * 16) = ar[i];
-    }
+    for (int i = 0; i < 4 * MT; ++i) *(bf16x8*)(at + (ar0 + 8 * i) * kAPitch + ac * 16) = ar[i];
   };
   // transpose-read offsets: the 16 lanes of a block fetch 4 consecutive rows x 16 output columns
   unsigned tr_off[2];
@@ -112,28 +108,28 @@ __global__ __launch_bounds__(256) void skinny_gemm_mfma_kernel(const bf16_t* __r
       tr_off[half] = row * 256 + ((c16 ^ swz(row & 7)) << 4) + ((sg & 1) << 3);
     }
   }
-  f32x16 acc[kMaxMTiles];
+  f32x16 acc[MT];
   {
     float z = 0.f;
     asm volatile("" : "+v"(z));   // a register zero: every MFMA below is emitted in the tied form
 #pragma unroll
-    for (int t = 0; t < kMaxMTiles; ++t)
+    for (int t = 0; t < MT; ++t)
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[t][i] = z;
   }
 
-  auto multiply = [&](int k0) {
-    const int steps = (min(kRowsChunk, k_end - k0) + 15) / 16;   // rows past k_end are zero in LDS
-    for (int ks = 0; ks < steps; ++ks) {
+  // all 16 k-steps of a chunk, straight-line so that the LDS reads of later steps are issued ahead of
+  // the MFMAs of earlier ones (rows past k_end are zero in LDS, on both sides)
+  auto multiply = [&]() {
+#pragma unroll
+    for (int ks = 0; ks < kRowsChunk / 16; ++ks) {
       const short4v lo = lds_tr16(wt + ks * 16 * 256 + tr_off[0]);
       const short4v hi = lds_tr16(wt + ks * 16 * 256 + tr_off[1]);
       const bf16x8 bm = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
 #pragma unroll
-      for (int t = 0; t < kMaxMTiles; ++t) {
-        if (t < m_tiles) {
-          const bf16x8 a = *(const bf16x8*)(at + (t * 32 + c32) * kAPitch + ks * 32 + g * 16);
-          acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bm, acc[t], 0, 0, 0);
-        }
+      for (int t = 0; t < MT; ++t) {
+        const bf16x8 a = *(const bf16x8*)(at + (t * 32 + c32) * kAPitch + ks * 32 + g * 16);
+        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bm, acc[t], 0, 0, 0);
       }
     }
   };
@@ -144,20 +140,19 @@ __global__ __launch_bounds__(256) void skinny_gemm_mfma_kernel(const bf16_t* __r
     stash(wreg[0], areg[0]);
     __syncthreads();
     if (k0 + 2 * kRowsChunk < k_end) fetch(k0 + 2 * kRowsChunk, wreg[0], areg[0]);
-    multiply(k0);
+    multiply();
     if (k0 + kRowsChunk < k_end) {
       __syncthreads();
       stash(wreg[1], areg[1]);
       __syncthreads();
       if (k0 + 3 * kRowsChunk < k_end) fetch(k0 + 3 * kRowsChunk, wreg[1], areg[1]);
-      multiply(k0 + kRowsChunk);
+      multiply();
     }
   }
   const int j = wave * 32 + c32;
   if (j < n_valid) {
 #pragma unroll
-    for (int t = 0; t < kMaxMTiles; ++t) {
-      if (t >= m_tiles) break;
+    for (int t = 0; t < MT; ++t) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int m = m_base + t * 32 + (r >> 2) * 8 + g * 4 + (r & 3);
@@ -323,19 +318,29 @@ int launch_gemm(int dtype, const void* A, int lda, int M, const GemmSegments& se
                 int rows_per_slice, float* part, int ld_out, hipStream_t stream) {
   if (gemm_mfma_ok(dtype, K, lda, segs)) {
     static bool configured = false;
+    const int max_lds = kRowsChunk * 256 + 32 * kMaxMTiles * kAPitch;
     if (!configured) {
-      if (hipFuncSetAttribute((const void*)skinny_gemm_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                              kRowsChunk * 256 + 32 * kMaxMTiles * kAPitch) != hipSuccess)
+      if (hipFuncSetAttribute((const void*)skinny_gemm_mfma_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                              max_lds) != hipSuccess ||
+          hipFuncSetAttribute((const void*)skinny_gemm_mfma_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                              max_lds) != hipSuccess ||
+          hipFuncSetAttribute((const void*)skinny_gemm_mfma_kernel<3>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                              max_lds) != hipSuccess ||
+          hipFuncSetAttribute((const void*)skinny_gemm_mfma_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                              max_lds) != hipSuccess)
         return MLRA_ERR_LAUNCH;
       configured = true;
     }
     int tiles = 0;
     for (int i = 0; i < segs.count; ++i) tiles += (segs.cols[i] + kColsWG - 1) / kColsWG;
-    dim3 grid(tiles, n_slices, (M + 32 * kMaxMTiles - 1) / (32 * kMaxMTiles));
-    const int a_rows = M < 32 * kMaxMTiles ? (M + 31) / 32 * 32 : 32 * kMaxMTiles;
-    const size_t lds = (size_t)kRowsChunk * 256 + (size_t)a_rows * kAPitch;
-    skinny_gemm_mfma_kernel<<<grid, 256, lds, stream>>>((const bf16_t*)A, lda, M, segs, K,
-                                                                     rows_per_slice, part, ld_out);
+    const int mt = M >= 32 * kMaxMTiles ? kMaxMTiles : (M + 31) / 32;
+    dim3 grid(tiles, n_slices, (M + 32 * mt - 1) / (32 * mt));
+    const size_t lds = (size_t)kRowsChunk * 256 + (size_t)32 * mt * kAPitch;
+    const bf16_t* a = (const bf16_t*)A;
+    if (mt == 1) skinny_gemm_mfma_kernel<1><<<grid, 256, lds, stream>>>(a, lda, M, segs, K, rows_per_slice, part, ld_out);
+    else if (mt == 2) skinny_gemm_mfma_kernel<2><<<grid, 256, lds, stream>>>(a, lda, M, segs, K, rows_per_slice, part, ld_out);
+    else if (mt == 3) skinny_gemm_mfma_kernel<3><<<grid, 256, lds, stream>>>(a, lda, M, segs, K, rows_per_slice, part, ld_out);
+    else skinny_gemm_mfma_kernel<4><<<grid, 256, lds, stream>>>(a, lda, M, segs, K, rows_per_slice, part, ld_out);
   } else {
     dim3 grid((ld_out + 255) / 256, M);
     if (dtype == MLRA_BF16)
@@ -357,7 +362,7 @@ PrePlan pre_plan(int dtype, int batch, int d, int d_cq, int d_c, int d_r, int h,
   p.n2 = h * (d_h + d_r);
   auto slices = [&](int K, int tiles, int& n_slices, int& rows) {
     const int chunks = (K + kRowsChunk - 1) / kRowsChunk;
-    int want = (device_cu_count() + tiles - 1) / tiles;
+    int want = (device_cu_count() + tiles / 2) / tiles;   // nearest: a second partial round costs more than idle CUs
     if (want > chunks) want = chunks;
     if (want < 1) want = 1;
     const int per = (chunks + want - 1) / want;
