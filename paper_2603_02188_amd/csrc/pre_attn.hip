@@ -24,6 +24,7 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 constexpr int kColsWG = 128;     // output columns per workgroup (32 per wave)
 constexpr int kRowsChunk = 256;  // weight rows resident in LDS at a time (64 KiB)
 constexpr int kMaxMTiles = 4;    // 32-row tiles of the batch held in accumulators at once
+constexpr int kSets = 2;         // chunks in flight in registers (loads of chunk c + kSets follow the use of chunk c)
 
 __device__ __forceinline__ int swz(int t) { return ((t & 3) << 1) | ((t >> 2) & 1); }
 
@@ -65,9 +66,9 @@ __global__ __launch_bounds__(256) void skinny_gemm_mfma_kernel(const bf16_t* __r
   const bool col_ok = cc * 8 < n_valid;
   // A: thread t moves 16-byte chunk t % 32 (8 of the chunk's 256 columns) of rows t / 32 + 8 i
   const int ac = tid & 31, ar0 = tid >> 5;
-  // two register sets: chunks c + 1 and c + 2 are in flight while chunk c is multiplied
-  bf16x8 wreg[2][kRowsChunk / 16];
-  bf16x8 areg[2][4 * MT];
+  // kSets register sets: that many chunks are in flight while one is multiplied
+  bf16x8 wreg[kSets][kRowsChunk / 16];
+  bf16x8 areg[kSets][4 * MT];
   auto fetch = [&](int k0, bf16x8 (&wr)[kRowsChunk / 16], bf16x8 (&ar)[4 * MT]) {
 #pragma unroll
     for (int i = 0; i < kRowsChunk / 16; ++i) {
@@ -133,20 +134,20 @@ __global__ __launch_bounds__(256) void skinny_gemm_mfma_kernel(const bf16_t* __r
       }
     }
   };
-  fetch(k_begin, wreg[0], areg[0]);
-  if (k_begin + kRowsChunk < k_end) fetch(k_begin + kRowsChunk, wreg[1], areg[1]);
-  for (int k0 = k_begin; k0 < k_end; k0 += 2 * kRowsChunk) {
-    __syncthreads();            // the previous chunk has been consumed
-    stash(wreg[0], areg[0]);
-    __syncthreads();
-    if (k0 + 2 * kRowsChunk < k_end) fetch(k0 + 2 * kRowsChunk, wreg[0], areg[0]);
-    multiply();
-    if (k0 + kRowsChunk < k_end) {
-      __syncthreads();
-      stash(wreg[1], areg[1]);
-      __syncthreads();
-      if (k0 + 3 * kRowsChunk < k_end) fetch(k0 + 3 * kRowsChunk, wreg[1], areg[1]);
-      multiply();
+#pragma unroll
+  for (int c = 0; c < kSets; ++c)
+    if (k_begin + c * kRowsChunk < k_end) fetch(k_begin + c * kRowsChunk, wreg[c], areg[c]);
+  for (int k0 = k_begin; k0 < k_end; k0 += kSets * kRowsChunk) {
+#pragma unroll
+    for (int c = 0; c < kSets; ++c) {
+      const int kc = k0 + c * kRowsChunk;
+      if (kc < k_end) {
+        __syncthreads();            // the previous chunk has been consumed
+        stash(wreg[c], areg[c]);
+        __syncthreads();
+        if (kc + kSets * kRowsChunk < k_end) fetch(kc + kSets * kRowsChunk, wreg[c], areg[c]);
+        multiply();
+      }
     }
   }
   const int j = wave * 32 + c32;

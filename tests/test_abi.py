@@ -69,6 +69,19 @@ def test_null_and_shape_errors_are_reported_on_the_host():
                                  null) == -2
     assert lib.mlra2_decode_attn(ctypes.byref(cs2), 1, 8, 64, one, one, one, 0.1, 1.0, one, 1, null, null, 0,
                                  null) == -4
+    # pre-attention: null weights, odd RoPE dim, workspace too small
+    pw = mlra._PreWeightsStruct(256, 256, 256, 256, 256, None, None, 96, 40, 8, 64, 1, 1.0, 1.0, 1e-6, 1e4)
+    pw_null = mlra._PreWeightsStruct(None, 256, 256, 256, 256, None, None, 96, 40, 8, 64, 1, 1.0, 1.0, 1e-6, 1e4)
+    assert lib.mlra_pre_attention(ctypes.byref(cs2), ctypes.byref(pw_null), 2, one, one, one, one, one, 1 << 30,
+                                  null) == -1
+    assert lib.mlra_pre_attention(ctypes.byref(cs2), None, 2, one, one, one, one, one, 1 << 30, null) == -1
+    cs_odd = mlra._CacheStruct(256, 256, 256, 256, 4, 64, 4, 4, 64, 31, 1)
+    assert lib.mlra_pre_attention(ctypes.byref(cs_odd), ctypes.byref(pw), 2, one, one, one, one, one, 1 << 30,
+                                  null) == -2
+    assert lib.mlra_pre_attention(ctypes.byref(cs2), ctypes.byref(pw), 2, one, one, one, one, one, 16, null) == -4
+    pw_dt = mlra._PreWeightsStruct(256, 256, 256, 256, 256, None, None, 96, 40, 8, 64, 9, 1.0, 1.0, 1e-6, 1e4)
+    assert lib.mlra_pre_attention(ctypes.byref(cs2), ctypes.byref(pw_dt), 2, one, one, one, one, one, 1 << 30,
+                                  null) == -3
     assert lib.gqa_decode_attn(one, one, one, one, 4, 64, 4, 1, 8, 3, 64, 0, one, 0.1, one, 1, one, 1 << 30,
                                null) == -2   # h % g != 0
     assert lib.gqa_decode_attn(null, one, one, one, 4, 64, 4, 1, 8, 2, 64, 0, one, 0.1, one, 1, one, 1 << 30,
@@ -83,6 +96,9 @@ def test_workspace_sizing():
     big = mlra.mlra_decode_workspace_bytes(64, 128, 4, 128, 8192)
     assert big >= 64 * 4 * 128 * (128 + 2) * 4 and big % 256 == 0
     assert mlra.gqa_decode_workspace_bytes(2, 16, 128, 4096) >= 2 * 16 * 130 * 4
+    assert mlra.mlra_pre_attention_workspace_bytes(64, 7168, 1536, 4, 128, 64, 128, 128, __import__("torch").bfloat16) \
+        >= 64 * (1536 + 512 + 64) * 4 + 64 * 1536 * 2 + 64 * 128 * 192 * 4
+    assert mlra.mlra_pre_attention_workspace_bytes(64, 7168, 1536, 4, 128, 63, 128, 128, __import__("torch").bfloat16) == 0
     # MLRA-2: each block holds partials for h/2 heads
     assert mlra.mlra2_decode_workspace_bytes(1, 7, 4, 64, 256) == 0
     m2 = mlra.mlra2_decode_workspace_bytes(64, 128, 4, 128, 8192)
