@@ -13,6 +13,9 @@ What each function follows (all citations are to the MLRA paper):
   * mlra_decode_absorbed    -- the three steps per block, block outputs summed (Eq. (5)),
     times the output rescale alpha_attn of Eq. (10).
   * mla_decode              -- the same with a single block of d_c channels (Section 2.1).
+  * mlra_decode_multi       -- Eq. (5) for the last q_len rows of a sequence at once: row n - q_len + j
+    attends to its prefix {0..n - q_len + j} (Section 2.1 states attention for a position over its
+    prefix), i.e. the causal tail of the n x n attention.
   * mlra2_decode_unabsorbed -- Eq. (6) (MLRA-2) with the group map gamma(i) and the group matrices
     W^(gamma),UK / W^(gamma),UV of Section 2.3 (GLA-2), for the single decode query.
   * mlra2_absorb_q / mlra2_decode_absorbed -- the three absorbed steps applied to each of
@@ -156,6 +159,21 @@ def mlra_decode_absorbed(q_nope, q_rope, C, KR, W_UK, W_UV, n_blocks, tau, out_s
         O = O + up_project(Z_b, W_UV[b * d_cb:(b + 1) * d_cb], h, d_h)
     O = out_scale * O
     return (O, lse) if return_lse else O
+
+
+def mlra_decode_multi(q_nope, q_rope, C, KR, W_UK, W_UV, n_blocks, tau, out_scale=1.0):
+    """Queries of the last q_len cached rows: q_nope [q_len][h][d_h], q_rope [q_len][h][d_r]; C, KR hold all
+    n rows (the q_len newest included).  Query j sits at row n - q_len + j and attends to rows
+    0 .. n - q_len + j.  Returns O [q_len][h][d_h]; a query whose prefix is empty (n < q_len) gives zeros."""
+    q_nope = np.asarray(q_nope, np.float64)
+    q_len, h, d_h = q_nope.shape
+    n = np.asarray(C).shape[0]
+    O = np.zeros((q_len, h, d_h))
+    for j in range(q_len):
+        n_eff = max(0, n - (q_len - 1 - j))
+        O[j] = mlra_decode_absorbed(q_nope[j], np.asarray(q_rope)[j], np.asarray(C)[:n_eff], np.asarray(KR)[:n_eff],
+                                    W_UK, W_UV, n_blocks, tau, out_scale)
+    return O
 
 
 def mla_decode(q_nope, q_rope, C, KR, W_UK, W_UV, tau):
@@ -413,6 +431,21 @@ def mlra_decode_batch(latent_pool, rope_pool, page_table, seq_lens, q_nope, q_ro
         O[k], L[k] = mlra_decode_absorbed(q_nope[b], q_rope[b], C, KR, W_UK, W_UV, NB, tau,
                                           out_scale, return_lse=True)
     return (O, L) if return_lse else O
+
+
+def mlra_decode_multi_batch(latent_pool, rope_pool, page_table, seq_lens, q_nope, q_rope, w_uk, w_uv, tau,
+                            out_scale=1.0, seqs=None):
+    """q_nope [B][q_len][h][d_h], q_rope [B][q_len][h][d_r]; returns O [len(seqs)][q_len][h][d_h]."""
+    NB = latent_pool.shape[1]
+    q_len, h, d_h = q_nope.shape[1], q_nope.shape[2], q_nope.shape[3]
+    W_UK = np.asarray(w_uk, np.float64).reshape(-1, h * d_h)
+    W_UV = np.asarray(w_uv, np.float64).reshape(-1, h * d_h)
+    seqs = list(range(len(seq_lens))) if seqs is None else list(seqs)
+    O = np.zeros((len(seqs), q_len, h, d_h))
+    for k, b in enumerate(seqs):
+        C, KR = gather_sequence(latent_pool, rope_pool, page_table[b], int(seq_lens[b]))
+        O[k] = mlra_decode_multi(q_nope[b], q_rope[b], C, KR, W_UK, W_UV, NB, tau, out_scale)
+    return O
 
 
 def mlra2_decode_batch(latent_pool, rope_pool, page_table, seq_lens, q_nope, q_rope, w_uk, w_uv,

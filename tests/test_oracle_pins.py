@@ -570,3 +570,53 @@ def test_pre_attention_scores_depend_on_relative_position_only():
         return q_rope @ k_rope
     assert np.max(np.abs(logit(40, 33) - logit(1040, 1033))) <= 1e-9
     assert np.max(np.abs(logit(40, 33) - logit(41, 33))) > 1e-6
+
+
+# =========================================================================================
+# Several query tokens per sequence (the causal tail of Eq. (5))
+# =========================================================================================
+def test_multi_token_decode_against_causal_library_sdpa():
+    """The last q_len rows of causal attention over all n rows, per block, with keys [C_b W^UK | K^RoPE] and
+    values C_b W^UV, computed by the library routine with an explicit lower-triangular mask."""
+    n, q_len, h, d_h, NB, d_cb, d_r = 21, 4, 3, 8, 4, 8, 4
+    c = _rand_case(81, n, h, d_h, NB, d_cb, d_r)
+    rng = np.random.default_rng(82)
+    qn, qr = rng.standard_normal((q_len, h, d_h)), rng.standard_normal((q_len, h, d_r))
+    got = orc.mlra_decode_multi(qn, qr, c["C"], c["KR"], c["W_UK"], c["W_UV"], NB, c["tau"])
+    mask = torch.zeros(q_len, n, dtype=torch.bool)
+    for j in range(q_len):
+        mask[j, :n - q_len + j + 1] = True
+    total = np.zeros((q_len, h, d_h))
+    for b in range(NB):
+        K = np.zeros((h, n, d_h + d_r)); V = np.zeros((h, n, d_h))
+        for i in range(h):
+            C_b = c["C"][:, b * d_cb:(b + 1) * d_cb]
+            K[i, :, :d_h] = C_b @ c["W_UK"][b * d_cb:(b + 1) * d_cb, i * d_h:(i + 1) * d_h]
+            K[i, :, d_h:] = c["KR"]
+            V[i] = C_b @ c["W_UV"][b * d_cb:(b + 1) * d_cb, i * d_h:(i + 1) * d_h]
+        q = np.concatenate([qn, qr], axis=2).transpose(1, 0, 2)                      # [h][q_len][D]
+        out = torch.nn.functional.scaled_dot_product_attention(
+            torch.from_numpy(q)[None], torch.from_numpy(K)[None], torch.from_numpy(V)[None],
+            attn_mask=mask, scale=c["tau"])[0].numpy()                               # [h][q_len][d_h]
+        total += out.transpose(1, 0, 2)
+    assert np.max(np.abs(got - total)) <= 1e-10
+
+
+def test_multi_token_decode_causality_and_single_token_case():
+    n, q_len, h, d_h, NB, d_cb, d_r = 12, 3, 2, 4, 2, 4, 2
+    c = _rand_case(83, n, h, d_h, NB, d_cb, d_r)
+    rng = np.random.default_rng(84)
+    qn, qr = rng.standard_normal((q_len, h, d_h)), rng.standard_normal((q_len, h, d_r))
+    args = (c["W_UK"], c["W_UV"], NB, c["tau"])
+    base = orc.mlra_decode_multi(qn, qr, c["C"], c["KR"], *args)
+    # the last query is the ordinary decode query
+    assert np.array_equal(base[-1], orc.mlra_decode_absorbed(qn[-1], qr[-1], c["C"], c["KR"], *args))
+    # changing the newest row changes only the newest query's output
+    C2, KR2 = c["C"].copy(), c["KR"].copy()
+    C2[-1] += 5.0; KR2[-1] -= 3.0
+    other = orc.mlra_decode_multi(qn, qr, C2, KR2, *args)
+    assert np.array_equal(base[:-1], other[:-1]) and not np.allclose(base[-1], other[-1])
+    # fewer cached rows than queries: the queries without a prefix give zeros
+    short = orc.mlra_decode_multi(qn, qr, c["C"][:2], c["KR"][:2], *args)
+    assert np.all(short[0] == 0.0) and np.any(short[1] != 0.0)
+    assert np.array_equal(short[1], orc.mlra_decode_absorbed(qn[1], qr[1], c["C"][:1], c["KR"][:1], *args))
