@@ -35,6 +35,9 @@ def _args():
     ap.add_argument("--pre-attention", action="store_true",
                     help="the step starts from hidden states: mlra_pre_attention (projections, RMSNorm, RoPE, cache "
                          "append; hidden size 7168, query latent 1536) replaces mlra_append_kv")
+    ap.add_argument("--q-len", type=int, default=1,
+                    help="query tokens per sequence (> 1: mlra_decode_attn_multi; the q_len newest rows are cached, "
+                         "the step appends only the newest one)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain 1 GiB device copies (reference dispatches for rocprofv3 byte counters)")
     return ap.parse_args()
@@ -202,6 +205,23 @@ def main():
                              dtype=torch.uint8, device=dev)
         q_nope, q_rope = torch.empty_like(q_nope), torch.empty_like(q_rope)
 
+    if a.q_len > 1:
+        if wl.groups != 1 or a.pre_attention:
+            print("--q-len > 1 applies to the MLRA-4 workloads without --pre-attention", file=sys.stderr)
+            sys.exit(2)
+        rng = np.random.default_rng([wl.seed, 0x4D7, a.q_len])
+        q_nope = up(gen.to_storage(rng.standard_normal((wl.batch * a.q_len, wl.h, wl.d_h), dtype=np.float32), wl.dtype), wl.dtype)
+        q_rope = up(gen.to_storage(rng.standard_normal((wl.batch, a.q_len, wl.h, wl.d_r), dtype=np.float32), wl.dtype), wl.dtype)
+        q_abs = torch.empty((wl.batch * a.q_len, wl.n_blocks, wl.h, wl.d_cb), dtype=q_nope.dtype, device=dev)
+        out = torch.empty((wl.batch, a.q_len, wl.h, wl.d_h), dtype=torch.bfloat16, device=dev)
+        ws = torch.empty(mlra.mlra_decode_multi_workspace_bytes(wl.batch, a.q_len, wl.h, wl.n_blocks, wl.d_cb,
+                                                                wl.page_size, caches[0].page_table.shape[1]),
+                         dtype=torch.uint8, device=dev)
+        q_abs5 = q_abs.view(wl.batch, a.q_len, wl.n_blocks, wl.h, wl.d_cb)
+
+        def decode_attn(c, q_abs_, q_rope_, w_uv_, tau, out_scale, out=None, workspace=None):   # noqa: F811
+            return mlra.mlra_decode_attn_multi(c, q_abs5, q_rope_, w_uv_, tau, out_scale, out=out, workspace=workspace)
+
     def step(i):
         c = caches[i % copies]
         if pre is None:
@@ -250,9 +270,16 @@ def main():
     dec = np.array([e0.elapsed_time(e1) for e0, e1 in evs]) * 1e3
 
     bytes_decode = rf.decode_bytes(inp.seq_lens, wl.h, wl.d_h, wl.n_blocks, wl.d_cb, wl.d_r, groups=wl.groups)
+    if a.q_len > 1:   # the cache is shared by the queries of a sequence; queries and outputs are not
+        for k in ("q_abs", "q_rope", "out"):
+            bytes_decode["total"] += (a.q_len - 1) * bytes_decode[k]
+            bytes_decode[k] *= a.q_len
     bytes_step = (bytes_decode["total"] + rf.absorb_bytes(wl.batch, wl.h, wl.d_h, wl.n_blocks, wl.d_cb, groups=wl.groups)
                   + rf.append_bytes(wl.batch, wl.n_blocks, wl.d_cb, wl.d_r))
     flops = rf.decode_flops(inp.seq_lens, wl.h, wl.d_h, wl.n_blocks, wl.d_cb, wl.d_r, groups=wl.groups)
+    if a.q_len > 1:
+        flops = sum(rf.decode_flops(np.maximum(inp.seq_lens - (a.q_len - 1 - j), 0), wl.h, wl.d_h, wl.n_blocks,
+                                    wl.d_cb, wl.d_r) for j in range(a.q_len))
     # dominant kernel: the context-streaming decode kernel; its algorithmic bytes are the cache rows of
     # every valid token plus the absorbed / RoPE queries (W^UV and the output belong to the epilogue)
     kernel_bytes = bytes_decode["cache"] + bytes_decode["q_abs"] + bytes_decode["q_rope"]
@@ -266,7 +293,7 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": wl.name, "batch": wl.batch, "context": [wl.n_min, wl.n_max], "n_blocks": wl.n_blocks,
                    "d_cb": wl.d_cb, "d_r": wl.d_r, "h": wl.h, "d_h": wl.d_h, "head_groups": wl.groups, "page_size": wl.page_size,
-                   "cache_copies_rotated": copies, "seed": wl.seed},
+                   "cache_copies_rotated": copies, "seed": wl.seed, "q_len": a.q_len},
         "step_gbps": bytes_step / (ms_per_step * 1e-3) / 1e9,
         "step_frac_of_hbm_peak": bytes_step / (ms_per_step * 1e-3) / 1e9 / rf.HBM_PEAK_GBS,
         "decode_attn_us": {"median": float(np.median(dec)), "p10": float(np.percentile(dec, 10)),
@@ -295,7 +322,14 @@ def main():
             print("--baselines applies to workload C5 (the paged mixed batch)", file=sys.stderr)
             sys.exit(2)
         res["baselines"] = _baselines(inp, float(np.median(dec)))
-    if not a.no_cpu_baseline:
+    if a.q_len > 1:
+        res["metric"] = res["metric"].replace("decode_attn)", "decode_attn_multi, %d query tokens per sequence)" % a.q_len)
+        # the cache is streamed once for q_len queries, so the path is bound by the matrix pipe
+        tf = res["roofline"]["mfma_tflops"]
+        res["roofline"].update({"bound": "mfma", "achieved": tf, "peak": rf.MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                "frac": tf / rf.MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                                "hbm_gbps_algorithmic": achieved})
+    if not a.no_cpu_baseline and a.q_len == 1:
         base, ref = _cpu_baseline(inp)
         res["cpu_baseline"] = base
         if a.parity:

@@ -110,6 +110,22 @@ MLRA_API int mlra_decode_attn(const mlra_cache* cache, int32_t batch, int32_t h,
                      const void* q_rope, const void* w_uv, float softmax_scale, float out_scale, void* out,
                      int32_t out_dtype, float* lse, void* workspace, size_t workspace_bytes, void* stream);
 
+/* Several query tokens per sequence (multi-token prediction / speculative decoding): the causal tail of
+ * Eq. (5).  The q_len newest rows of every sequence are already cached (seq_lens counts them); query j
+ * of sequence s sits at row seq_lens[s] - q_len + j and attends to rows 0 .. seq_lens[s] - q_len + j
+ * (Section 2.1: a position attends to its prefix).  A query whose prefix is empty gives a zero row.
+ *   q_abs [batch][q_len][n_blocks][h][d_cb]   (mlra_absorb_q with batch*q_len rows produces this)
+ *   q_rope [batch][q_len][h][d_r], out [batch][q_len][h][d_h], lse optional [batch][q_len][n_blocks][h]
+ * Everything else as mlra_decode_attn.  The q_len queries of a sequence run as q_len independent decode
+ * units over the same pages (their cache reads meet in the memory-side cache); workspace from
+ * mlra_decode_multi_workspace_bytes (max_pages_per_seq as in the cache passed later). */
+MLRA_API size_t mlra_decode_multi_workspace_bytes(int32_t batch, int32_t q_len, int32_t h, int32_t n_blocks,
+                                         int32_t d_cb, int32_t page_size, int32_t max_pages_per_seq);
+MLRA_API int mlra_decode_attn_multi(const mlra_cache* cache, int32_t batch, int32_t q_len, int32_t h, int32_t d_h,
+                           const void* q_abs, const void* q_rope, const void* w_uv, float softmax_scale,
+                           float out_scale, void* out, int32_t out_dtype, float* lse, void* workspace,
+                           size_t workspace_bytes, void* stream);
+
 /* MLA decode (Section 2.1, three-step algorithm): the same computation with one latent block of
  * d_c channels.  Requires cache->n_blocks == 1; out_scale is 1. */
 MLRA_API int mla_decode_attn(const mlra_cache* cache, int32_t batch, int32_t h, int32_t d_h, const void* q_abs,

@@ -21,7 +21,8 @@ MLRA_BF16, MLRA_F32 = 0, 1
 
 EXPORTS = ("mlra_strerror", "mlra_append_kv", "mlra_absorb_q", "mlra_decode_workspace_bytes",
            "mlra_decode_attn", "mla_decode_attn", "mlra2_absorb_q", "mlra2_decode_workspace_bytes",
-           "mlra2_decode_attn", "mlra_pre_attention_workspace_bytes", "mlra_pre_attention",
+           "mlra2_decode_attn", "mlra_decode_multi_workspace_bytes", "mlra_decode_attn_multi",
+           "mlra_pre_attention_workspace_bytes", "mlra_pre_attention",
            "gqa_decode_workspace_bytes", "gqa_decode_attn", "mlra_kernel_timing_begin",
            "mlra_kernel_timing_end")
 
@@ -74,6 +75,10 @@ def load_library() -> ctypes.CDLL:
     lib.mlra2_decode_workspace_bytes.argtypes = lib.mlra_decode_workspace_bytes.argtypes
     lib.mlra2_decode_attn.restype = ctypes.c_int
     lib.mlra2_decode_attn.argtypes = lib.mlra_decode_attn.argtypes
+    lib.mlra_decode_multi_workspace_bytes.restype = sz
+    lib.mlra_decode_multi_workspace_bytes.argtypes = [i32] * 7
+    lib.mlra_decode_attn_multi.restype = ctypes.c_int
+    lib.mlra_decode_attn_multi.argtypes = [cp, i32, i32, i32, i32, vp, vp, vp, f32, f32, vp, i32, vp, vp, sz, vp]
     lib.mlra_pre_attention_workspace_bytes.restype = sz
     lib.mlra_pre_attention_workspace_bytes.argtypes = [i32] * 9
     lib.mlra_pre_attention.restype = ctypes.c_int
@@ -209,6 +214,34 @@ def mla_decode_attn(cache: Cache, q_abs: torch.Tensor, q_rope: torch.Tensor, w_u
                     workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
     return _decode("mla_decode_attn", cache, q_abs, q_rope, w_uv, softmax_scale, 1.0, out, out_dtype, lse,
                    workspace, stream)
+
+
+def mlra_decode_multi_workspace_bytes(batch: int, q_len: int, h: int, n_blocks: int, d_cb: int, page_size: int,
+                                      max_pages_per_seq: int) -> int:
+    return int(load_library().mlra_decode_multi_workspace_bytes(batch, q_len, h, n_blocks, d_cb, page_size,
+                                                                max_pages_per_seq))
+
+
+def mlra_decode_attn_multi(cache: Cache, q_abs: torch.Tensor, q_rope: torch.Tensor, w_uv: torch.Tensor,
+                           softmax_scale: float, out_scale: float = 1.0, out: Optional[torch.Tensor] = None,
+                           out_dtype: Optional[torch.dtype] = None, lse: Optional[torch.Tensor] = None,
+                           workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """q_abs [batch][q_len][n_blocks][h][d_cb], q_rope [batch][q_len][h][d_r] -> out [batch][q_len][h][d_h]."""
+    lib = load_library()
+    cs = cache.struct()
+    batch, q_len, n_blocks, h, d_cb = q_abs.shape
+    d_h = w_uv.shape[2] // h
+    assert w_uv.shape == (n_blocks, d_cb, h * d_h) and q_rope.shape[:3] == (batch, q_len, h)
+    if out is None:
+        out = torch.empty((batch, q_len, h, d_h), dtype=out_dtype or q_abs.dtype, device=q_abs.device)
+    if workspace is None:
+        need = mlra_decode_multi_workspace_bytes(batch, q_len, h, n_blocks, d_cb, cs.page_size, cs.max_pages_per_seq)
+        workspace = torch.empty(need, dtype=torch.uint8, device=q_abs.device)
+    _check(lib.mlra_decode_attn_multi(ctypes.byref(cs), batch, q_len, h, d_h, _ptr(q_abs), _ptr(q_rope), _ptr(w_uv),
+                                      float(softmax_scale), float(out_scale), _ptr(out), _dt(out.dtype), _ptr(lse),
+                                      _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                      _stream(stream)), "mlra_decode_attn_multi")
+    return out
 
 
 def mlra2_absorb_q(q_nope: torch.Tensor, w_uk: torch.Tensor, q_abs: Optional[torch.Tensor] = None,

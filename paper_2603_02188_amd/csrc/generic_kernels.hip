@@ -60,6 +60,26 @@ int launch_append_kv(const mlra_cache* c, int batch, const void* c_kv_new, const
 }
 
 // ------------------------------------------------------------------------------------------------
+// Several query tokens per sequence: every (sequence, query) pair becomes a decode unit of its own with
+// the sequence's pages and the length of the query's causal prefix.
+// ------------------------------------------------------------------------------------------------
+__global__ void expand_queries_kernel(const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ page_table,
+                                      int q_len, int max_pages, int32_t* __restrict__ seq_lens_out,
+                                      int32_t* __restrict__ page_table_out) {
+  const int u = blockIdx.x, s = u / q_len, j = u % q_len;
+  if (threadIdx.x == 0) seq_lens_out[u] = max(0, seq_lens[s] - (q_len - 1 - j));
+  for (int p = threadIdx.x; p < max_pages; p += blockDim.x)
+    page_table_out[(size_t)u * max_pages + p] = page_table[(size_t)s * max_pages + p];
+}
+
+int launch_expand_queries(const int32_t* seq_lens, const int32_t* page_table, int batch, int q_len, int max_pages,
+                          int32_t* seq_lens_out, int32_t* page_table_out, hipStream_t stream) {
+  expand_queries_kernel<<<batch * q_len, 256, 0, stream>>>(seq_lens, page_table, q_len, max_pages, seq_lens_out,
+                                                           page_table_out);
+  return check_launch();
+}
+
+// ------------------------------------------------------------------------------------------------
 // mlra_absorb_q, generic form (Step 1, Section 2.1): one workgroup per (head, block, sequence);
 // each wave produces rows c of q~ = W^UK_(b),(i) q with lanes striding the d_h contraction.
 // ------------------------------------------------------------------------------------------------

@@ -194,6 +194,54 @@ int mlra_decode_attn(const mlra_cache* cache, int32_t batch, int32_t h, int32_t 
                        workspace, workspace_bytes, stream);
 }
 
+size_t mlra_decode_multi_workspace_bytes(int32_t batch, int32_t q_len, int32_t h, int32_t n_blocks, int32_t d_cb,
+                                         int32_t page_size, int32_t max_pages_per_seq) {
+  if (batch <= 0 || q_len <= 0 || h <= 0 || n_blocks <= 0 || d_cb <= 0 || page_size <= 0 || max_pages_per_seq <= 0)
+    return 0;
+  if ((long)batch * q_len > 65535 || (long)max_pages_per_seq * page_size > 0x7fffffffL) return 0;
+  const int units = batch * q_len;
+  return align_up((size_t)units * sizeof(int32_t), 256) +
+         align_up((size_t)units * max_pages_per_seq * sizeof(int32_t), 256) +
+         mlra_decode_workspace_bytes(units, h, n_blocks, d_cb, max_pages_per_seq * page_size);
+}
+
+int mlra_decode_attn_multi(const mlra_cache* c, int32_t batch, int32_t q_len, int32_t h, int32_t d_h,
+                           const void* q_abs, const void* q_rope, const void* w_uv, float softmax_scale,
+                           float out_scale, void* out, int32_t out_dtype, float* lse, void* workspace,
+                           size_t workspace_bytes, void* stream) {
+  if (!c || !c->page_table || !c->seq_lens) return MLRA_ERR_NULL;
+  if (batch <= 0 || q_len <= 0 || (long)batch * q_len > 65535 || c->max_pages_per_seq <= 0 || c->page_size <= 0)
+    return MLRA_ERR_SHAPE;
+  if (q_len == 1)
+    return decode_common(c, batch, h, 1, d_h, q_abs, q_rope, w_uv, softmax_scale, out_scale, out, out_dtype, lse,
+                         workspace, workspace_bytes, stream);
+  const int units = batch * q_len;
+  const size_t lens_bytes = align_up((size_t)units * sizeof(int32_t), 256);
+  const size_t table_bytes = align_up((size_t)units * c->max_pages_per_seq * sizeof(int32_t), 256);
+  if (!workspace || ((uintptr_t)workspace) % 256 != 0 || workspace_bytes < lens_bytes + table_bytes)
+    return MLRA_ERR_WORKSPACE;
+  // every host-checkable condition of the decode proper is checked here first, so that an error return
+  // never leaves the expansion kernel enqueued
+  const size_t need = mlra_decode_multi_workspace_bytes(batch, q_len, h, c->n_blocks, c->d_cb, c->page_size,
+                                                        c->max_pages_per_seq);
+  if (need == 0) return MLRA_ERR_SHAPE;
+  if (workspace_bytes < need) return MLRA_ERR_WORKSPACE;
+  if (!q_abs || !q_rope || !w_uv || !out || !c->latent || !c->rope) return MLRA_ERR_NULL;
+  if (!valid_dtype(c->dtype) || !valid_dtype(out_dtype)) return MLRA_ERR_DTYPE;
+  if (h <= 0 || d_h <= 0 || c->n_blocks <= 0 || c->d_cb <= 0 || c->d_r <= 0 || c->num_pages <= 0) return MLRA_ERR_SHAPE;
+  int32_t* lens2 = (int32_t*)workspace;
+  int32_t* table2 = (int32_t*)((char*)workspace + lens_bytes);
+  int st = launch_expand_queries(c->seq_lens, c->page_table, batch, q_len, c->max_pages_per_seq, lens2, table2,
+                                 (hipStream_t)stream);
+  if (st != MLRA_OK) return st;
+  mlra_cache c2 = *c;
+  c2.page_table = table2;
+  c2.seq_lens = lens2;
+  return decode_common(&c2, units, h, 1, d_h, q_abs, q_rope, w_uv, softmax_scale, out_scale, out, out_dtype, lse,
+                       (char*)workspace + lens_bytes + table_bytes, workspace_bytes - lens_bytes - table_bytes,
+                       stream);
+}
+
 int mlra2_absorb_q(int32_t batch, int32_t h, int32_t d_h, int32_t n_blocks, int32_t d_cb, const void* q_nope,
                    const void* w_uk, void* q_abs, int32_t dtype, void* stream) {
   if (!q_nope || !w_uk || !q_abs) return MLRA_ERR_NULL;

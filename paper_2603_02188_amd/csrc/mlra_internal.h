@@ -74,6 +74,9 @@ int launch_append_kv(const mlra_cache* c, int batch, const void* c_kv_new, const
 int launch_absorb_q_generic(int batch, int h, int d_h, int n_blocks, int groups, int d_cb, const void* q_nope,
                             const void* w_uk, void* q_abs, int dtype, hipStream_t stream);
 int launch_decode_generic(const DecodeArgs& a);
+// seq_lens_out[s * q_len + j] = max(0, seq_lens[s] - (q_len - 1 - j)); page_table_out row s * q_len + j = row s
+int launch_expand_queries(const int32_t* seq_lens, const int32_t* page_table, int batch, int q_len, int max_pages,
+                          int32_t* seq_lens_out, int32_t* page_table_out, hipStream_t stream);
 int launch_merge_upproj_generic(const DecodeArgs& a);
 
 // Fast paths (bf16, MFMA); the *_supported predicates are false outside the shapes they were written for.
