@@ -69,6 +69,15 @@ def test_null_and_shape_errors_are_reported_on_the_host():
                                  null) == -2
     assert lib.mlra2_decode_attn(ctypes.byref(cs2), 1, 8, 64, one, one, one, 0.1, 1.0, one, 1, null, null, 0,
                                  null) == -4
+    # several query tokens: bad q_len, workspace too small, null cache
+    assert lib.mlra_decode_attn_multi(ctypes.byref(cs2), 1, 0, 8, 64, one, one, one, 0.1, 1.0, one, 1, null, one,
+                                      1 << 30, null) == -2
+    assert lib.mlra_decode_attn_multi(ctypes.byref(cs2), 1, 3, 8, 64, one, one, one, 0.1, 1.0, one, 1, null, one,
+                                      64, null) == -4
+    assert lib.mlra_decode_attn_multi(None, 1, 3, 8, 64, one, one, one, 0.1, 1.0, one, 1, null, one, 1 << 30,
+                                      null) == -1
+    assert lib.mlra_decode_attn_multi(ctypes.byref(cs2), 1, 3, 8, 64, null, one, one, 0.1, 1.0, one, 1, null, one,
+                                      1 << 30, null) == -1
     # pre-attention: null weights, odd RoPE dim, workspace too small
     pw = mlra._PreWeightsStruct(256, 256, 256, 256, 256, None, None, 96, 40, 8, 64, 1, 1.0, 1.0, 1e-6, 1e4)
     pw_null = mlra._PreWeightsStruct(None, 256, 256, 256, 256, None, None, 96, 40, 8, 64, 1, 1.0, 1.0, 1e-6, 1e4)
@@ -99,6 +108,8 @@ def test_workspace_sizing():
     assert mlra.mlra_pre_attention_workspace_bytes(64, 7168, 1536, 4, 128, 64, 128, 128, __import__("torch").bfloat16) \
         >= 64 * (1536 + 512 + 64) * 4 + 64 * 1536 * 2 + 64 * 128 * 192 * 4
     assert mlra.mlra_pre_attention_workspace_bytes(64, 7168, 1536, 4, 128, 63, 128, 128, __import__("torch").bfloat16) == 0
+    assert mlra.mlra_decode_multi_workspace_bytes(2, 0, 8, 4, 64, 64, 4) == 0
+    assert mlra.mlra_decode_multi_workspace_bytes(2, 3, 8, 4, 64, 64, 4) > mlra.mlra_decode_workspace_bytes(6, 8, 4, 64, 256)
     # MLRA-2: each block holds partials for h/2 heads
     assert mlra.mlra2_decode_workspace_bytes(1, 7, 4, 64, 256) == 0
     m2 = mlra.mlra2_decode_workspace_bytes(64, 128, 4, 128, 8192)
