@@ -1,5 +1,5 @@
 // MFMA decode kernel for bf16 latent caches with d_cb = 128, d_r = 64 (Step 2 of the absorbed decode,
-// Eq. (1), applied to one latent block; the block loop of Eq. (5) is the grid's y dimension).
+// Eq. (1), applied to one latent block; the blocks of Eq. (5) are spread over the grid).
 //
 // One workgroup (4 wavefronts) owns one (context chunk, latent block, 128 query heads, sequence).
 //   * Tiles of 64 tokens [C_b | K^RoPE] stream HBM -> LDS with direct-to-LDS loads, kStages deep.

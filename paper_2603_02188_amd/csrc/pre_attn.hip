@@ -10,8 +10,6 @@
 //   4. finish:      sum the slices, RoPE on the RoPE part, store q_nope and q_rope
 // The bf16 GEMM runs on MFMA with the batch as the M dimension; the weights pass through LDS 256 rows at
 // a time and reach the B operand through transpose reads.  Other dtypes and odd shapes use a plain kernel.
-#include <type_traits>
-
 #include "mlra_internal.h"
 
 namespace mlra {
@@ -386,7 +384,6 @@ PrePlan pre_plan(int dtype, int batch, int d, int d_cq, int d_c, int d_r, int h,
   p.off_cs = p.off_cq + align_up((size_t)batch * d_cq * elt, 256);
   p.off_part2 = p.off_cs + align_up((size_t)batch * d_r * sizeof(float), 256);
   p.bytes = p.off_part2 + align_up((size_t)p.slices2 * batch * p.n2 * sizeof(float), 256);
-  (void)batch;
   return p;
 }
 
