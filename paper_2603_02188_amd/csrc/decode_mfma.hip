@@ -149,25 +149,41 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
   const int blk = PAIRED ? blk0 + hw : blk0;                // this wave's block
   const int wave_head0 = PAIRED ? hgrp * 64 : hgrp * kHeadsWG + hw * 64;   // this wave's first head
 
-  // ---- absorbed + RoPE queries as MFMA B operands, resident in accumulation registers for the whole
-  // chunk (MFMA reads its B operand from there directly, which leaves the architectural VGPRs to the
-  // per-tile working set).  The loads are issued first thing, straight into those registers and
-  // invisibly to the compiler's wait-count bookkeeping: they are older than every tile load, so the
-  // first explicit wait for a tile (vector-memory operations retire in order) also covers them, and
-  // nothing reads these registers before the first MFMA, which comes after that wait. ----
-  bf16x8 qreg[2][12];
+  // ---- absorbed + RoPE queries: MFMA B operands, resident in accumulation registers for the whole chunk
+  // (MFMA reads its B operand from there directly, which leaves the architectural VGPRs to the per-tile
+  // working set).  They travel global -> LDS -> registers: the workgroup's 128 q_abs rows (256 B each) and
+  // its RoPE query rows (128 B each) are fetched once with direct-to-LDS loads into the end of the tile
+  // buffer, which the first tiles do not need yet, and every wave then reads its own B operands from
+  // there (the two waves of a head half would otherwise both fetch the same 24 KiB from L2).  16-byte
+  // chunk c of q_abs row r sits at chunk position c ^ (r & 15), chunk c of RoPE row r at c ^ ((r >> 1) & 7):
+  // the 16 lanes that a 128-bit LDS read serves together then hit 16 different bank groups.
+  constexpr int kQRopeRows = PAIRED ? 64 : kHeadsWG;
+  constexpr int kQBytes = kHeadsWG * (kDcb * 2) + kQRopeRows * (kDr * 2);     // 48 KiB, or 40 KiB
+  constexpr int kQStages = (kQBytes + kStageB - 1) / kStageB;                 // stages the queries occupy
+  const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
+  const unsigned wave_u = __builtin_amdgcn_readfirstlane(wave);
+  const unsigned q_lds = lds_base + STAGES * kStageB - kQBytes;
+  const int grp_head0 = (blk0 / (p.n_blocks / p.groups)) * p.h;   // first head of this block's group in q_rope
+  {
 #pragma unroll
-  for (int nt = 0; nt < 2; ++nt) {
-    const int head = min(wave_head0 + nt * 32 + c32, p.h - 1);
-    const bf16_t* qa = p.q_abs + (((size_t)seq * p.n_blocks + blk) * p.h + head) * kDcb + g * 8;
-    const int rope_head = (blk / (p.n_blocks / p.groups)) * p.h + head;   // the head's row among all heads
-    const bf16_t* qr = p.q_rope + ((size_t)seq * p.h * p.groups + rope_head) * kDr + g * 8;
+    for (int q = 0; q < 8; ++q) {                                  // q_abs rows 32 w + 4 q + lane / 16
+      const int row = 32 * wave + 4 * q + (lane >> 4);
+      const int row_blk = PAIRED ? blk0 + (row >> 6) : blk0;
+      const int head = min(PAIRED ? hgrp * 64 + (row & 63) : hgrp * kHeadsWG + row, p.h - 1);
+      const unsigned voff = ((unsigned)(seq * p.n_blocks + row_blk) * p.h + head) * (kDcb * 2) +
+                            (((lane & 15) ^ (row & 15)) << 4);
+      set_m0(q_lds + (32 * wave_u + 4 * q) * (kDcb * 2));
+      lds_dma16<0>(p.q_abs, voff);
+    }
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks)
-      asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=a"(qreg[nt][ks]) : "v"(qa), "n"(ks * 32) : "memory");
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks)
-      asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=a"(qreg[nt][8 + ks]) : "v"(qr), "n"(ks * 32) : "memory");
+    for (int q = 0; q < kQRopeRows / 32; ++q) {                    // RoPE rows (rows per wave) w + 8 q + lane / 8
+      const int row = (kQRopeRows / 4) * wave + 8 * q + (lane >> 3);
+      const int head = min(hgrp * kHeadsPerWG + row, p.h - 1);
+      const unsigned voff = ((unsigned)seq * p.h * p.groups + grp_head0 + head) * (kDr * 2) +
+                            (((lane & 7) ^ ((row >> 1) & 7)) << 4);
+      set_m0(q_lds + kHeadsWG * (kDcb * 2) + ((kQRopeRows / 4) * wave_u + 8 * q) * (kDr * 2));
+      lds_dma16<0>(p.q_rope, voff);
+    }
   }
 
   const int t0 = split * chunk_len;
@@ -178,7 +194,10 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
   int issue_page_idx = t0 / p.page_size;
   int issue_page = pt_row[min(issue_page_idx, p.max_pages - 1)];
   const int n = ((const_i32_ptr)p.seq_lens)[seq];
-  if (t0 >= n) return;
+  if (t0 >= n) {
+    wait_vmcnt<0>();   // the query loads target this workgroup's LDS: let them land before it is released
+    return;
+  }
   const int t1 = min(n, t0 + chunk_len);
   const int ntiles = (t1 - t0 + kTile - 1) / kTile;
   const int nvalid_last = t1 - t0 - (ntiles - 1) * kTile;
@@ -199,8 +218,6 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
 #pragma unroll
   for (int q = 0; q < 2; ++q)
     rope_voff[q] = (lane >> 3) * (kDr * 2) + (((lane & 7) ^ rope_swz(8 * q + (lane >> 3))) << 4);
-  const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
-  const unsigned wave_u = __builtin_amdgcn_readfirstlane(wave);
   const size_t lat_page_bytes = (size_t)p.n_blocks * p.page_size * (kDcb * 2);
   const size_t rope_page_bytes = (size_t)p.page_size * (kDr * 2);
   const size_t lat_plane_bytes = (size_t)p.page_size * (kDcb * 2);     // one block's rows inside a page
@@ -406,11 +423,31 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
   };
 
   // ---- prologue: every stage gets a tile; scores and column maxima of tile 0; K operands of tile 1 ----
-  for (int jj = 0; jj < STAGES && jj < ntiles; ++jj) {
-    // (the 24 query loads and STAGES tiles must stay within the 63 loads the counter can hold)
-    if (24 + STAGES * kLoadsTile > 63 && jj == STAGES - 1) wait_vmcnt<(STAGES - 1) * kLoadsTile>();
-    issue_tile(jj);
+  bf16x8 qreg[2][12];
+  for (int jj = 0; jj < STAGES - kQStages && jj < ntiles; ++jj) issue_tile(jj);
+  // queries landed (they are older than the tile loads; vector-memory operations retire in order) ...
+  if (ntiles >= STAGES - kQStages) wait_vmcnt<kLoadsTile * (STAGES - kQStages)>(); else wait_vmcnt<0>();
+  __builtin_amdgcn_s_barrier();   // ... in every wave's share
+#pragma unroll
+  for (int nt = 0; nt < 2; ++nt) {
+    const int row = hw * 64 + nt * 32 + c32;                       // q_abs row of this lane's head column
+    const int rrow = PAIRED ? nt * 32 + c32 : row;                 // its RoPE row
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      const unsigned addr = q_lds + row * (kDcb * 2) + (((2 * ks + g) ^ (row & 15)) << 4);
+      asm volatile("ds_read_b128 %0, %1" : "=a"(qreg[nt][ks]) : "v"(addr) : "memory");
+    }
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      const unsigned addr = q_lds + kHeadsWG * (kDcb * 2) + rrow * (kDr * 2) + (((2 * ks + g) ^ ((rrow >> 1) & 7)) << 4);
+      asm volatile("ds_read_b128 %0, %1" : "=a"(qreg[nt][8 + ks]) : "v"(addr) : "memory");
+    }
   }
+  // the reads above are asm, invisible to the compiler's wait counts: wait for them here (the tile loads
+  // may stay in flight), then let every wave finish before the stages under the queries are refilled
+  wait_vm_lgkm<63>();
+  __builtin_amdgcn_s_barrier();
+  for (int jj = STAGES - kQStages; jj < STAGES && jj < ntiles; ++jj) issue_tile(jj);
   if (ntiles >= STAGES) wait_vmcnt<kLoadsTile * (STAGES - 2)>(); else wait_vmcnt<0>();
   __builtin_amdgcn_s_barrier();   // tiles 0 and 1 landed for every wave
   f32x16 sa0, sa1, sb0, sb1;
@@ -655,8 +692,11 @@ int launch_seq_order(const DecodeArgs& a) {
 }
 
 bool decode_mfma_supported(const DecodeArgs& a) {
+  // (the query rows are addressed with 32-bit byte offsets from q_abs / q_rope)
   return a.dtype == MLRA_BF16 && a.d_cb == kDcb && a.d_r == kDr && a.page_size % kTile == 0 &&
-         a.plan.chunk_tokens % kTile == 0;
+         a.plan.chunk_tokens % kTile == 0 &&
+         (long long)a.batch * a.n_blocks * a.h * (kDcb * 2) < (1LL << 32) &&
+         (long long)a.batch * a.h * a.groups * (kDr * 2) < (1LL << 32);
 }
 
 // Blocks that serve at most 64 heads in their last 128-head group leave half of the plain form's waves
