@@ -87,6 +87,13 @@ def test_mlra2_bf16_split_context():
     _check(gen.make_decode_inputs(wl, poison=True))
 
 
+def test_mlra2_length_proportional_chunks_on_a_ragged_long_batch():
+    # two blocks per workgroup and chunk lengths that follow the sequence lengths (chunks of 128 tiles or more)
+    lens = np.array([131072, 40000, 300, 0, 5000, 64, 9000, 70000], dtype=np.int32)
+    wl = gen.WORKLOADS["M2"].scaled(batch=len(lens), n_min=0, n_max=int(lens.max()))
+    _check(gen.make_decode_inputs(wl, poison=True, seq_lens=lens), seqs=[0, 1, 2, 3, 5, 7])
+
+
 def test_mlra2_two_blocks_is_gla2_shape():
     # n_blocks = 2: one block per group (GLA-2, Eq. (3)); d_cb = 2 d_h runs on the generic kernels
     wl = gen.WORKLOADS["C1"].scaled(name="gla2-shape", batch=2, n_blocks=2, d_cb=64, d_h=32, h=8, d_r=16,

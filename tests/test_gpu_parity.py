@@ -256,9 +256,9 @@ def test_longest_first_order_with_ties_and_empty_sequences():
 
 
 def test_length_proportional_chunks_on_a_ragged_long_batch():
-    # split mode with chunks of 64 tiles or more: chunk lengths follow the sequence lengths (one sequence
+    # split mode with chunks of 128 tiles or more: chunk lengths follow the sequence lengths (one sequence
     # takes most of the chunk slots, one is shorter than a single chunk, one is empty)
-    lens = np.array([66000, 20000, 300, 0], dtype=np.int32)
+    lens = np.array([131072, 40000, 300, 0], dtype=np.int32)
     wl = gen.WORKLOADS["C4"].scaled(batch=len(lens), n_min=0, n_max=int(lens.max()))
     inp = gen.make_decode_inputs(wl, seq_lens=lens)
     out = _check_mlra(inp)
