@@ -110,6 +110,15 @@ MLRA_API int mlra_decode_attn(const mlra_cache* cache, int32_t batch, int32_t h,
                      const void* q_rope, const void* w_uv, float softmax_scale, float out_scale, void* out,
                      int32_t out_dtype, float* lse, void* workspace, size_t workspace_bytes, void* stream);
 
+/* Gated attention output (Appendix E, "Gated Attention": O^attn = Attention(H') . G with
+ * G = sigma(H W^G) in R^{h d_h}): mlra_decode_attn with its output multiplied elementwise by
+ *   gate [batch][h][d_h] of the cache dtype, the values of G (the nonlinearity is applied upstream).
+ * The product is taken in fp32 before the output is rounded. */
+MLRA_API int mlra_decode_attn_gated(const mlra_cache* cache, int32_t batch, int32_t h, int32_t d_h, const void* q_abs,
+                           const void* q_rope, const void* w_uv, const void* gate, float softmax_scale,
+                           float out_scale, void* out, int32_t out_dtype, float* lse, void* workspace,
+                           size_t workspace_bytes, void* stream);
+
 /* Several query tokens per sequence (multi-token prediction / speculative decoding): the causal tail of
  * Eq. (5).  The q_len newest rows of every sequence are already cached (seq_lens counts them); query j
  * of sequence s sits at row seq_lens[s] - q_len + j and attends to rows 0 .. seq_lens[s] - q_len + j

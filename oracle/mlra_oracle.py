@@ -13,6 +13,7 @@ What each function follows (all citations are to the MLRA paper):
   * mlra_decode_absorbed    -- the three steps per block, block outputs summed (Eq. (5)),
     times the output rescale alpha_attn of Eq. (10).
   * mla_decode              -- the same with a single block of d_c channels (Section 2.1).
+  * gated_output            -- Appendix E: the attention output times the gate G, elementwise.
   * mlra_decode_multi       -- Eq. (5) for the last q_len rows of a sequence at once: row n - q_len + j
     attends to its prefix {0..n - q_len + j} (Section 2.1 states attention for a position over its
     prefix), i.e. the causal tail of the n x n attention.
@@ -174,6 +175,11 @@ def mlra_decode_multi(q_nope, q_rope, C, KR, W_UK, W_UV, n_blocks, tau, out_scal
         O[j] = mlra_decode_absorbed(q_nope[j], np.asarray(q_rope)[j], np.asarray(C)[:n_eff], np.asarray(KR)[:n_eff],
                                     W_UK, W_UV, n_blocks, tau, out_scale)
     return O
+
+
+def gated_output(O, G):
+    """Appendix E ("Gated Attention"): O^attn = Attention(H') (.) G, elementwise, with G = sigma(H W^G) given."""
+    return np.asarray(O, np.float64) * np.asarray(G, np.float64)
 
 
 def mla_decode(q_nope, q_rope, C, KR, W_UK, W_UV, tau):

@@ -21,7 +21,7 @@ MLRA_BF16, MLRA_F32 = 0, 1
 
 EXPORTS = ("mlra_strerror", "mlra_append_kv", "mlra_absorb_q", "mlra_decode_workspace_bytes",
            "mlra_decode_attn", "mla_decode_attn", "mlra2_absorb_q", "mlra2_decode_workspace_bytes",
-           "mlra2_decode_attn", "mlra_decode_multi_workspace_bytes", "mlra_decode_attn_multi",
+           "mlra2_decode_attn", "mlra_decode_attn_gated", "mlra_decode_multi_workspace_bytes", "mlra_decode_attn_multi",
            "mlra_pre_attention_workspace_bytes", "mlra_pre_attention",
            "gqa_decode_workspace_bytes", "gqa_decode_attn", "mlra_kernel_timing_begin",
            "mlra_kernel_timing_end")
@@ -75,6 +75,8 @@ def load_library() -> ctypes.CDLL:
     lib.mlra2_decode_workspace_bytes.argtypes = lib.mlra_decode_workspace_bytes.argtypes
     lib.mlra2_decode_attn.restype = ctypes.c_int
     lib.mlra2_decode_attn.argtypes = lib.mlra_decode_attn.argtypes
+    lib.mlra_decode_attn_gated.restype = ctypes.c_int
+    lib.mlra_decode_attn_gated.argtypes = [cp, i32, i32, i32, vp, vp, vp, vp, f32, f32, vp, i32, vp, vp, sz, vp]
     lib.mlra_decode_multi_workspace_bytes.restype = sz
     lib.mlra_decode_multi_workspace_bytes.argtypes = [i32] * 7
     lib.mlra_decode_attn_multi.restype = ctypes.c_int
@@ -214,6 +216,29 @@ def mla_decode_attn(cache: Cache, q_abs: torch.Tensor, q_rope: torch.Tensor, w_u
                     workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
     return _decode("mla_decode_attn", cache, q_abs, q_rope, w_uv, softmax_scale, 1.0, out, out_dtype, lse,
                    workspace, stream)
+
+
+def mlra_decode_attn_gated(cache: Cache, q_abs: torch.Tensor, q_rope: torch.Tensor, w_uv: torch.Tensor,
+                           gate: torch.Tensor, softmax_scale: float, out_scale: float = 1.0,
+                           out: Optional[torch.Tensor] = None, out_dtype: Optional[torch.dtype] = None,
+                           lse: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                           stream=None) -> torch.Tensor:
+    """mlra_decode_attn with the output multiplied elementwise by gate [batch][h][d_h] (Appendix E)."""
+    lib = load_library()
+    cs = cache.struct()
+    batch, n_blocks, h, d_cb = q_abs.shape
+    d_h = w_uv.shape[2] // h
+    assert gate.shape == (batch, h, d_h) and gate.dtype == q_abs.dtype
+    if out is None:
+        out = torch.empty((batch, h, d_h), dtype=out_dtype or q_abs.dtype, device=q_abs.device)
+    if workspace is None:
+        need = mlra_decode_workspace_bytes(batch, h, n_blocks, d_cb, cache.max_seq_len)
+        workspace = torch.empty(need, dtype=torch.uint8, device=q_abs.device)
+    _check(lib.mlra_decode_attn_gated(ctypes.byref(cs), batch, h, d_h, _ptr(q_abs), _ptr(q_rope), _ptr(w_uv),
+                                      _ptr(gate), float(softmax_scale), float(out_scale), _ptr(out), _dt(out.dtype),
+                                      _ptr(lse), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                      _stream(stream)), "mlra_decode_attn_gated")
+    return out
 
 
 def mlra_decode_multi_workspace_bytes(batch: int, q_len: int, h: int, n_blocks: int, d_cb: int, page_size: int,

@@ -255,7 +255,7 @@ template <typename T, typename TO>
 __global__ __launch_bounds__(256) void merge_upproj_generic_kernel(
     const float* __restrict__ part_z, const float* __restrict__ part_ml, const int32_t* __restrict__ seq_lens,
     const T* __restrict__ w_uv, TO* __restrict__ out, float* __restrict__ lse, int h, int d_h, int n_blocks,
-    int d_cb, int n_splits, int chunk, float out_scale, int groups) {
+    int d_cb, int n_splits, int chunk, float out_scale, int groups, const T* __restrict__ gate) {
   extern __shared__ float zs[];  // [bpg*d_cb]
   // output head blockIdx.x = grp * h + head; its branches are the bpg blocks of group grp (Eq. (6);
   // one group of all blocks is Eq. (5))
@@ -292,7 +292,8 @@ __global__ __launch_bounds__(256) void merge_upproj_generic_kernel(
     float acc = 0.f;
     for (int r = 0; r < d_cg; ++r)
       acc += zs[r] * load_f32(w_uv, ((size_t)b0 * d_cb + r) * ld + (size_t)head * d_h + j);
-    store_f32(out, ((size_t)s * h * groups + blockIdx.x) * d_h + j, acc * out_scale);
+    const size_t o = ((size_t)s * h * groups + blockIdx.x) * d_h + j;
+    store_f32(out, o, acc * out_scale * (gate ? load_f32(gate, o) : 1.f));   // gate: Appendix E, O^attn = Attention . G
   }
 }
 
@@ -302,7 +303,7 @@ int launch_merge_upproj_generic(const DecodeArgs& a) {
 #define MLRA_MERGE(T, TO)                                                                                       \
   merge_upproj_generic_kernel<T, TO><<<grid, 256, lds, a.stream>>>(                                             \
       a.part_z, a.part_ml, a.seq_lens, (const T*)a.w_uv, (TO*)a.out, a.lse, a.h, a.d_h, a.n_blocks, a.d_cb,     \
-      a.plan.n_splits, a.plan.chunk_tokens, a.out_scale, a.groups)
+      a.plan.n_splits, a.plan.chunk_tokens, a.out_scale, a.groups, (const T*)a.gate)
   if (a.dtype == MLRA_BF16 && a.out_dtype == MLRA_BF16) MLRA_MERGE(bf16_t, bf16_t);
   else if (a.dtype == MLRA_BF16) MLRA_MERGE(bf16_t, float);
   else if (a.out_dtype == MLRA_BF16) MLRA_MERGE(float, bf16_t);

@@ -81,7 +81,8 @@ static size_t decode_ws_bytes(int batch, int h, int n_blocks, int d_cb, const Sp
 // h: heads served by one block (all heads when groups == 1, the heads of one group otherwise)
 static int decode_common(const mlra_cache* c, int batch, int h, int groups, int d_h, const void* q_abs,
                          const void* q_rope, const void* w_uv, float softmax_scale, float out_scale, void* out,
-                         int out_dtype, float* lse, void* workspace, size_t workspace_bytes, void* stream) {
+                         int out_dtype, float* lse, void* workspace, size_t workspace_bytes, void* stream,
+                         const void* gate = nullptr) {
   if (!c || !q_abs || !q_rope || !w_uv || !out) return MLRA_ERR_NULL;
   if (!c->latent || !c->rope || !c->page_table || !c->seq_lens) return MLRA_ERR_NULL;
   if (!valid_dtype(c->dtype) || !valid_dtype(out_dtype)) return MLRA_ERR_DTYPE;
@@ -125,6 +126,7 @@ static int decode_common(const mlra_cache* c, int batch, int h, int groups, int 
   a.out = out;
   a.out_dtype = out_dtype;
   a.lse = lse;
+  a.gate = gate;
   a.dtype = c->dtype;
   a.stream = (hipStream_t)stream;
   timing_mark(0, a.stream);
@@ -240,6 +242,15 @@ int mlra_decode_attn_multi(const mlra_cache* c, int32_t batch, int32_t q_len, in
   return decode_common(&c2, units, h, 1, d_h, q_abs, q_rope, w_uv, softmax_scale, out_scale, out, out_dtype, lse,
                        (char*)workspace + lens_bytes + table_bytes, workspace_bytes - lens_bytes - table_bytes,
                        stream);
+}
+
+int mlra_decode_attn_gated(const mlra_cache* cache, int32_t batch, int32_t h, int32_t d_h, const void* q_abs,
+                           const void* q_rope, const void* w_uv, const void* gate, float softmax_scale,
+                           float out_scale, void* out, int32_t out_dtype, float* lse, void* workspace,
+                           size_t workspace_bytes, void* stream) {
+  if (!gate) return MLRA_ERR_NULL;
+  return decode_common(cache, batch, h, 1, d_h, q_abs, q_rope, w_uv, softmax_scale, out_scale, out, out_dtype, lse,
+                       workspace, workspace_bytes, stream, gate);
 }
 
 int mlra2_absorb_q(int32_t batch, int32_t h, int32_t d_h, int32_t n_blocks, int32_t d_cb, const void* q_nope,

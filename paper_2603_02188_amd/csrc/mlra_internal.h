@@ -57,6 +57,7 @@ struct DecodeArgs {
   void* out;
   int out_dtype;
   float* lse;
+  const void* gate;    // optional [batch][groups * h][d_h] of the cache dtype: out is multiplied by it elementwise
   float* part_z;   // [batch][n_blocks][n_splits][h][d_cb]
   float* part_ml;  // [batch][n_blocks][n_splits][h][2]  (running max, running sum)
   int32_t* seq_order;  // [batch] sequence ids, longest first (workspace); filled by the MFMA launcher when used

@@ -98,7 +98,8 @@ template <typename TO>
 __global__ __launch_bounds__(256) void merge_upproj_mfma_kernel(
     const float* __restrict__ part_z, const float* __restrict__ part_ml, const int32_t* __restrict__ seq_lens,
     const bf16_t* __restrict__ w_uv, TO* __restrict__ out, float* __restrict__ lse, int batch, int h, int nb_total,
-    int d_cb, int n_splits, int chunk, const int32_t* __restrict__ chunk_tab, float out_scale) {
+    int d_cb, int n_splits, int chunk, const int32_t* __restrict__ chunk_tab, float out_scale,
+    const bf16_t* __restrict__ gate) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   // blockIdx.z = head group (Eq. (6)); one group of all blocks is Eq. (5).  h: heads per block; this
   // workgroup's head is h * group + head in out, and its branches are blocks [b0, b0 + n_blocks).
@@ -280,7 +281,10 @@ __global__ __launch_bounds__(256) void merge_upproj_mfma_kernel(
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
     const int s = m0 + (r >> 2) * 8 + g * 4 + (r & 3);
-    if (s < batch) store_f32(out, ((size_t)s * h * gridDim.z + blockIdx.z * h + head) * kDh + j, acc[r] * out_scale);
+    if (s < batch) {
+      const size_t o = ((size_t)s * h * gridDim.z + blockIdx.z * h + head) * kDh + j;
+      store_f32(out, o, acc[r] * out_scale * (gate ? bf16_to_f32(gate[o]) : 1.f));   // gate: Appendix E
+    }
   }
 }
 
@@ -321,11 +325,13 @@ int launch_merge_upproj_mfma(const DecodeArgs& a) {
   if (a.out_dtype == MLRA_BF16)
     merge_upproj_mfma_kernel<bf16_t><<<grid, 256, lds, a.stream>>>(
         a.part_z, a.part_ml, a.seq_lens, (const bf16_t*)a.w_uv, (bf16_t*)a.out, a.lse, a.batch, a.h, a.n_blocks, a.d_cb,
-        a.plan.n_splits, a.plan.chunk_tokens, a.balanced ? a.chunk_tab : nullptr, a.out_scale);
+        a.plan.n_splits, a.plan.chunk_tokens, a.balanced ? a.chunk_tab : nullptr, a.out_scale,
+        (const bf16_t*)a.gate);
   else
     merge_upproj_mfma_kernel<float><<<grid, 256, lds, a.stream>>>(
         a.part_z, a.part_ml, a.seq_lens, (const bf16_t*)a.w_uv, (float*)a.out, a.lse, a.batch, a.h, a.n_blocks, a.d_cb,
-        a.plan.n_splits, a.plan.chunk_tokens, a.balanced ? a.chunk_tab : nullptr, a.out_scale);
+        a.plan.n_splits, a.plan.chunk_tokens, a.balanced ? a.chunk_tab : nullptr, a.out_scale,
+        (const bf16_t*)a.gate);
   return check_launch();
 }
 

@@ -69,6 +69,9 @@ def test_null_and_shape_errors_are_reported_on_the_host():
                                  null) == -2
     assert lib.mlra2_decode_attn(ctypes.byref(cs2), 1, 8, 64, one, one, one, 0.1, 1.0, one, 1, null, null, 0,
                                  null) == -4
+    # gated output needs its gate
+    assert lib.mlra_decode_attn_gated(ctypes.byref(cs2), 1, 8, 64, one, one, one, null, 0.1, 1.0, one, 1, null, one,
+                                      1 << 30, null) == -1
     # several query tokens: bad q_len, workspace too small, null cache
     assert lib.mlra_decode_attn_multi(ctypes.byref(cs2), 1, 0, 8, 64, one, one, one, 0.1, 1.0, one, 1, null, one,
                                       1 << 30, null) == -2

@@ -265,6 +265,26 @@ def test_length_proportional_chunks_on_a_ragged_long_batch():
     assert np.all(out[3] == 0)
 
 
+@pytest.mark.parametrize("key,out_dtype", [("C1", torch.float32), ("C3", torch.float32), ("C3", torch.bfloat16)])
+def test_gated_output(key, out_dtype):
+    # Appendix E: the attention output times a gate G = sigmoid(...) in (0, 1), elementwise
+    wl = gen.WORKLOADS[key].scaled(batch=3, n_min=40, n_max=700)
+    inp = gen.make_decode_inputs(wl)
+    rng = np.random.default_rng([wl.seed, 0x6A7E])
+    gate = gen.to_storage((1.0 / (1.0 + np.exp(-rng.standard_normal((wl.batch, wl.h, wl.d_h))))).astype(np.float32),
+                          wl.dtype)
+    cache = device_cache(inp)
+    q_nope, q_rope, w_uk, w_uv = device_queries_weights(inp)
+    q_abs = mlra.mlra_absorb_q(q_nope, w_uk)
+    out = host(mlra.mlra_decode_attn_gated(cache, q_abs, q_rope, w_uv, to_device(gate, wl.dtype), wl.tau, 0.5,
+                                           out_dtype=out_dtype))
+    ref, _ = _oracle_out(inp, 0.5)
+    ref = orc.gated_output(ref, gen.to_f64(gate, wl.dtype))
+    err = max_rel_err(out, ref)
+    _say(f"[case] gated {wl.name} out={out_dtype}: max rel err {err:.3e}")
+    assert err <= TOL[wl.dtype]
+
+
 def test_workspace_too_small_is_refused_on_device_pointers():
     wl = gen.WORKLOADS["C1"]
     inp = gen.make_decode_inputs(wl)

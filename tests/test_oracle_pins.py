@@ -620,3 +620,12 @@ def test_multi_token_decode_causality_and_single_token_case():
     short = orc.mlra_decode_multi(qn, qr, c["C"][:2], c["KR"][:2], *args)
     assert np.all(short[0] == 0.0) and np.any(short[1] != 0.0)
     assert np.array_equal(short[1], orc.mlra_decode_absorbed(qn[1], qr[1], c["C"][:1], c["KR"][:1], *args))
+
+
+def test_gated_output_is_the_elementwise_product():
+    rng = np.random.default_rng(91)
+    O, G = rng.standard_normal((3, 4)), 1.0 / (1.0 + np.exp(-rng.standard_normal((3, 4))))
+    got = orc.gated_output(O, G)
+    for i in range(3):
+        for p in range(4):
+            assert got[i][p] == O[i][p] * G[i][p]
