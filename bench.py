@@ -26,7 +26,7 @@ def _args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="C3", choices=["C2", "C3", "C4", "C5", "M2"])
+    ap.add_argument("--workload", default="C3", choices=["C2", "C3", "C4", "C5", "M2", "G2"])
     ap.add_argument("--copies", type=int, default=0, help="cache copies to rotate over (0 = enough for ~3 GB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--parity", action="store_true", help="also compare the GPU output with the oracle")
@@ -60,7 +60,10 @@ def _cpu_baseline(inp, max_seconds=25.0):
     done_tokens, done_seqs = 0, 0
     t0 = time.perf_counter()
     outs = []
-    decode_batch = orc.mlra2_decode_batch if wl.groups == 2 else orc.mlra_decode_batch
+    if wl.groups == 2 and wl.n_blocks == 2:
+        decode_batch = orc.gla2_decode_batch
+    else:
+        decode_batch = orc.mlra2_decode_batch if wl.groups == 2 else orc.mlra_decode_batch
     for b in range(wl.batch):
         outs.append(decode_batch(lat, rope, inp.page_table, inp.seq_lens, qn, qr, wk, wv, wl.tau, seqs=[b])[0])
         done_tokens += int(inp.seq_lens[b])
@@ -287,7 +290,7 @@ def main():
 
     res = {
         "metric": "decode attention us/step, %s bf16 (append_kv + absorb_q + decode_attn)"
-                  % ("MLRA-2" if wl.groups == 2 else "MLRA-4"),
+                  % ("GLA-2" if wl.groups == 2 and wl.n_blocks == 2 else "MLRA-2" if wl.groups == 2 else "MLRA-4"),
         "value": ms_per_step * 1e3, "unit": "us/step", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",

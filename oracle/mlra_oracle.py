@@ -13,6 +13,8 @@ What each function follows (all citations are to the MLRA paper):
   * mlra_decode_absorbed    -- the three steps per block, block outputs summed (Eq. (5)),
     times the output rescale alpha_attn of Eq. (10).
   * mla_decode              -- the same with a single block of d_c channels (Section 2.1).
+  * gla2_decode             -- GLA-2 (Section 2.3, Eq. (3)-(4)): head i attends through the latent head of its
+    group, [C_(2g), C_(2g+1)], with that group's matrices; the absorbed three steps on 2 d_cb channels.
   * gated_output            -- Appendix E: the attention output times the gate G, elementwise.
   * mlra_decode_multi       -- Eq. (5) for the last q_len rows of a sequence at once: row n - q_len + j
     attends to its prefix {0..n - q_len + j} (Section 2.1 states attention for a position over its
@@ -174,6 +176,23 @@ def mlra_decode_multi(q_nope, q_rope, C, KR, W_UK, W_UV, n_blocks, tau, out_scal
         n_eff = max(0, n - (q_len - 1 - j))
         O[j] = mlra_decode_absorbed(q_nope[j], np.asarray(q_rope)[j], np.asarray(C)[:n_eff], np.asarray(KR)[:n_eff],
                                     W_UK, W_UV, n_blocks, tau, out_scale)
+    return O
+
+
+def gla2_decode(q_nope, q_rope, C, KR, W_UK_g, W_UV_g, tau):
+    """GLA-2: O_i = Softmax(tau q^N_i ([C_(2g), C_(2g+1)] W^(g),UK_:,(i))^T + tau q^R_i KR^T) [C_(2g), C_(2g+1)] W^(g),UV_:,(i),
+    g = gamma(i).  q_nope [h][d_h], C [n][d_c] (two latent heads of d_c/2 channels side by side),
+    W_UK_g / W_UV_g [2][d_c/2][(h/2)*d_h].  Returns O [h][d_h]."""
+    q_nope = np.asarray(q_nope, np.float64)
+    q_rope = np.asarray(q_rope, np.float64)
+    C = np.asarray(C, np.float64)
+    h, d_h = q_nope.shape
+    hg, d_g = h // 2, C.shape[1] // 2
+    O = np.zeros((h, d_h))
+    for g in range(2):
+        heads = slice(g * hg, (g + 1) * hg)
+        O[heads] = mla_decode(q_nope[heads], q_rope[heads], C[:, g * d_g:(g + 1) * d_g], KR,
+                              np.asarray(W_UK_g, np.float64)[g], np.asarray(W_UV_g, np.float64)[g], tau)
     return O
 
 
@@ -474,6 +493,18 @@ def mlra2_decode_batch(latent_pool, rope_pool, page_table, seq_lens, q_nope, q_r
         O[k], L[k] = mlra2_decode_absorbed(q_nope[b], q_rope[b], C, KR, W_UK_g, W_UV_g, tau,
                                            out_scale, return_lse=True)
     return (O, L) if return_lse else O
+
+
+def gla2_decode_batch(latent_pool, rope_pool, page_table, seq_lens, q_nope, q_rope, w_uk, w_uv, tau, seqs=None):
+    """GLA-2 on a cache of two latent heads (pool [P][2][page][d_c/2]); w_uk / w_uv [2][d_c/2][(h/2)*d_h]."""
+    assert latent_pool.shape[1] == 2
+    seqs = list(range(len(seq_lens))) if seqs is None else list(seqs)
+    h, d_h = q_nope.shape[1], q_nope.shape[2]
+    O = np.zeros((len(seqs), h, d_h))
+    for k, b in enumerate(seqs):
+        C, KR = gather_sequence(latent_pool, rope_pool, page_table[b], int(seq_lens[b]))
+        O[k] = gla2_decode(q_nope[b], q_rope[b], C, KR, w_uk, w_uv, tau)
+    return O
 
 
 def gqa_decode_batch(k_pool, v_pool, page_table, seq_lens, q, scale, seqs=None):

@@ -17,6 +17,14 @@
 // runs block 2 pair + hw for all 64 heads on tokens [32 tw, +32).  Each wave does exactly the work it
 // does in the plain form; the tile in LDS holds both blocks' latent rows and the shared RoPE rows
 // (40 KiB per stage, four stages), so the RoPE rows are fetched once for the two branches.
+//
+// GLA form, for the GLA-2 baseline (Section 2.3, Eq. (3)-(4)): one latent head of 256 channels serves 64
+// heads.  The workgroup is laid out as in the PAIRED form, but the two "blocks" are the two 128-channel
+// halves of the one latent head: wave (hw, tw) computes the partial scores of its half (and of half of
+// the RoPE channels), the two waves of a token half exchange their partial scores through LDS and add
+// them (a + b and b + a are the same float, so both hold identical scores and take identical softmax
+// decisions), and each then accumulates Z for its own 128 channels.  Three stages of 40 KiB plus a
+// 32 KiB exchange buffer; two workgroup barriers per tile.
 #include "mfma_tile.h"
 
 #include <type_traits>
@@ -104,10 +112,13 @@ __global__ __launch_bounds__(256) void plan_chunks_kernel(const int32_t* __restr
   for (int u = n_active + threadIdx.x; u < batch * max_slots; u += 256) unit_tab[u] = -1;
 }
 
-template <int STAGES, bool PAIRED>
+template <int STAGES, int MODE>   // MODE 0: plain, 1: PAIRED, 2: GLA (see the head of the file)
 __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
-  constexpr int kBlocksWG = PAIRED ? 2 : 1;                 // latent blocks whose tiles share a stage
+  constexpr bool PAIRED = MODE != 0;                        // two 128-channel latent tiles per stage, 64 heads
+  constexpr bool GLA = MODE == 2;                           // ... that are the halves of one 256-channel block
+  constexpr int kLatRow = GLA ? 2 * kDcb * 2 : kDcb * 2;    // bytes of one cached latent row of a block
+  constexpr int kBlocksWG = PAIRED ? 2 : 1;                 // latent tiles that share a stage
   constexpr int kRopeOff = kBlocksWG * kLatBytes;           // RoPE tile behind the latent tile(s)
   constexpr int kStageB = kRopeOff + kRopeBytes;            // 24 KiB, or 40 KiB
   constexpr int kLoadsTile = 4 * kBlocksWG + 2;             // direct-to-LDS loads per wave and tile
@@ -117,7 +128,7 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
   // the 8 XCDs, each with its own L2, so the members of such a family are given ids 8 apart: they land
   // on one XCD at about the same time and all but the first read of a shared row hit in that L2.
   const int n_hg = (p.h + kHeadsPerWG - 1) / kHeadsPerWG;
-  const int fam = p.n_blocks / kBlocksWG * n_hg;
+  const int fam = (GLA ? p.n_blocks : p.n_blocks / kBlocksWG) * n_hg;
   const int n_units = p.n_splits * p.batch;
   const int full_units = n_units & ~7;
   int wg = blockIdx.x, su, member;
@@ -145,8 +156,8 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
   const int hgrp = member % n_hg;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int hw = wave & 1, tw = wave >> 1, g = lane >> 5, c32 = lane & 31;
-  const int blk0 = member / n_hg * kBlocksWG;               // first (or only) block of this workgroup
-  const int blk = PAIRED ? blk0 + hw : blk0;                // this wave's block
+  const int blk0 = member / n_hg * (GLA ? 1 : kBlocksWG);   // first (or only) block of this workgroup
+  const int blk = (PAIRED && !GLA) ? blk0 + hw : blk0;      // this wave's block
   const int wave_head0 = PAIRED ? hgrp * 64 : hgrp * kHeadsWG + hw * 64;   // this wave's first head
 
   // ---- absorbed + RoPE queries: MFMA B operands, resident in accumulation registers for the whole chunk
@@ -168,10 +179,11 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
 #pragma unroll
     for (int q = 0; q < 8; ++q) {                                  // q_abs rows 32 w + 4 q + lane / 16
       const int row = 32 * wave + 4 * q + (lane >> 4);
-      const int row_blk = PAIRED ? blk0 + (row >> 6) : blk0;
+      const int row_blk = (PAIRED && !GLA) ? blk0 + (row >> 6) : blk0;
       const int head = min(PAIRED ? hgrp * 64 + (row & 63) : hgrp * kHeadsWG + row, p.h - 1);
-      const unsigned voff = ((unsigned)(seq * p.n_blocks + row_blk) * p.h + head) * (kDcb * 2) +
-                            (((lane & 15) ^ (row & 15)) << 4);
+      // (GLA: LDS rows 64..127 hold channels 128..255 of the same 64 heads)
+      const unsigned voff = ((unsigned)(seq * p.n_blocks + row_blk) * p.h + head) * kLatRow +
+                            (GLA ? (row >> 6) * (kDcb * 2) : 0) + (((lane & 15) ^ (row & 15)) << 4);
       set_m0(q_lds + (32 * wave_u + 4 * q) * (kDcb * 2));
       lds_dma16<0>(p.q_abs, voff);
     }
@@ -214,13 +226,16 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
   unsigned lat_voff[4], rope_voff[2];
 #pragma unroll
   for (int q = 0; q < 4; ++q)
-    lat_voff[q] = (lane >> 4) * (kDcb * 2) + (((lane & 15) ^ lat_swz(4 * q + (lane >> 4))) << 4);
+    // (the instruction offset 1024 q moves both sides; rows twice as long need the rest of the step here)
+    lat_voff[q] = (lane >> 4) * kLatRow + (((lane & 15) ^ lat_swz(4 * q + (lane >> 4))) << 4) +
+                  q * (4 * kLatRow - 1024);
 #pragma unroll
   for (int q = 0; q < 2; ++q)
     rope_voff[q] = (lane >> 3) * (kDr * 2) + (((lane & 7) ^ rope_swz(8 * q + (lane >> 3))) << 4);
-  const size_t lat_page_bytes = (size_t)p.n_blocks * p.page_size * (kDcb * 2);
+  const size_t lat_page_bytes = (size_t)p.n_blocks * p.page_size * kLatRow;
   const size_t rope_page_bytes = (size_t)p.page_size * (kDr * 2);
-  const size_t lat_plane_bytes = (size_t)p.page_size * (kDcb * 2);     // one block's rows inside a page
+  const size_t lat_plane_bytes = (size_t)p.page_size * kLatRow;        // one block's rows inside a page
+  const size_t lat_half_step = GLA ? kDcb * 2 : lat_plane_bytes;       // from the first latent tile's source to the second's
   const char* lat_blk = (const char*)p.latent + (size_t)blk0 * lat_plane_bytes;
   int issue_slot = t0 % p.page_size;   // slot of the next tile to issue inside its page (tiles go in order)
   int issue_stage = 0;
@@ -235,7 +250,7 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
     const unsigned page = (unsigned)issue_page;
     iss_last = min(kTile, t1 - t0 - jj * kTile) - 1;
     // start of this tile's latent rows (block plane blk) and RoPE rows inside the page
-    iss_lat = lat_blk + page * lat_page_bytes + (unsigned)issue_slot * (unsigned)(kDcb * 2);
+    iss_lat = lat_blk + page * lat_page_bytes + (unsigned)issue_slot * (unsigned)kLatRow;
     iss_rope = (const char*)p.rope + page * rope_page_bytes + (unsigned)issue_slot * (unsigned)(kDr * 2);
     iss_stage = lds_base + issue_stage * kStageB;
   };
@@ -243,7 +258,7 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
   auto issue_full_part = [&](int part) {
     if (part < 4 * kBlocksWG) {
       const int jb = part >> 2, q = part & 3;
-      const char* src = iss_lat + jb * lat_plane_bytes + wave_u * 4096;
+      const char* src = iss_lat + jb * lat_half_step + wave_u * (16 * kLatRow);
       if (q == 0) set_m0(iss_stage + jb * kLatBytes + wave_u * 4096);
       if (q == 0) lds_dma16<0>(src, lat_voff[0]);
       if (q == 1) lds_dma16<1024>(src, lat_voff[1]);
@@ -266,7 +281,7 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
         const int t = (wave * 4 + q) * 4 + (lane >> 4);          // 0..63
         const unsigned row = (unsigned)min(t, iss_last);           // 0..last
         set_m0(iss_stage + jb * kLatBytes + wave_u * 4096 + q * 1024);
-        lds_dma16<0>(iss_lat + jb * lat_plane_bytes, row * (kDcb * 2) + (((lane & 15) ^ lat_swz(t)) << 4));
+        lds_dma16<0>(iss_lat + jb * lat_half_step, row * kLatRow + (((lane & 15) ^ lat_swz(t)) << 4));
       }
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
@@ -425,6 +440,7 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
   // ---- prologue: every stage gets a tile; scores and column maxima of tile 0; K operands of tile 1 ----
   bf16x8 qreg[2][12];
   for (int jj = 0; jj < STAGES - kQStages && jj < ntiles; ++jj) issue_tile(jj);
+  if (GLA && tid < 4) ((float*)(smem + STAGES * kStageB))[tid] = 0.f;   // the zeros some RoPE reads below take
   // queries landed (they are older than the tile loads; vector-memory operations retire in order) ...
   if (ntiles >= STAGES - kQStages) wait_vmcnt<kLoadsTile * (STAGES - kQStages)>(); else wait_vmcnt<0>();
   __builtin_amdgcn_s_barrier();   // ... in every wave's share
@@ -440,7 +456,10 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
       const unsigned addr = q_lds + kHeadsWG * (kDcb * 2) + rrow * (kDr * 2) + (((2 * ks + g) ^ ((rrow >> 1) & 7)) << 4);
-      asm volatile("ds_read_b128 %0, %1" : "=a"(qreg[nt][8 + ks]) : "v"(addr) : "memory");
+      // GLA: the RoPE channels are split between the two waves whose partial scores are added, so that
+      // the RoPE term is counted once; the other wave's channels are read from 16 bytes of zeros
+      const unsigned src = (!GLA || (ks >> 1) == hw) ? addr : lds_base + STAGES * kStageB;
+      asm volatile("ds_read_b128 %0, %1" : "=a"(qreg[nt][8 + ks]) : "v"(src) : "memory");
     }
   }
   // the reads above are asm, invisible to the compiler's wait counts: wait for them here (the tile loads
@@ -465,6 +484,22 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
     // the maxima read the accumulators through asm, which the compiler's MFMA hazard bookkeeping does
     // not see: let the last score MFMA retire first
     asm volatile("s_nop 15\n\ts_nop 15" : "+v"(sa0), "+v"(sa1));
+    if (GLA) {   // add the partner's partial scores of tile 0 (as in the main loop)
+      f32x4* const xb = (f32x4*)(smem + STAGES * kStageB);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        xb[(wave * 8 + i) * 64 + lane] = f32x4{sa0[4 * i], sa0[4 * i + 1], sa0[4 * i + 2], sa0[4 * i + 3]};
+        xb[(wave * 8 + 4 + i) * 64 + lane] = f32x4{sa1[4 * i], sa1[4 * i + 1], sa1[4 * i + 2], sa1[4 * i + 3]};
+      }
+      __syncthreads();
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const f32x4 x0 = xb[((wave ^ 1) * 8 + i) * 64 + lane], x1 = xb[((wave ^ 1) * 8 + 4 + i) * 64 + lane];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { sa0[4 * i + e] += x0[e]; sa1[4 * i + e] += x1[e]; }
+      }
+      __syncthreads();
+    }
     float mx0, mx1;
     col_max2(sa0, sa1, mx0, mx1);
     m_run[0] = mx0 * sc;
@@ -527,6 +562,16 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
       __builtin_amdgcn_sched_barrier(0);
     }
 
+    // GLA: this wave's partial scores of tile j+1 go to the exchange buffer (complete only now: the
+    // stores wait for the last score MFMA); the partner's are added behind MFMAs 2..5 below
+    f32x4* const xbuf = (f32x4*)(smem + STAGES * kStageB);   // [4 waves][8][64 lanes] x 16 bytes
+    if (GLA) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        xbuf[(wave * 8 + i) * 64 + lane] = f32x4{n0[4 * i], n0[4 * i + 1], n0[4 * i + 2], n0[4 * i + 3]};
+        xbuf[(wave * 8 + 4 + i) * 64 + lane] = f32x4{n1[4 * i], n1[4 * i + 1], n1[4 * i + 2], n1[4 * i + 3]};
+      }
+    }
     // ---- block B: 16 MFMAs (m = 0..15: ss = m / 8, mt = (m / 2) % 4, nt = m % 2)
     float mx0 = 0.f, mx1 = 0.f;
 #pragma unroll
@@ -550,6 +595,17 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
       if (FAST && m == 2 + kLoadsTile / 2) issue_end();
       // (the last K read is three MFMAs from the end of the step: the first wait of the next step, which
       // covers every LDS read because a scalar load is in flight, then finds them all returned)
+      if (GLA && m >= 2 && m <= 5) {
+        // partner = the wave with the other channel half and the same token half (the barrier behind MFMA 1
+        // made its stores visible); after MFMA 5 every wave has its sums and the buffer may be rewritten
+        const f32x4* px = xbuf + ((wave ^ 1) * 8 + 2 * (m - 2)) * 64 + lane;
+        const f32x4 x0 = px[0], x1 = px[64];
+        f32x16& dst = (m < 4) ? n0 : n1;
+        const int r0 = 8 * ((m - 2) & 1);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { dst[r0 + e] += x0[e]; dst[r0 + 4 + e] += x1[e]; }
+        if (m == 5) __builtin_amdgcn_s_barrier();
+      }
       if (m >= 2 && m <= 13) load_k_part(st_k2, m - 2, ka);
       if (m == 6) mx0 = max4(max4(n0[0], n0, 0), n0, 4);
       if (m == 8) mx0 = max4(max4(mx0, n0, 8), n0, 12);
@@ -647,16 +703,19 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
   __syncthreads();
   // zbuf row hl = hw * 64 + (head inside the wave's 64): plain form, 128 heads of one block; PAIRED, 64
   // heads of block blk0 then the same 64 heads of block blk0 + 1
+  // (GLA: rows 64..127 are channels 128..255 of the same 64 heads of the one block)
+  constexpr int kZRow = GLA ? 2 * kDcb : kDcb;   // channels of one partial row in the workspace
   for (int idx = tid; idx < kHeadsWG * (kDcb / 4); idx += 256) {
     const int hl = idx / (kDcb / 4), f4 = idx % (kDcb / 4);
-    const int row_blk = PAIRED ? blk0 + (hl >> 6) : blk0;
+    const int row_blk = (PAIRED && !GLA) ? blk0 + (hl >> 6) : blk0;
     const int row_head = PAIRED ? hgrp * 64 + (hl & 63) : hgrp * kHeadsWG + hl;
     const size_t row_unit = ((size_t)seq * p.n_blocks + row_blk) * p.n_splits + split;
     if (row_head < p.h)
-      *(f32x4*)(p.part_z + (row_unit * p.h + row_head) * kDcb + f4 * 4) = *(const f32x4*)(zbuf + hl * kZPitch + f4 * 4);
+      *(f32x4*)(p.part_z + (row_unit * p.h + row_head) * kZRow + (GLA ? (hl >> 6) * kDcb : 0) + f4 * 4) =
+          *(const f32x4*)(zbuf + hl * kZPitch + f4 * 4);
   }
   const size_t unit = ((size_t)seq * p.n_blocks + blk) * p.n_splits + split;
-  if (tw == 0 && g == 0) {
+  if (tw == 0 && g == 0 && !(GLA && hw == 1)) {   // (GLA: both channel halves hold the same m and l)
 #pragma unroll
     for (int nt = 0; nt < 2; ++nt) {
       const int head = wave_head0 + nt * 32 + c32;
@@ -703,14 +762,60 @@ bool decode_mfma_supported(const DecodeArgs& a) {
 // idle; with an even number of blocks the PAIRED form runs two blocks per workgroup instead.
 bool decode_mfma_paired(int h, int n_blocks) { return n_blocks % 2 == 0 && (h - 1) % kHeadsWG < 64; }
 
+// GLA-2 shape: latent heads of 256 channels (Section 2.3); 64 heads per workgroup.
+bool decode_gla_supported(const DecodeArgs& a) {
+  return a.dtype == MLRA_BF16 && a.d_cb == 2 * kDcb && a.d_r == kDr && a.page_size % kTile == 0 &&
+         a.plan.chunk_tokens % kTile == 0 &&
+         (long long)a.batch * a.n_blocks * a.h * (4 * kDcb) < (1LL << 32) &&
+         (long long)a.batch * a.h * a.groups * (kDr * 2) < (1LL << 32);
+}
+
+int launch_decode_gla(const DecodeArgs& a) {
+  static bool configured = false;
+  constexpr int kStagesGla = 3;
+  const int lds = kStagesGla * (2 * kLatBytes + kRopeBytes) + 4 * 8 * 64 * 16;   // stages + score exchange
+  if (!configured) {
+    if (hipFuncSetAttribute((const void*)decode_mfma_kernel<kStagesGla, 2>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
+      return MLRA_ERR_LAUNCH;
+    configured = true;
+  }
+  MfmaParams p;
+  p.latent = (const bf16_t*)a.latent;
+  p.rope = (const bf16_t*)a.rope;
+  p.page_table = a.page_table;
+  p.seq_lens = a.seq_lens;
+  p.q_abs = (const bf16_t*)a.q_abs;
+  p.q_rope = (const bf16_t*)a.q_rope;
+  p.part_z = a.part_z;
+  p.part_ml = a.part_ml;
+  p.page_size = a.page_size;
+  p.max_pages = a.max_pages;
+  p.n_blocks = a.n_blocks;
+  p.h = a.h;
+  p.groups = a.groups;
+  p.n_splits = a.plan.n_splits;
+  p.chunk = a.plan.chunk_tokens;
+  p.batch = a.batch;
+  p.scale_log2 = a.softmax_scale * 1.4426950408889634f;
+  p.chunk_tab = nullptr;
+  p.unit_tab = nullptr;
+  p.seq_order = nullptr;
+  const long long n_wg = (long long)a.plan.n_splits * a.n_blocks * ((a.h + 63) / 64) * a.batch;
+  if (n_wg <= 0 || n_wg > 0x7fffffffLL) return MLRA_ERR_SHAPE;
+  if (n_wg > device_cu_count() && launch_seq_order(a) == MLRA_OK) p.seq_order = a.seq_order;
+  decode_mfma_kernel<kStagesGla, 2><<<dim3((unsigned)n_wg), 256, lds, a.stream>>>(p);
+  return check_launch();
+}
+
 int launch_decode_mfma(const DecodeArgs& a) {
   static bool configured = false;
   const bool paired = decode_mfma_paired(a.h, a.n_blocks);
   const int lds = paired ? kStagesPaired * (2 * kLatBytes + kRopeBytes) : kStages * kStageBytes;
   if (!configured) {
-    if (hipFuncSetAttribute((const void*)decode_mfma_kernel<kStages, false>,
+    if (hipFuncSetAttribute((const void*)decode_mfma_kernel<kStages, 0>,
                             hipFuncAttributeMaxDynamicSharedMemorySize, kStages * kStageBytes) != hipSuccess ||
-        hipFuncSetAttribute((const void*)decode_mfma_kernel<kStagesPaired, true>,
+        hipFuncSetAttribute((const void*)decode_mfma_kernel<kStagesPaired, 1>,
                             hipFuncAttributeMaxDynamicSharedMemorySize,
                             kStagesPaired * (2 * kLatBytes + kRopeBytes)) != hipSuccess)
       return MLRA_ERR_LAUNCH;
@@ -742,8 +847,8 @@ int launch_decode_mfma(const DecodeArgs& a) {
   p.chunk_tab = a.balanced ? a.chunk_tab : nullptr;
   p.unit_tab = a.balanced ? a.unit_tab : nullptr;
   if (!a.balanced && n_wg > device_cu_count() && launch_seq_order(a) == MLRA_OK) p.seq_order = a.seq_order;
-  if (paired) decode_mfma_kernel<kStagesPaired, true><<<dim3((unsigned)n_wg), 256, lds, a.stream>>>(p);
-  else decode_mfma_kernel<kStages, false><<<dim3((unsigned)n_wg), 256, lds, a.stream>>>(p);
+  if (paired) decode_mfma_kernel<kStagesPaired, 1><<<dim3((unsigned)n_wg), 256, lds, a.stream>>>(p);
+  else decode_mfma_kernel<kStages, 0><<<dim3((unsigned)n_wg), 256, lds, a.stream>>>(p);
   return check_launch();
 }
 

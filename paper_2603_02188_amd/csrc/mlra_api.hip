@@ -134,6 +134,7 @@ static int decode_common(const mlra_cache* c, int batch, int h, int groups, int 
   if (a.plan.target_chunks > 0 && decode_mfma_supported(a) && merge_upproj_mfma_supported(a))
     a.balanced = launch_plan_chunks(a) == MLRA_OK;
   int st = decode_mfma_supported(a) ? launch_decode_mfma(a)
+           : decode_gla_supported(a) ? launch_decode_gla(a)
            : mla_mfma_supported(a)  ? launch_mla_mfma(a)
                                     : launch_decode_generic(a);
   if (st != MLRA_OK) return st;

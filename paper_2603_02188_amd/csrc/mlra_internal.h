@@ -86,7 +86,9 @@ int launch_plan_chunks(const DecodeArgs& a);
 bool mla_mfma_supported(const DecodeArgs& a);
 int launch_mla_mfma(const DecodeArgs& a);
 bool decode_mfma_supported(const DecodeArgs& a);
-bool decode_mfma_paired(int h, int n_blocks);   // two blocks x 64 heads per workgroup instead of one x 128
+bool decode_mfma_paired(int h, int n_blocks);
+bool decode_gla_supported(const DecodeArgs& a);   // 256-channel latent heads (GLA-2)
+int launch_decode_gla(const DecodeArgs& a);   // two blocks x 64 heads per workgroup instead of one x 128
 int launch_decode_mfma(const DecodeArgs& a);
 bool absorb_q_mfma_supported(int d_h, int d_cb, int dtype);
 int launch_absorb_q_mfma(int batch, int h, int d_h, int n_blocks, int groups, int d_cb, const void* q_nope,

@@ -118,6 +118,9 @@ WORKLOADS: Dict[str, Workload] = {
                    d_cb=128, d_r=64, h=128, d_h=128, dtype="bf16", shuffle_pages=True,
                    spare_frac=0.10),
     # MLRA-2 (Eq. (6)) on the shape of C3: same cache, each block serves 64 of the 128 heads
+    # GLA-2 baseline (Eq. (3)) on the same sizes: two latent heads of 2 d_h channels, each for half of the heads
+    "G2": Workload("G2-gla2-bf16", 7, batch=64, n_min=8192, n_max=8192, n_blocks=2,
+                   d_cb=256, d_r=64, h=128, d_h=128, dtype="bf16", groups=2),
     "M2": Workload("M2-mlra2-bf16", 6, batch=64, n_min=8192, n_max=8192, n_blocks=4,
                    d_cb=128, d_r=64, h=128, d_h=128, dtype="bf16", groups=2),
 }

@@ -101,13 +101,41 @@ def test_mlra2_two_blocks_is_gla2_shape():
     inp = gen.make_decode_inputs(wl, poison=True)
     out, lse, _ = _run(inp)
     v = oracle_views(inp)
-    hg = wl.h // 2
-    for s in range(wl.batch):
-        C, KR = orc.gather_sequence(v["latent_pool"], v["rope_pool"], v["page_table"][s], int(v["seq_lens"][s]))
-        for grp in range(2):
-            ref = orc.mla_decode(v["q_nope"][s][grp * hg:(grp + 1) * hg], v["q_rope"][s][grp * hg:(grp + 1) * hg],
-                                 C[:, grp * wl.d_cb:(grp + 1) * wl.d_cb], KR, v["w_uk"][grp], v["w_uv"][grp], wl.tau)
-            assert max_rel_err(out[s][grp * hg:(grp + 1) * hg], ref) <= 1e-2
+    ref = orc.gla2_decode_batch(v["latent_pool"], v["rope_pool"], v["page_table"], v["seq_lens"], v["q_nope"],
+                                v["q_rope"], v["w_uk"], v["w_uv"], wl.tau)
+    assert max_rel_err(out, ref) <= 1e-2
+
+
+def _check_gla2(wl, lens, seqs=None, append=False, out_dtype=torch.float32):
+    print(f"[case] GLA-2 {wl.name} B={wl.batch} h={wl.h} d_cb={wl.d_cb} append={append} out={out_dtype}", flush=True)
+    inp = gen.make_decode_inputs(wl, poison=True, hole=append, seq_lens=lens)
+    out, lse, _ = _run(inp, out_dtype=out_dtype, append=append)
+    ref_inp = gen.make_decode_inputs(wl, poison=True, hole=False, seq_lens=lens) if append else inp
+    v = oracle_views(ref_inp)
+    seqs = list(range(wl.batch)) if seqs is None else seqs
+    ref = orc.gla2_decode_batch(v["latent_pool"], v["rope_pool"], v["page_table"], v["seq_lens"], v["q_nope"],
+                                v["q_rope"], v["w_uk"], v["w_uv"], wl.tau, seqs=seqs)
+    err = max_rel_err(out[seqs], ref)
+    print(f"       max rel err {err:.3e}", flush=True)
+    assert err <= 1e-2
+    for s in seqs:
+        assert np.all(np.isfinite(lse[s])) == (int(lens[s]) > 0)
+
+
+@pytest.mark.parametrize("h", [128, 256, 48])
+def test_gla2_bf16_fast_path_ragged(h):
+    # 256-channel latent heads on the MFMA kernel: 64 heads per group (one workgroup), 128 (two), 24 (partial)
+    wl = gen.WORKLOADS["G2"].scaled(batch=6, h=h, n_min=0, n_max=1500, shuffle_pages=True, spare_frac=0.1)
+    lens = np.array([1500, 64, 1, 777, 0, 65], dtype=np.int32)
+    _check_gla2(wl, lens, append=True)
+    _check_gla2(wl, lens, out_dtype=torch.bfloat16)
+
+
+def test_gla2_bf16_split_context_and_full_size_samples():
+    wl = gen.WORKLOADS["G2"].scaled(batch=2, n_min=5000, n_max=9000)
+    _check_gla2(wl, np.array([9000, 5000], dtype=np.int32))
+    wl = gen.WORKLOADS["G2"]
+    _check_gla2(wl, gen.draw_seq_lens(wl), seqs=[0, 40, 63], out_dtype=torch.bfloat16)
 
 
 def test_mlra2_full_size_sampled_sequences():

@@ -629,3 +629,21 @@ def test_gated_output_is_the_elementwise_product():
     for i in range(3):
         for p in range(4):
             assert got[i][p] == O[i][p] * G[i][p]
+
+
+def test_gla2_against_library_sdpa_on_materialised_keys_and_values():
+    """Eq. (3)-(4): K_i = [C_(2g), C_(2g+1)] W^(g),UK_:,(i) and V_i likewise; plain attention on them."""
+    rng = np.random.default_rng(92)
+    n, h, d_h, d_g, d_r = 19, 4, 8, 16, 4
+    qn, qr = rng.standard_normal((h, d_h)), rng.standard_normal((h, d_r))
+    C, KR = rng.standard_normal((n, 2 * d_g)), rng.standard_normal((n, d_r))
+    WK, WV = rng.standard_normal((2, d_g, (h // 2) * d_h)), rng.standard_normal((2, d_g, (h // 2) * d_h))
+    tau = 1.0 / math.sqrt(d_h + d_r)
+    K = np.zeros((h, n, d_h + d_r)); V = np.zeros((h, n, d_h))
+    for i in range(h):
+        g, ib = i // (h // 2), i % (h // 2)
+        K[i, :, :d_h] = C[:, g * d_g:(g + 1) * d_g] @ WK[g][:, ib * d_h:(ib + 1) * d_h]
+        K[i, :, d_h:] = KR
+        V[i] = C[:, g * d_g:(g + 1) * d_g] @ WV[g][:, ib * d_h:(ib + 1) * d_h]
+    ref = _sdpa(np.concatenate([qn, qr], axis=1), K, V, tau)
+    assert np.max(np.abs(orc.gla2_decode(qn, qr, C, KR, WK, WV, tau) - ref)) <= 1e-10
