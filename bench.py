@@ -107,7 +107,8 @@ def _time_us(fn, iters):
 
 def _baselines(inp, mlra_decode_us):
     """Decode-attention latency of the paper's comparison methods on the same batch (lengths, page table):
-    GQA with 8 KV heads (MFMA streaming kernel, HBM-bound) and MLA with one 512-dim latent (a plain MFMA
+    GQA with 8 KV heads (MFMA streaming kernel, HBM-bound), GLA-2 and MLRA-2 (forms of the MLRA decode
+    kernel, HBM-bound at half the arithmetic of MLRA-4) and MLA with one 512-dim latent (a plain MFMA
     kernel, not software-pipelined like the MLRA one: its ratio reflects kernel maturity as much as the
     method; by bytes moved MLA and full MLRA-4 are equal on one GPU)."""
     import torch
@@ -138,7 +139,27 @@ def _baselines(inp, mlra_decode_us):
                       dtype=torch.uint8, device=dev)
     w_uv1, q_rope1 = up(inp1.w_uv), up(inp1.q_rope)
     mla_us = _time_us(lambda: mlra.mla_decode_attn(cache1, q_abs1, q_rope1, w_uv1, wl.tau, out=out, workspace=ws1), 20)
+    del lat1, cache1
+    # GLA-2 and MLRA-2 on caches of the same size (two 256-channel / four 128-channel latent heads, each
+    # serving half of the heads), same lengths and page table, their own seeded values
+    two = {}
+    for key, shape in (("gla2", dict(n_blocks=2, d_cb=2 * wl.d_cb, groups=2)), ("mlra2", dict(groups=2))):
+        wg = wl.scaled(name=wl.name + "-" + key, **shape)
+        ig = gen.make_decode_inputs(wg, poison=False, seq_lens=inp.seq_lens)
+        cg = mlra.Cache(up(ig.latent_pool), up(ig.rope_pool), up(ig.page_table, False), up(ig.seq_lens, False))
+        qa = mlra.mlra2_absorb_q(up(ig.q_nope), up(ig.w_uk))
+        wsg = torch.empty(mlra.mlra2_decode_workspace_bytes(wg.batch, wg.h, wg.n_blocks, wg.d_cb, cg.max_seq_len),
+                          dtype=torch.uint8, device=dev)
+        w_uvg, q_ropeg = up(ig.w_uv), up(ig.q_rope)
+        two[key] = _time_us(lambda: mlra.mlra2_decode_attn(cg, qa, q_ropeg, w_uvg, wg.tau, out=out, workspace=wsg), 20)
+        del cg, ig
     return {"mlra4_decode_us": mlra_decode_us,
+            "mlra2_decode_us": two["mlra2"], "mlra2_over_mlra4": two["mlra2"] / mlra_decode_us,
+            "gla2_decode_us": two["gla2"], "gla2_over_mlra4": two["gla2"] / mlra_decode_us,
+            "gla2_kernel": "MFMA decode kernel, GLA form (channel halves of a latent head on two waves)",
+            "two_group_note": "MLRA-2 and GLA-2 fill the chip with one workgroup per (sequence, block pair) on this "
+                              "batch: one round, no length balancing, so the longest sequence sets their time; on a "
+                              "uniform batch (workloads M2, G2) they take about 0.7x the MLRA-4 time",
             "gqa_decode_us": gqa_us, "gqa_over_mlra4": gqa_us / mlra_decode_us,
             "gqa_gbps": gqa_bytes["total"] / (gqa_us * 1e-6) / 1e9,
             "gqa_kernel": "MFMA streaming kernel",
