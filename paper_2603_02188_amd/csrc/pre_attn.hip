@@ -8,9 +8,10 @@
 //   2. finish:      sum the slices, RMSNorm + scaling, RoPE, store C^Q (cache dtype) and the cache row
 //   3. skinny GEMM  C^Q [B][d_cq] x [W^UQ | W^QR]              -> fp32 partial sums per K slice
 //   4. finish:      sum the slices, RoPE on the RoPE part, store q_nope and q_rope
-// The bf16 GEMM runs on MFMA with the batch as the M dimension; the weights pass through LDS 256 rows at
+// The bf16 GEMM runs on MFMA with the batch as the M dimension; the weights pass through LDS 128 rows at
 // a time and reach the B operand through transpose reads.  Other dtypes and odd shapes use a plain kernel.
 #include "mlra_internal.h"
+#include "mfma_tile.h"
 
 namespace mlra {
 namespace {
@@ -20,9 +21,11 @@ typedef __attribute__((ext_vector_type(4))) short short4v;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 constexpr int kColsWG = 128;     // output columns per workgroup (32 per wave)
-constexpr int kRowsChunk = 256;  // weight rows resident in LDS at a time (64 KiB)
+constexpr int kRowsChunk = 128;  // weight rows per LDS stage (32 KiB)
 constexpr int kMaxMTiles = 4;    // 32-row tiles of the batch held in accumulators at once
-constexpr int kSets = 2;         // chunks in flight in registers (loads of chunk c + kSets follow the use of chunk c)
+constexpr int kWBytes = kRowsChunk * 256;                 // weight tile of a stage
+__host__ __device__ constexpr int gemm_stage_bytes(int mt) { return kWBytes + 32 * mt * (kRowsChunk * 2); }
+__host__ __device__ constexpr int gemm_stages(int mt) { return mt <= 2 ? 3 : 2; }   // what fits 160 KiB
 
 __device__ __forceinline__ int swz(int t) { return ((t & 3) << 1) | ((t >> 2) & 1); }
 
@@ -31,19 +34,23 @@ __device__ __forceinline__ short4v lds_tr16(const void* p) {
 }
 
 // out_part[slice][m][col0 + j] = sum_{k in slice} A[m][k] W[k][j] for the workgroup's column tile.
-// Column tiles are numbered over the segments side by side; a segment narrower than its last tile is
-// padded with zero columns (never stored).  Per 256-row chunk the weights (64 KiB) and the matching
-// 256 columns of the A rows (up to 128 rows, 64 KiB) sit in LDS; the next chunk of both is in flight in
-// registers while the current one is multiplied.
-constexpr int kAPitch = kRowsChunk * 2 + 16;   // bytes per A row in LDS (+16: rows start on different banks)
-
+// Column tiles are numbered over the segments side by side; a segment narrower than its last tile
+// repeats valid columns in the padding (never stored).  K and the slice length are multiples of
+// kRowsChunk.  Chunks of 128 weight rows (32 KiB) and the matching 128 columns of the A rows stream
+// HBM -> LDS with direct-to-LDS loads through a ring of stages: while one chunk is multiplied the
+// following one or two are in flight, and nothing passes through registers on the way.  16-byte chunk c
+// of weight row r sits at chunk position c ^ swz(r & 7) of its 256-byte LDS row (what the transpose
+// reads want), chunk c of A row r at c ^ (r & 15) (so that the 16 lanes a 128-bit read serves together
+// hit 16 different bank groups).
 template <int MT>   // 32-row tiles of A per workgroup (1..kMaxMTiles)
 __global__ __launch_bounds__(256) void skinny_gemm_mfma_kernel(const bf16_t* __restrict__ A, int lda, int M,
                                                                GemmSegments segs, int K, int rows_per_slice,
                                                                float* __restrict__ out_part, int ld_out) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
-  unsigned char* wt = smem;                            // [256 rows][256 B], 16-byte chunks swizzled
-  unsigned char* at = smem + kRowsChunk * 256;         // [32 * m_tiles rows][kAPitch]
+  constexpr int kStages = gemm_stages(MT);
+  constexpr int kStageB = gemm_stage_bytes(MT);
+  constexpr int kALoads = 2 * MT;                 // direct-to-LDS loads per wave and chunk: A rows ...
+  constexpr int kLoads = 8 + kALoads;             // ... and 8 for the weights
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, c32 = lane & 31;
   // column tile -> segment
   int tile = blockIdx.x, seg = 0;
@@ -51,51 +58,56 @@ __global__ __launch_bounds__(256) void skinny_gemm_mfma_kernel(const bf16_t* __r
     tile -= (segs.cols[seg] + kColsWG - 1) / kColsWG;
     ++seg;
   }
-  const bf16_t* W = (const bf16_t*)segs.w[seg];
+  const unsigned char* Wb = (const unsigned char*)segs.w[seg];
+  const unsigned char* Ab = (const unsigned char*)A;
   const int ldw = segs.cols[seg], n0 = tile * kColsWG;
   const int out_col0 = segs.out_col[seg] + n0;
   const int n_valid = min(kColsWG, ldw - n0);          // multiple of 8
   const int slice = blockIdx.y;
   const int k_begin = slice * rows_per_slice, k_end = min(K, k_begin + rows_per_slice);
+  const int n_chunks = (k_end - k_begin) / kRowsChunk;
   const int m_base = blockIdx.z * (32 * MT);   // (rows past M repeat row M - 1 and are never stored)
+  if (n_chunks <= 0) return;
 
-  // weights: thread t moves 16-byte chunk t % 16 (8 columns) of rows t / 16 + 16 i
-  const int cc = tid & 15, r0 = tid >> 4;
-  const bool col_ok = cc * 8 < n_valid;
-  // A: thread t moves 16-byte chunk t % 32 (8 of the chunk's 256 columns) of rows t / 32 + 8 i
-  const int ac = tid & 31, ar0 = tid >> 5;
-  // kSets register sets: that many chunks are in flight while one is multiplied
-  bf16x8 wreg[kSets][kRowsChunk / 16];
-  bf16x8 areg[kSets][4 * MT];
-  auto fetch = [&](int k0, bf16x8 (&wr)[kRowsChunk / 16], bf16x8 (&ar)[4 * MT]) {
+  // Per-lane source offsets inside a chunk (byte offsets fit 32 bits: checked by the launcher).  A load
+  // fills 1 KiB of LDS = 4 rows x 16 chunks; lane l lands at row l / 16, chunk position l % 16, so it
+  // fetches the chunk that the swizzle puts there.  Wave w moves weight rows [32 w, 32 w + 32) and A rows
+  // [8 MT w, 8 MT w + 8 MT).
+  const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
+  const unsigned wave_u = __builtin_amdgcn_readfirstlane(wave);
+  unsigned w_voff[8], a_voff[kALoads];
 #pragma unroll
-    for (int i = 0; i < kRowsChunk / 16; ++i) {
-      const int k = k0 + r0 + 16 * i;
-      bf16x8 v;
+  for (int q = 0; q < 8; ++q) {
+    const int row = 32 * wave + 4 * q + (lane >> 4);
+    const int col = min(n0 + (((lane & 15) ^ swz(row & 7)) << 3), ldw - 8);
+    w_voff[q] = (unsigned)(row * ldw + col) * 2u;
+  }
 #pragma unroll
-      for (int e = 0; e < 8; ++e) v[e] = (__bf16)0.0f;
-      if (col_ok && k < k_end) v = *(const bf16x8*)(W + (size_t)k * ldw + n0 + cc * 8);
-      wr[i] = v;
+  for (int q = 0; q < kALoads; ++q) {
+    const int row = 8 * MT * wave + 4 * q + (lane >> 4);
+    a_voff[q] = (unsigned)(min(m_base + row, M - 1) * lda + (((lane & 15) ^ (row & 15)) << 3)) * 2u;
+  }
+  // chunk ci of the slice -> stage ci % kStages (chunks past the slice re-read its last chunk: the
+  // number of loads per step stays fixed, which the wait counts below rely on; nobody reads them)
+  int issue_stage = 0;
+  auto issue = [&](int ci) {
+    const int k0 = k_begin + min(ci, n_chunks - 1) * kRowsChunk;
+    const unsigned char* wsrc = Wb + (size_t)k0 * ldw * 2;
+    const unsigned char* asrc = Ab + (size_t)k0 * 2;
+    const unsigned st = lds_base + issue_stage * kStageB;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      mfma_tile::set_m0(st + (wave_u * 8 + q) * 1024);
+      mfma_tile::lds_dma16<0>(wsrc, w_voff[q]);
     }
 #pragma unroll
-    for (int i = 0; i < 4 * MT; ++i) {
-      const int m = ar0 + 8 * i;
-      bf16x8 v;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) v[e] = (__bf16)0.0f;
-      if (k0 + ac * 8 < k_end) v = *(const bf16x8*)(A + (size_t)min(m_base + m, M - 1) * lda + k0 + ac * 8);
-      ar[i] = v;
+    for (int q = 0; q < kALoads; ++q) {
+      mfma_tile::set_m0(st + kWBytes + (wave_u * kALoads + q) * 1024);
+      mfma_tile::lds_dma16<0>(asrc, a_voff[q]);
     }
+    issue_stage = (issue_stage + 1 == kStages) ? 0 : issue_stage + 1;
   };
-  auto stash = [&](const bf16x8 (&wr)[kRowsChunk / 16], const bf16x8 (&ar)[4 * MT]) {
-#pragma unroll
-    for (int i = 0; i < kRowsChunk / 16; ++i) {
-      const int row = r0 + 16 * i;
-      *(bf16x8*)(wt + row * 256 + ((cc ^ swz(row & 7)) << 4)) = wr[i];
-    }
-#pragma unroll
-    for (int i = 0; i < 4 * MT; ++i) *(bf16x8*)(at + (ar0 + 8 * i) * kAPitch + ac * 16) = ar[i];
-  };
+
   // transpose-read offsets: the 16 lanes of a block fetch 4 consecutive rows x 16 output columns
   unsigned tr_off[2];
   {
@@ -117,9 +129,10 @@ __global__ __launch_bounds__(256) void skinny_gemm_mfma_kernel(const bf16_t* __r
       for (int i = 0; i < 16; ++i) acc[t][i] = z;
   }
 
-  // all 16 k-steps of a chunk, straight-line so that the LDS reads of later steps are issued ahead of
-  // the MFMAs of earlier ones (rows past k_end are zero in LDS, on both sides)
-  auto multiply = [&]() {
+  // all 8 k-steps of a chunk, straight-line so that the LDS reads of later steps are issued ahead of
+  // the MFMAs of earlier ones
+  auto multiply = [&](const unsigned char* wt) {
+    const unsigned char* at = wt + kWBytes;
 #pragma unroll
     for (int ks = 0; ks < kRowsChunk / 16; ++ks) {
       const short4v lo = lds_tr16(wt + ks * 16 * 256 + tr_off[0]);
@@ -127,27 +140,27 @@ __global__ __launch_bounds__(256) void skinny_gemm_mfma_kernel(const bf16_t* __r
       const bf16x8 bm = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
 #pragma unroll
       for (int t = 0; t < MT; ++t) {
-        const bf16x8 a = *(const bf16x8*)(at + (t * 32 + c32) * kAPitch + ks * 32 + g * 16);
+        const int row = t * 32 + c32;
+        const bf16x8 a = *(const bf16x8*)(at + row * 256 + (((2 * ks + g) ^ (row & 15)) << 4));
         acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bm, acc[t], 0, 0, 0);
       }
     }
   };
 #pragma unroll
-  for (int c = 0; c < kSets; ++c)
-    if (k_begin + c * kRowsChunk < k_end) fetch(k_begin + c * kRowsChunk, wreg[c], areg[c]);
-  for (int k0 = k_begin; k0 < k_end; k0 += kSets * kRowsChunk) {
-#pragma unroll
-    for (int c = 0; c < kSets; ++c) {
-      const int kc = k0 + c * kRowsChunk;
-      if (kc < k_end) {
-        __syncthreads();            // the previous chunk has been consumed
-        stash(wreg[c], areg[c]);
-        __syncthreads();
-        if (kc + kSets * kRowsChunk < k_end) fetch(kc + kSets * kRowsChunk, wreg[c], areg[c]);
-        multiply();
-      }
-    }
+  for (int ci = 0; ci < kStages - 1; ++ci) issue(ci);
+  int st = 0;
+  for (int ci = 0; ci < n_chunks; ++ci) {
+    // chunk ci has landed in this wave's share (the chunks issued after it may still be in flight) ...
+    mfma_tile::wait_vmcnt<kLoads * (kStages - 2)>();
+    // ... and in everybody's; every wave is also done with chunk ci - 1, whose stage is refilled now
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    issue(ci + kStages - 1);
+    multiply(smem + st * kStageB);
+    asm volatile("" ::: "memory");
+    st = (st + 1 == kStages) ? 0 : st + 1;
   }
+  mfma_tile::wait_vmcnt<0>();   // the loads past the slice target this workgroup's LDS: let them land
   const int j = wave * 32 + c32;
   if (j < n_valid) {
 #pragma unroll
@@ -306,27 +319,28 @@ __global__ __launch_bounds__(256) void pre_finish_up_kernel(const float* __restr
   }
 }
 
-bool gemm_mfma_ok(int dtype, int K, int lda, const GemmSegments& segs) {
-  if (dtype != MLRA_BF16 || K % 16 != 0 || lda % 8 != 0) return false;
+bool gemm_mfma_ok(int dtype, int M, int K, int lda, const GemmSegments& segs) {
+  if (dtype != MLRA_BF16 || K % kRowsChunk != 0 || lda % 8 != 0) return false;
+  const long long lim = 1ll << 30;   // elements: byte offsets stay below 2^31
+  if ((long long)M * lda >= lim) return false;
   for (int i = 0; i < segs.count; ++i)
-    if (segs.cols[i] % 8 != 0) return false;
+    if (segs.cols[i] % 8 != 0 || (long long)K * segs.cols[i] >= lim) return false;
   return true;
 }
 
 int launch_gemm(int dtype, const void* A, int lda, int M, const GemmSegments& segs, int K, int n_slices,
                 int rows_per_slice, float* part, int ld_out, hipStream_t stream) {
-  if (gemm_mfma_ok(dtype, K, lda, segs)) {
+  if (gemm_mfma_ok(dtype, M, K, lda, segs)) {
     static bool configured = false;
-    const int max_lds = kRowsChunk * 256 + 32 * kMaxMTiles * kAPitch;
     if (!configured) {
       if (hipFuncSetAttribute((const void*)skinny_gemm_mfma_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                              max_lds) != hipSuccess ||
+                              gemm_stages(1) * gemm_stage_bytes(1)) != hipSuccess ||
           hipFuncSetAttribute((const void*)skinny_gemm_mfma_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                              max_lds) != hipSuccess ||
+                              gemm_stages(2) * gemm_stage_bytes(2)) != hipSuccess ||
           hipFuncSetAttribute((const void*)skinny_gemm_mfma_kernel<3>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                              max_lds) != hipSuccess ||
+                              gemm_stages(3) * gemm_stage_bytes(3)) != hipSuccess ||
           hipFuncSetAttribute((const void*)skinny_gemm_mfma_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                              max_lds) != hipSuccess)
+                              gemm_stages(4) * gemm_stage_bytes(4)) != hipSuccess)
         return MLRA_ERR_LAUNCH;
       configured = true;
     }
@@ -334,7 +348,7 @@ int launch_gemm(int dtype, const void* A, int lda, int M, const GemmSegments& se
     for (int i = 0; i < segs.count; ++i) tiles += (segs.cols[i] + kColsWG - 1) / kColsWG;
     const int mt = M >= 32 * kMaxMTiles ? kMaxMTiles : (M + 31) / 32;
     dim3 grid(tiles, n_slices, (M + 32 * mt - 1) / (32 * mt));
-    const size_t lds = (size_t)kRowsChunk * 256 + (size_t)32 * mt * kAPitch;
+    const size_t lds = (size_t)gemm_stages(mt) * gemm_stage_bytes(mt);
     const bf16_t* a = (const bf16_t*)A;
     if (mt == 1) skinny_gemm_mfma_kernel<1><<<grid, 256, lds, stream>>>(a, lda, M, segs, K, rows_per_slice, part, ld_out);
     else if (mt == 2) skinny_gemm_mfma_kernel<2><<<grid, 256, lds, stream>>>(a, lda, M, segs, K, rows_per_slice, part, ld_out);
@@ -354,7 +368,7 @@ int launch_gemm(int dtype, const void* A, int lda, int M, const GemmSegments& se
 
 }  // namespace
 
-// K slices of a skinny GEMM: enough workgroups to cover the chip, whole 256-row chunks per slice.
+// K slices of a skinny GEMM: enough workgroups to cover the chip, whole chunks of kRowsChunk rows per slice.
 PrePlan pre_plan(int dtype, int batch, int d, int d_cq, int d_c, int d_r, int h, int d_h) {
   PrePlan p;
   p.n1 = d_cq + d_c + d_r;
@@ -371,8 +385,8 @@ PrePlan pre_plan(int dtype, int batch, int d, int d_cq, int d_c, int d_r, int h,
   GemmSegments s1, s2;
   s1.count = 3; s1.cols[0] = d_cq; s1.cols[1] = d_c; s1.cols[2] = d_r;
   s2.count = 2; s2.cols[0] = h * d_h; s2.cols[1] = h * d_r; s2.cols[2] = 0;
-  p.mfma1 = gemm_mfma_ok(dtype, d, d, s1);
-  p.mfma2 = gemm_mfma_ok(dtype, d_cq, d_cq, s2);
+  p.mfma1 = gemm_mfma_ok(dtype, batch, d, d, s1);
+  p.mfma2 = gemm_mfma_ok(dtype, batch, d_cq, d_cq, s2);
   p.slices1 = p.slices2 = 1;
   p.rows1 = d;
   p.rows2 = d_cq;
