@@ -78,13 +78,21 @@ def test_pre_attention_fp32_odd_dims():
     _run_and_check(wl, d=50, d_cq=28, lens=np.array([300, 17, 129], dtype=np.int32))
 
 
-@pytest.mark.parametrize("batch", [1, 37, 64, 130])
+@pytest.mark.parametrize("batch", [1, 37, 64, 96, 130])
 def test_pre_attention_bf16_mfma_path(batch):
-    # K slices, a narrow last segment (d_r = 64 < one column tile), ragged batch tiles, far positions
-    wl = gen.WORKLOADS["C3"].scaled(name="pre-bf16", batch=batch, h=16, n_min=1, n_max=4000)
+    # K slices, a narrow last segment (d_r = 64 < one column tile) and a ragged one (17 heads x 64 RoPE
+    # channels), ragged batch tiles (1..4 accumulator tiles, two batch tiles at 130), far positions
+    wl = gen.WORKLOADS["C3"].scaled(name="pre-bf16", batch=batch, h=17, n_min=1, n_max=4000)
     rng = np.random.default_rng(5 + batch)
     lens = rng.integers(1, 4001, size=batch).astype(np.int32)
     lens[0] = 4000
+    _run_and_check(wl, d=1024, d_cq=384, lens=lens)
+
+
+def test_pre_attention_bf16_row_counts_off_the_chunk():
+    # projection depths that are not multiples of the MFMA kernel's 128-row chunks: the plain kernel runs
+    wl = gen.WORKLOADS["C3"].scaled(name="pre-bf16-odd", batch=9, h=16, n_min=1, n_max=4000)
+    lens = np.array([4000, 1, 2, 63, 64, 65, 1000, 3999, 77], dtype=np.int32)
     _run_and_check(wl, d=1024 + 16, d_cq=384 + 8, lens=lens)
 
 
