@@ -771,14 +771,15 @@ bool decode_gla_supported(const DecodeArgs& a) {
 }
 
 int launch_decode_gla(const DecodeArgs& a) {
-  static bool configured = false;
+  static PerDeviceSetup setup;
+  int setup_dev = -1;
   constexpr int kStagesGla = 3;
   const int lds = kStagesGla * (2 * kLatBytes + kRopeBytes) + 4 * 8 * 64 * 16;   // stages + score exchange
-  if (!configured) {
+  if (setup.needed(&setup_dev)) {
     if (hipFuncSetAttribute((const void*)decode_mfma_kernel<kStagesGla, 2>,
                             hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
       return MLRA_ERR_LAUNCH;
-    configured = true;
+    setup.done(setup_dev);
   }
   MfmaParams p;
   p.latent = (const bf16_t*)a.latent;
@@ -809,17 +810,18 @@ int launch_decode_gla(const DecodeArgs& a) {
 }
 
 int launch_decode_mfma(const DecodeArgs& a) {
-  static bool configured = false;
+  static PerDeviceSetup setup;
+  int setup_dev = -1;
   const bool paired = decode_mfma_paired(a.h, a.n_blocks);
   const int lds = paired ? kStagesPaired * (2 * kLatBytes + kRopeBytes) : kStages * kStageBytes;
-  if (!configured) {
+  if (setup.needed(&setup_dev)) {
     if (hipFuncSetAttribute((const void*)decode_mfma_kernel<kStages, 0>,
                             hipFuncAttributeMaxDynamicSharedMemorySize, kStages * kStageBytes) != hipSuccess ||
         hipFuncSetAttribute((const void*)decode_mfma_kernel<kStagesPaired, 1>,
                             hipFuncAttributeMaxDynamicSharedMemorySize,
                             kStagesPaired * (2 * kLatBytes + kRopeBytes)) != hipSuccess)
       return MLRA_ERR_LAUNCH;
-    configured = true;
+    setup.done(setup_dev);
   }
   MfmaParams p;
   p.latent = (const bf16_t*)a.latent;

@@ -271,12 +271,13 @@ bool gqa_mfma_supported(const GqaArgs& a) {
 }
 
 int launch_gqa_mfma(const GqaArgs& a) {
-  static bool configured = false;
-  if (!configured) {
+  static PerDeviceSetup setup;
+  int setup_dev = -1;
+  if (setup.needed(&setup_dev)) {
     if (hipFuncSetAttribute((const void*)gqa_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kGLds) !=
         hipSuccess)
       return MLRA_ERR_LAUNCH;
-    configured = true;
+    setup.done(setup_dev);
   }
   GqaMfmaParams p;
   p.k_pool = (const bf16_t*)a.k_pool;

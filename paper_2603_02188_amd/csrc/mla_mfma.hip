@@ -295,12 +295,13 @@ bool mla_mfma_supported(const DecodeArgs& a) {
 }
 
 int launch_mla_mfma(const DecodeArgs& a) {
-  static bool configured = false;
-  if (!configured) {
+  static PerDeviceSetup setup;
+  int setup_dev = -1;
+  if (setup.needed(&setup_dev)) {
     if (hipFuncSetAttribute((const void*)mla_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kMLds) !=
         hipSuccess)
       return MLRA_ERR_LAUNCH;
-    configured = true;
+    setup.done(setup_dev);
   }
   MfmaParams p;
   p.latent = (const bf16_t*)a.latent;

@@ -16,13 +16,15 @@ static void timing_mark(int which, hipStream_t stream) {
 }
 
 int device_cu_count() {
-  static int cached = 0;
-  if (cached > 0) return cached;
+  static std::atomic<int> cached[64];   // per device, 0 = not asked yet
   int dev = 0, cus = 0;
-  if (hipGetDevice(&dev) == hipSuccess &&
-      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0) {
-    cached = cus;
-    return cached;
+  if (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < 64) {
+    const int have = cached[dev].load(std::memory_order_relaxed);
+    if (have > 0) return have;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0) {
+      cached[dev].store(cus, std::memory_order_relaxed);
+      return cus;
+    }
   }
   (void)hipGetLastError();
   return 256;  // MI355X; used only when no device can be queried (e.g. sizing on a CPU-only host)

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "mlra.h"
 
 namespace mlra {
@@ -36,6 +38,22 @@ struct SplitPlan {
 };
 
 int device_cu_count();
+
+// Kernel attributes (the dynamic LDS limit) belong to a device: a launcher sets them the first time it
+// runs on each device.  needed() says whether the current device still lacks them, done() records that
+// they are set.  Two threads racing through a first call both set the attributes, which is harmless.
+class PerDeviceSetup {
+ public:
+  bool needed(int* dev) const {
+    if (hipGetDevice(dev) != hipSuccess || *dev < 0 || *dev >= 64) { *dev = -1; return true; }
+    return ((seen_.load(std::memory_order_acquire) >> *dev) & 1ull) == 0;
+  }
+  void done(int dev) {
+    if (dev >= 0) seen_.fetch_or(1ull << dev, std::memory_order_release);
+  }
+ private:
+  std::atomic<unsigned long long> seen_{0};
+};
 SplitPlan plan_splits(int batch, int n_blocks, int max_seq_len);
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }

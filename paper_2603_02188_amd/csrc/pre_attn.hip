@@ -331,8 +331,9 @@ bool gemm_mfma_ok(int dtype, int M, int K, int lda, const GemmSegments& segs) {
 int launch_gemm(int dtype, const void* A, int lda, int M, const GemmSegments& segs, int K, int n_slices,
                 int rows_per_slice, float* part, int ld_out, hipStream_t stream) {
   if (gemm_mfma_ok(dtype, M, K, lda, segs)) {
-    static bool configured = false;
-    if (!configured) {
+    static PerDeviceSetup setup;
+    int setup_dev = -1;
+    if (setup.needed(&setup_dev)) {
       if (hipFuncSetAttribute((const void*)skinny_gemm_mfma_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize,
                               gemm_stages(1) * gemm_stage_bytes(1)) != hipSuccess ||
           hipFuncSetAttribute((const void*)skinny_gemm_mfma_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -342,7 +343,7 @@ int launch_gemm(int dtype, const void* A, int lda, int M, const GemmSegments& se
           hipFuncSetAttribute((const void*)skinny_gemm_mfma_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize,
                               gemm_stages(4) * gemm_stage_bytes(4)) != hipSuccess)
         return MLRA_ERR_LAUNCH;
-      configured = true;
+      setup.done(setup_dev);
     }
     int tiles = 0;
     for (int i = 0; i < segs.count; ++i) tiles += (segs.cols[i] + kColsWG - 1) / kColsWG;

@@ -312,14 +312,15 @@ int launch_merge_upproj_mfma(const DecodeArgs& a) {
   const int bpg = a.n_blocks / a.groups, R = bpg * a.d_cb;
   const size_t lds = (size_t)kWRowsLds * 256 + (size_t)32 * (R + 8) * 2 +
                      (size_t)64 * bpg * a.plan.n_splits * sizeof(float) + 32 * sizeof(int);
-  static bool configured = false;
-  if (!configured) {
+  static PerDeviceSetup setup;
+  int setup_dev = -1;
+  if (setup.needed(&setup_dev)) {
     if (hipFuncSetAttribute((const void*)merge_upproj_mfma_kernel<bf16_t>, hipFuncAttributeMaxDynamicSharedMemorySize,
                             160 * 1024) != hipSuccess ||
         hipFuncSetAttribute((const void*)merge_upproj_mfma_kernel<float>, hipFuncAttributeMaxDynamicSharedMemorySize,
                             160 * 1024) != hipSuccess)
       return MLRA_ERR_LAUNCH;
-    configured = true;
+    setup.done(setup_dev);
   }
   dim3 grid(a.h, (a.batch + 31) / 32, a.groups);
   if (a.out_dtype == MLRA_BF16)
