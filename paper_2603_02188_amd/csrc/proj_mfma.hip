@@ -41,39 +41,69 @@ __device__ __forceinline__ short4v lds_tr16(const void* p) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// absorb_q.  One workgroup per (head, block); wave w produces channel tiles ct = w, w+4, ... of 32
-// channels.  S^T-free formulation: out[seq][c] = sum_p q[seq][p] W[c][p], so the A operand (rows =
-// sequences) and the B operand (columns = channels) are both contiguous 16-byte global loads.
+// absorb_q.  One workgroup per (head, block); wave w produces the 32-channel tile ct0 + w of each pass
+// over four tiles.  S^T-free formulation: out[seq][c] = sum_p q[seq][p] W[c][p], so the A operand (rows =
+// sequences) and the B operand (columns = channels) are both contiguous 16-byte global loads.  Sixty-four
+// sequences go through at a time: all of their query loads are issued before the first MFMA (one
+// round trip instead of one per k-step), and the results pass through LDS so that they leave as whole
+// 16-byte pieces of the q_abs rows instead of single elements.
 // ------------------------------------------------------------------------------------------------
+constexpr int kAbsPitch = 128 * 2 + 16;   // bytes per staged sequence row (128 channels; +16: rows on different banks)
+
 __global__ __launch_bounds__(256) void absorb_q_mfma_kernel(const bf16_t* __restrict__ q_nope,
                                                             const bf16_t* __restrict__ w_uk,
                                                             bf16_t* __restrict__ q_abs, int batch, int h,
                                                             int n_blocks, int groups, int d_cb) {
   // h: heads per block; q_nope holds groups * h heads and block b reads those of its group (Eq. (6))
+  __shared__ __attribute__((aligned(16))) unsigned char stage[64 * kAbsPitch];
   const int head = blockIdx.x, b = blockIdx.y;
   const int q_head = (b / (n_blocks / groups)) * h + head, q_heads = h * groups;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, g = lane >> 5, c32 = lane & 31;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, c32 = lane & 31;
   const size_t ldw = (size_t)h * kDh;
-  for (int ct = wave; ct * 32 < d_cb; ct += 4) {
-    const int c = ct * 32 + c32;
+  for (int ct0 = 0; ct0 * 32 < d_cb; ct0 += 4) {
+    const int ct = ct0 + wave;
+    const bool live = ct * 32 < d_cb;                       // (uniform per wave)
+    const int c = min(ct * 32 + c32, d_cb - 1);
     const bf16_t* wrow = w_uk + ((size_t)b * d_cb + c) * ldw + (size_t)head * kDh + g * 8;
     bf16x8 breg[8];
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) breg[ks] = *(const bf16x8*)(wrow + ks * 16);
-    for (int m0 = 0; m0 < batch; m0 += 32) {
-      const int seq = min(m0 + c32, batch - 1);
-      const bf16_t* qrow = q_nope + ((size_t)seq * q_heads + q_head) * kDh + g * 8;
-      f32x16 acc = opaque_zero();
+    const int pass_ch = min(128, d_cb - ct0 * 32);          // channels this pass produces
+    for (int m0 = 0; m0 < batch; m0 += 64) {
+      bf16x8 areg[2][8];
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
-        const bf16x8 a = *(const bf16x8*)(qrow + ks * 16);
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, breg[ks], acc, 0, 0, 0);
-      }
+      for (int t = 0; t < 2; ++t) {
+        const int seq = min(m0 + 32 * t + c32, batch - 1);
+        const bf16_t* qrow = q_nope + ((size_t)seq * q_heads + q_head) * kDh + g * 8;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int s = m0 + (r >> 2) * 8 + g * 4 + (r & 3);
-        if (s < batch) q_abs[(((size_t)s * n_blocks + b) * h + head) * d_cb + c] = f32_to_bf16(acc[r]);
+        for (int ks = 0; ks < 8; ++ks) areg[t][ks] = *(const bf16x8*)(qrow + ks * 16);
       }
+      __builtin_amdgcn_sched_barrier(0);   // every load above is in flight before the first MFMA waits
+      f32x16 acc[2] = {opaque_zero(), opaque_zero()};
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {   // (a wave past the last channel tile repeats it and stores nothing)
+        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(areg[0][ks], breg[ks], acc[0], 0, 0, 0);
+        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(areg[1][ks], breg[ks], acc[1], 0, 0, 0);
+      }
+      if (live) {
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int row = 32 * t + (r >> 2) * 8 + g * 4 + (r & 3);
+            *(bf16_t*)(stage + row * kAbsPitch + (wave * 32 + c32) * 2) = f32_to_bf16(acc[t][r]);
+          }
+      }
+      __syncthreads();
+      // 64 rows x (pass_ch / 8) 16-byte pieces, one piece per thread and step
+      const int pieces = pass_ch >> 3;
+      for (int id = tid; id < 64 * pieces; id += 256) {
+        const int row = id / pieces, pc = id - row * pieces, s_ = m0 + row;
+        if (s_ < batch)
+          *(bf16x8*)(q_abs + (((size_t)s_ * n_blocks + b) * h + head) * d_cb + ct0 * 32 + pc * 8) =
+              *(const bf16x8*)(stage + row * kAbsPitch + pc * 16);
+      }
+      __syncthreads();
     }
   }
 }
