@@ -203,7 +203,10 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
   // any length)
   typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
   const const_i32_ptr pt_row = (const_i32_ptr)(p.page_table + (size_t)seq * p.max_pages);
-  int issue_page_idx = t0 / p.page_size;
+  // (pages hold a multiple of 16 tokens and chunks start on multiples of 64, so the 16 rows that a wave
+  // loads of each tile lie in one page: the page ids below are this wave's; with pages of 16 or 32 tokens
+  // the four waves of a tile read different pages)
+  int issue_page_idx = (t0 + 16 * (int)wave_u) / p.page_size;
   int issue_page = pt_row[min(issue_page_idx, p.max_pages - 1)];
   const int n = ((const_i32_ptr)p.seq_lens)[seq];
   if (t0 >= n) {
@@ -237,7 +240,8 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
   const size_t lat_plane_bytes = (size_t)p.page_size * kLatRow;        // one block's rows inside a page
   const size_t lat_half_step = GLA ? kDcb * 2 : lat_plane_bytes;       // from the first latent tile's source to the second's
   const char* lat_blk = (const char*)p.latent + (size_t)blk0 * lat_plane_bytes;
-  int issue_slot = t0 % p.page_size;   // slot of the next tile to issue inside its page (tiles go in order)
+  // slot, inside its page, of this wave's first row of the next tile to issue (tiles go in order)
+  int issue_slot = (t0 + 16 * (int)wave_u) % p.page_size;
   int issue_stage = 0;
 
   // A tile is issued in parts so that the parts can sit behind different MFMAs: issue_begin (scalar
@@ -249,7 +253,7 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
   auto issue_begin = [&](int jj) {
     const unsigned page = (unsigned)issue_page;
     iss_last = min(kTile, t1 - t0 - jj * kTile) - 1;
-    // start of this tile's latent rows (block plane blk) and RoPE rows inside the page
+    // start of this wave's 16 latent rows (block plane blk0) and RoPE rows of the tile inside the page
     iss_lat = lat_blk + page * lat_page_bytes + (unsigned)issue_slot * (unsigned)kLatRow;
     iss_rope = (const char*)p.rope + page * rope_page_bytes + (unsigned)issue_slot * (unsigned)(kDr * 2);
     iss_stage = lds_base + issue_stage * kStageB;
@@ -258,7 +262,7 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
   auto issue_full_part = [&](int part) {
     if (part < 4 * kBlocksWG) {
       const int jb = part >> 2, q = part & 3;
-      const char* src = iss_lat + jb * lat_half_step + wave_u * (16 * kLatRow);
+      const char* src = iss_lat + jb * lat_half_step;
       if (q == 0) set_m0(iss_stage + jb * kLatBytes + wave_u * 4096);
       if (q == 0) lds_dma16<0>(src, lat_voff[0]);
       if (q == 1) lds_dma16<1024>(src, lat_voff[1]);
@@ -267,35 +271,50 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
     } else {
       const int q = part - 4 * kBlocksWG;
       if (q == 0) set_m0(iss_stage + kRopeOff + wave_u * 2048);
-      if (q == 0) lds_dma16<0>(iss_rope + wave_u * 2048, rope_voff[0]);
-      if (q == 1) lds_dma16<1024>(iss_rope + wave_u * 2048, rope_voff[1]);
+      if (q == 0) lds_dma16<0>(iss_rope, rope_voff[0]);
+      if (q == 1) lds_dma16<1024>(iss_rope, rope_voff[1]);
     }
   };
-  // ragged end of the chunk: rows past it re-read its last row (finite values, weight 0 later).
-  // Offsets are taken from the tile start so that they never go negative.
+  // ragged end of the chunk: rows past it re-read its last row (finite values, weight 0 later).  The
+  // rows of this wave that exist lie in its own page; if none exists, every lane reads the tile's last
+  // valid row, whose page may be another one (pages shorter than a tile).
   auto issue_ragged = [&]() {
+    const int w0 = 16 * (int)wave_u;                 // first tile row of this wave
+    int first = w0;                                  // the tile row that src_lat / src_rope point at
+    const char* src_lat = iss_lat;
+    const char* src_rope = iss_rope;
+    if (w0 > iss_last) {
+      first = iss_last;
+      const int tok = issue_page_idx * p.page_size + issue_slot - w0 + iss_last;   // the last valid token
+      const int idx = tok / p.page_size, slot = tok - idx * p.page_size;
+      const unsigned page = (unsigned)pt_row[idx];
+      src_lat = lat_blk + page * lat_page_bytes + (unsigned)slot * (unsigned)kLatRow;
+      src_rope = (const char*)p.rope + page * rope_page_bytes + (unsigned)slot * (unsigned)(kDr * 2);
+    }
 #pragma unroll
     for (int jb = 0; jb < kBlocksWG; ++jb)
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const int t = (wave * 4 + q) * 4 + (lane >> 4);          // 0..63
-        const unsigned row = (unsigned)min(t, iss_last);           // 0..last
+        const unsigned row = (unsigned)(min(t, iss_last) - first);   // rows from src_lat, never negative
         set_m0(iss_stage + jb * kLatBytes + wave_u * 4096 + q * 1024);
-        lds_dma16<0>(iss_lat + jb * lat_half_step, row * kLatRow + (((lane & 15) ^ lat_swz(t)) << 4));
+        lds_dma16<0>(src_lat + jb * lat_half_step, row * kLatRow + (((lane & 15) ^ lat_swz(t)) << 4));
       }
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
       const int t = (wave * 2 + q) * 8 + (lane >> 3);          // 0..63
-      const unsigned row = (unsigned)min(t, iss_last);
+      const unsigned row = (unsigned)(min(t, iss_last) - first);
       set_m0(iss_stage + kRopeOff + wave_u * 2048 + q * 1024);
-      lds_dma16<0>(iss_rope, row * (kDr * 2) + (((lane & 7) ^ rope_swz(t)) << 4));
+      lds_dma16<0>(src_rope, row * (kDr * 2) + (((lane & 7) ^ rope_swz(t)) << 4));
     }
   };
   auto issue_end = [&]() {
     issue_slot += kTile;
     if (issue_slot >= p.page_size) {
-      issue_slot = 0;
-      ++issue_page_idx;
+      do {                       // (up to four pages further with 16-token pages)
+        issue_slot -= p.page_size;
+        ++issue_page_idx;
+      } while (issue_slot >= p.page_size);
       issue_page = pt_row[min(issue_page_idx, p.max_pages - 1)];
     }
     issue_stage = (issue_stage + 1 == STAGES) ? 0 : issue_stage + 1;
@@ -750,9 +769,12 @@ int launch_seq_order(const DecodeArgs& a) {
   return check_launch();
 }
 
+// Pages of 16 or 32 tokens (a wave's 16 rows of a tile never straddle a page), or whole tiles.
+static bool page_size_ok(int page_size) { return page_size == 16 || page_size == 32 || page_size % kTile == 0; }
+
 bool decode_mfma_supported(const DecodeArgs& a) {
   // (the query rows are addressed with 32-bit byte offsets from q_abs / q_rope)
-  return a.dtype == MLRA_BF16 && a.d_cb == kDcb && a.d_r == kDr && a.page_size % kTile == 0 &&
+  return a.dtype == MLRA_BF16 && a.d_cb == kDcb && a.d_r == kDr && page_size_ok(a.page_size) &&
          a.plan.chunk_tokens % kTile == 0 &&
          (long long)a.batch * a.n_blocks * a.h * (kDcb * 2) < (1LL << 32) &&
          (long long)a.batch * a.h * a.groups * (kDr * 2) < (1LL << 32);
@@ -764,7 +786,7 @@ bool decode_mfma_paired(int h, int n_blocks) { return n_blocks % 2 == 0 && (h - 
 
 // GLA-2 shape: latent heads of 256 channels (Section 2.3); 64 heads per workgroup.
 bool decode_gla_supported(const DecodeArgs& a) {
-  return a.dtype == MLRA_BF16 && a.d_cb == 2 * kDcb && a.d_r == kDr && a.page_size % kTile == 0 &&
+  return a.dtype == MLRA_BF16 && a.d_cb == 2 * kDcb && a.d_r == kDr && page_size_ok(a.page_size) &&
          a.plan.chunk_tokens % kTile == 0 &&
          (long long)a.batch * a.n_blocks * a.h * (4 * kDcb) < (1LL << 32) &&
          (long long)a.batch * a.h * a.groups * (kDr * 2) < (1LL << 32);

@@ -161,7 +161,9 @@ def draw_seq_lens(wl: Workload) -> np.ndarray:
 
 
 def draw_page_table(wl: Workload, seq_lens: np.ndarray):
-    """Returns (page_table [B][max_pages], num_pages).  Unused entries are 0."""
+    """Returns (page_table [B][max_pages], num_pages).  Unused entries name a spare page that no sequence
+    owns (poisoned in parity tests, so a read through an unmapped entry shows up), or page 0 if the pool
+    has no spare page."""
     pages = (seq_lens.astype(np.int64) + wl.page_size - 1) // wl.page_size
     used = int(pages.sum())
     num_pages = max(1, int(np.ceil(used * (1.0 + wl.spare_frac))))
@@ -171,7 +173,7 @@ def draw_page_table(wl: Workload, seq_lens: np.ndarray):
     else:
         order = np.arange(num_pages, dtype=np.int32)
     max_pages = max(1, int(pages.max()) if len(pages) else 1)
-    table = np.zeros((wl.batch, max_pages), dtype=np.int32)
+    table = np.full((wl.batch, max_pages), order[used] if num_pages > used else 0, dtype=np.int32)
     at = 0
     for b in range(wl.batch):
         k = int(pages[b])

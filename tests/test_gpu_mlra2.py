@@ -131,6 +131,18 @@ def test_gla2_bf16_fast_path_ragged(h):
     _check_gla2(wl, lens, out_dtype=torch.bfloat16)
 
 
+@pytest.mark.parametrize("page_size", [16, 32])
+def test_two_group_forms_with_pages_shorter_than_a_tile(page_size):
+    # PAIRED (MLRA-2) and GLA forms of the decode kernel on pages of 16 / 32 tokens
+    lens = np.array([1500, 65, 1, 81, 0, 17], dtype=np.int32)
+    wl = gen.WORKLOADS["M2"].scaled(batch=6, n_min=0, n_max=1500, page_size=page_size, shuffle_pages=True,
+                                    spare_frac=0.2)
+    _check(gen.make_decode_inputs(wl, poison=True, hole=True, seq_lens=lens), append=True)
+    wl = gen.WORKLOADS["G2"].scaled(batch=6, n_min=0, n_max=1500, page_size=page_size, shuffle_pages=True,
+                                    spare_frac=0.2)
+    _check_gla2(wl, lens, append=True)
+
+
 def test_gla2_bf16_split_context_and_full_size_samples():
     wl = gen.WORKLOADS["G2"].scaled(batch=2, n_min=5000, n_max=9000)
     _check_gla2(wl, np.array([9000, 5000], dtype=np.int32))

@@ -109,6 +109,21 @@ def test_bf16_large_page_size():
     _check_mlra(gen.make_decode_inputs(wl))
 
 
+@pytest.mark.parametrize("page_size", [16, 32])
+def test_bf16_pages_shorter_than_a_tile(page_size):
+    """Pages of 16 and 32 tokens: the four waves of a 64-token tile read different pages, and at a ragged
+    end the waves past it re-read the last valid row from a page that is not theirs (unmapped table
+    entries and spare page slots hold poison)."""
+    wl = gen.WORKLOADS["C3"].scaled(batch=9, n_min=1, n_max=2100, page_size=page_size, shuffle_pages=True,
+                                    spare_frac=0.3)
+    lens = np.array([1, 16, 17, 65, 81, 100, 1337, 2047, 2100], dtype=np.int32)
+    _check_mlra(gen.make_decode_inputs(wl, hole=True, seq_lens=lens), append=True)
+    # one block, few sequences: the context is split into chunks
+    wl = gen.WORKLOADS["C2"].scaled(batch=2, n_min=3000, n_max=5000, page_size=page_size, shuffle_pages=True,
+                                    spare_frac=0.2)
+    _check_mlra(gen.make_decode_inputs(wl, seq_lens=np.array([4993, 3001], dtype=np.int32)))
+
+
 def test_deterministic_bitwise():
     wl = gen.WORKLOADS["C5"].scaled(batch=3, n_min=900, n_max=2100)
     inp = gen.make_decode_inputs(wl)
