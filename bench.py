@@ -157,9 +157,9 @@ def _baselines(inp, mlra_decode_us):
             "mlra2_decode_us": two["mlra2"], "mlra2_over_mlra4": two["mlra2"] / mlra_decode_us,
             "gla2_decode_us": two["gla2"], "gla2_over_mlra4": two["gla2"] / mlra_decode_us,
             "gla2_kernel": "MFMA decode kernel, GLA form (channel halves of a latent head on two waves)",
-            "two_group_note": "MLRA-2 and GLA-2 fill the chip with one workgroup per (sequence, block pair) on this "
-                              "batch: one round, no length balancing, so the longest sequence sets their time; on a "
-                              "uniform batch (workloads M2, G2) they take about 0.7x the MLRA-4 time",
+            "two_group_note": "MLRA-2, GLA-2 and MLA give about one round of workgroups on this batch, so a planning "
+                              "kernel cuts the long sequences into chunks and hands them out longest first; on a "
+                              "uniform batch (workloads M2, G2) the two-group forms take about 0.7x the MLRA-4 time",
             "gqa_decode_us": gqa_us, "gqa_over_mlra4": gqa_us / mlra_decode_us,
             "gqa_gbps": gqa_bytes["total"] / (gqa_us * 1e-6) / 1e9,
             "gqa_kernel": "MFMA streaming kernel",

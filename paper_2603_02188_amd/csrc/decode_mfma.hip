@@ -56,35 +56,47 @@ __global__ __launch_bounds__(256) void seq_order_kernel(const int32_t* __restric
 // Chunk lengths that follow the sequence lengths.  With uniform chunks a ragged batch leaves workgroups
 // idle (a sequence half as long as the longest uses half of its chunk slots); here sequence i gets
 // S_i ~ target * n_i / sum(n) chunks of ceil(n_i / S_i) tokens (rounded up to the tile, at least
-// min_chunk), so that about `target` chunks per block are active in total and they are equally long.
+// min_chunk), so that about `target` chunks per block are active in total and they are about equally long.
 // unit_tab lists the active (sequence, chunk) pairs, packed as sequence * 1024 + chunk, and -1 after
 // them: workgroup ids go round-robin over the XCDs, so the active ones must be contiguous to spread
-// evenly (scattered, they leave some XCDs with more work than CUs and others idle).
+// evenly (scattered, they leave some XCDs with more work than CUs and others idle).  The pairs are listed
+// longest chunk first (for batches of up to 512 sequences): when they need more than one round of
+// workgroups, that is the longest-processing-time rule.  With single_if_uniform, a batch whose longest
+// sequence is within 25 % of the mean keeps one chunk per sequence (cutting it would only add partials).
 __global__ __launch_bounds__(256) void plan_chunks_kernel(const int32_t* __restrict__ seq_lens,
                                                           int32_t* __restrict__ chunk_tab,
                                                           int32_t* __restrict__ unit_tab, int batch, int target,
-                                                          int max_slots, int min_chunk) {
+                                                          int max_slots, int min_chunk, int single_if_uniform) {
   __shared__ float part[256];
+  __shared__ int part_max[256];
   __shared__ int seg_sum[256];
   __shared__ int n_active;
-  extern __shared__ int32_t tab[];             // [batch] lengths, [batch] chunk lengths
+  extern __shared__ int32_t tab[];             // [batch] lengths, [batch] chunk lengths, [batch] dispatch order
   int32_t* lens = tab;
   int32_t* chunks = tab + batch;
+  int32_t* order = tab + 2 * batch;
   float sum = 0.f;
+  int longest = 0;
   for (int i = threadIdx.x; i < batch; i += 256) {
     lens[i] = seq_lens[i];
     sum += (float)lens[i];
+    longest = max(longest, lens[i]);
   }
   part[threadIdx.x] = sum;
+  part_max[threadIdx.x] = longest;
   __syncthreads();
   for (int s = 128; s > 0; s >>= 1) {
-    if (threadIdx.x < s) part[threadIdx.x] += part[threadIdx.x + s];
+    if (threadIdx.x < s) {
+      part[threadIdx.x] += part[threadIdx.x + s];
+      part_max[threadIdx.x] = max(part_max[threadIdx.x], part_max[threadIdx.x + s]);
+    }
     __syncthreads();
   }
   const float total = part[0];
+  const bool single = single_if_uniform && (float)part_max[0] * (float)batch <= 1.25f * total;
   for (int i = threadIdx.x; i < batch; i += 256) {
     const int n = lens[i];
-    int s_i = total > 0.f ? (int)((float)target * (float)n / total + 0.5f) : 1;
+    int s_i = (total > 0.f && !single) ? (int)((float)target * (float)n / total + 0.5f) : 1;
     s_i = min(max(s_i, 1), max_slots);
     int chunk = (n + s_i - 1) / s_i;
     chunk = max(min_chunk, (chunk + kTile - 1) / kTile * kTile);
@@ -92,10 +104,27 @@ __global__ __launch_bounds__(256) void plan_chunks_kernel(const int32_t* __restr
     chunk_tab[i] = chunk;
   }
   __syncthreads();
-  // exclusive scan of the active chunk counts: 256 contiguous segments of sequences, one per thread
+  // dispatch order: rank sort by chunk length, longest first (ties keep index order)
+  for (int i = threadIdx.x; i < batch; i += 256) {
+    int rank = i;
+    if (batch <= 512) {
+      const int c = chunks[i];
+      rank = 0;
+      for (int j = 0; j < batch; ++j) {
+        const int cj = chunks[j];
+        rank += (cj > c || (cj == c && j < i)) ? 1 : 0;
+      }
+    }
+    order[rank] = i;
+  }
+  __syncthreads();
+  // exclusive scan of the active chunk counts in dispatch order: 256 contiguous segments, one per thread
   const int per = (batch + 255) / 256, lo = min(batch, (int)threadIdx.x * per), hi = min(batch, lo + per);
   int mine = 0;
-  for (int i = lo; i < hi; ++i) mine += (lens[i] + chunks[i] - 1) / chunks[i];
+  for (int r = lo; r < hi; ++r) {
+    const int i = order[r];
+    mine += (lens[i] + chunks[i] - 1) / chunks[i];
+  }
   seg_sum[threadIdx.x] = mine;
   __syncthreads();
   if (threadIdx.x == 0) {
@@ -105,7 +134,8 @@ __global__ __launch_bounds__(256) void plan_chunks_kernel(const int32_t* __restr
   }
   __syncthreads();
   int u = seg_sum[threadIdx.x];
-  for (int i = lo; i < hi; ++i) {
+  for (int r = lo; r < hi; ++r) {
+    const int i = order[r];
     const int active = (lens[i] + chunks[i] - 1) / chunks[i];
     for (int k = 0; k < active; ++k) unit_tab[u++] = i * 1024 + k;
   }
@@ -755,8 +785,9 @@ constexpr int kStagesPaired = 4;   // PAIRED form: 4 x 40 KiB = all 160 KiB of L
 int launch_plan_chunks(const DecodeArgs& a) {
   if (!a.chunk_tab || !a.unit_tab || a.plan.target_chunks <= 0) return MLRA_ERR_SHAPE;
   if (a.plan.n_splits > 1023 || a.batch > 2048) return MLRA_ERR_SHAPE;
-  plan_chunks_kernel<<<1, 256, 2 * a.batch * sizeof(int32_t), a.stream>>>(a.seq_lens, a.chunk_tab, a.unit_tab, a.batch, a.plan.target_chunks,
-                                              a.plan.n_splits, 128);
+  plan_chunks_kernel<<<1, 256, 3 * a.batch * sizeof(int32_t), a.stream>>>(
+      a.seq_lens, a.chunk_tab, a.unit_tab, a.batch, a.plan.target_chunks, a.plan.n_splits, 128,
+      a.plan.single_if_uniform ? 1 : 0);
   return check_launch();
 }
 
@@ -821,12 +852,12 @@ int launch_decode_gla(const DecodeArgs& a) {
   p.chunk = a.plan.chunk_tokens;
   p.batch = a.batch;
   p.scale_log2 = a.softmax_scale * 1.4426950408889634f;
-  p.chunk_tab = nullptr;
-  p.unit_tab = nullptr;
+  p.chunk_tab = a.balanced ? a.chunk_tab : nullptr;
+  p.unit_tab = a.balanced ? a.unit_tab : nullptr;
   p.seq_order = nullptr;
   const long long n_wg = (long long)a.plan.n_splits * a.n_blocks * ((a.h + 63) / 64) * a.batch;
   if (n_wg <= 0 || n_wg > 0x7fffffffLL) return MLRA_ERR_SHAPE;
-  if (n_wg > device_cu_count() && launch_seq_order(a) == MLRA_OK) p.seq_order = a.seq_order;
+  if (!a.balanced && n_wg > device_cu_count() && launch_seq_order(a) == MLRA_OK) p.seq_order = a.seq_order;
   decode_mfma_kernel<kStagesGla, 2><<<dim3((unsigned)n_wg), 256, lds, a.stream>>>(p);
   return check_launch();
 }

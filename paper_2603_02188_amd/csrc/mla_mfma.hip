@@ -56,13 +56,23 @@ __global__ __launch_bounds__(256) void mla_mfma_kernel(MfmaParams p) {
     su = full_units + wg / n_hg;
     hgrp = wg % n_hg;
   }
-  const int split = su % p.n_splits;
-  const int seq = p.seq_order ? p.seq_order[su / p.n_splits] : su / p.n_splits;
+  int split, seq, chunk_len;
+  if (p.unit_tab) {            // chunk lengths follow the sequence lengths: active units listed first
+    const int code = p.unit_tab[su];
+    if (code < 0) return;
+    seq = code >> 10;
+    split = code & 1023;
+    chunk_len = p.chunk_tab[seq];
+  } else {
+    split = su % p.n_splits;
+    seq = p.seq_order ? p.seq_order[su / p.n_splits] : su / p.n_splits;
+    chunk_len = p.chunk;
+  }
   typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
   const int n = ((const_i32_ptr)p.seq_lens)[seq];
-  const int t0 = split * p.chunk;
+  const int t0 = split * chunk_len;
   if (t0 >= n) return;
-  const int t1 = min(n, t0 + p.chunk);
+  const int t1 = min(n, t0 + chunk_len);
   const int ntiles = (t1 - t0 + kMTok - 1) / kMTok;
   const int nvalid_last = t1 - t0 - (ntiles - 1) * kMTok;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -309,8 +319,8 @@ int launch_mla_mfma(const DecodeArgs& a) {
   p.page_table = a.page_table;
   p.seq_lens = a.seq_lens;
   p.seq_order = nullptr;   // set below when the launch needs more than one round of workgroups
-  p.chunk_tab = nullptr;
-  p.unit_tab = nullptr;
+  p.chunk_tab = a.balanced ? a.chunk_tab : nullptr;
+  p.unit_tab = a.balanced ? a.unit_tab : nullptr;
   p.q_abs = (const bf16_t*)a.q_abs;
   p.q_rope = (const bf16_t*)a.q_rope;
   p.part_z = a.part_z;
@@ -327,7 +337,7 @@ int launch_mla_mfma(const DecodeArgs& a) {
   const int n_hg = (a.h + kMHeads - 1) / kMHeads;
   const long long n_wg = (long long)a.plan.n_splits * n_hg * a.batch;
   if (n_wg <= 0 || n_wg > 0x7fffffffLL) return MLRA_ERR_SHAPE;
-  if (n_wg > device_cu_count() && launch_seq_order(a) == MLRA_OK) p.seq_order = a.seq_order;
+  if (!a.balanced && n_wg > device_cu_count() && launch_seq_order(a) == MLRA_OK) p.seq_order = a.seq_order;
   mla_mfma_kernel<<<dim3((unsigned)n_wg), 256, kMLds, a.stream>>>(p);
   return check_launch();
 }

@@ -5,6 +5,8 @@
 
 #include "mlra_internal.h"
 
+#include <algorithm>
+
 namespace mlra {
 
 // Optional per-kernel timing of the decode entry points (see mlra_kernel_timing_begin).
@@ -48,6 +50,20 @@ static SplitPlan plan_decode(int batch, int h, int n_blocks, int d_cb, int max_s
   if (d_cb == 128 && p.n_splits > 1 && p.chunk_tokens >= 8192 && 2 * p.n_splits * n_blocks <= 128) {
     p.target_chunks = p.n_splits * batch;
     p.n_splits *= 2;
+  }
+  // The forms that run one workgroup per two blocks or per 64 heads (MLRA-2 / GLA-2 at 128 heads, the MLA
+  // baseline): when the batch alone gives about one round of workgroups, a ragged batch would leave the
+  // CUs of its short sequences idle while the longest finishes.  Four chunk slots per sequence and a
+  // target of two rounds let the planning kernel cut the long sequences and hand the chunks out longest
+  // first; a batch of nearly equal lengths is left uncut.
+  const bool mla = n_blocks == 1 && d_cb == 512;
+  const bool two_per_wg = (d_cb == 128 && decode_mfma_paired(h, n_blocks)) || d_cb == 256;
+  const long wgs = (long)batch * groups;
+  if ((mla || two_per_wg) && p.n_splits == 1 && p.target_chunks == 0 && 2 * wgs > device_cu_count() &&
+      wgs < 2 * device_cu_count() && max_seq_len >= 2048 && batch <= 512) {
+    p.target_chunks = (int)std::max<long>(batch, 2L * device_cu_count() / groups);
+    p.n_splits = 4;
+    p.single_if_uniform = true;
   }
   return p;
 }
@@ -133,7 +149,8 @@ static int decode_common(const mlra_cache* c, int batch, int h, int groups, int 
   a.stream = (hipStream_t)stream;
   timing_mark(0, a.stream);
   // chunk lengths that follow the sequence lengths need both MFMA kernels (they read the table)
-  if (a.plan.target_chunks > 0 && decode_mfma_supported(a) && merge_upproj_mfma_supported(a))
+  if (a.plan.target_chunks > 0 && merge_upproj_mfma_supported(a) &&
+      (decode_mfma_supported(a) || decode_gla_supported(a) || mla_mfma_supported(a)))
     a.balanced = launch_plan_chunks(a) == MLRA_OK;
   int st = decode_mfma_supported(a) ? launch_decode_mfma(a)
            : decode_gla_supported(a) ? launch_decode_gla(a)

@@ -35,6 +35,7 @@ struct SplitPlan {
   int chunk_tokens;   // uniform chunk length
   int target_chunks;  // > 0: chunk lengths may follow the sequence lengths so that about this many chunks
                       // per block are active in total (see launch_plan_chunks); 0: uniform chunks only
+  bool single_if_uniform = false;   // with target_chunks: a batch of nearly equal lengths is not cut at all
 };
 
 int device_cu_count();

@@ -143,6 +143,22 @@ def test_two_group_forms_with_pages_shorter_than_a_tile(page_size):
     _check_gla2(wl, lens, append=True)
 
 
+@pytest.mark.parametrize("uniform", [False, True])
+def test_two_group_forms_one_round_batches_are_cut_by_length(uniform):
+    # about one round of workgroups (140 sequences x 2 block pairs): a ragged batch is cut into chunks that
+    # follow the lengths and handed out longest first; a batch of nearly equal lengths is left uncut
+    rng = np.random.default_rng(77)
+    lens = (np.full(140, 2100) - rng.integers(0, 200, size=140) if uniform
+            else rng.integers(1, 3001, size=140)).astype(np.int32)
+    if not uniform:
+        lens[[3, 50]] = [0, 3000]
+    seqs = [0, 3, 17, 50, 99, 139, int(np.argmax(lens)), int(np.argmin(np.where(lens > 0, lens, 1 << 30)))]
+    wl = gen.WORKLOADS["M2"].scaled(batch=140, n_min=0, n_max=3000, shuffle_pages=True, spare_frac=0.1)
+    _check(gen.make_decode_inputs(wl, poison=True, seq_lens=lens), seqs=seqs)
+    wl = gen.WORKLOADS["G2"].scaled(batch=140, n_min=0, n_max=3000, shuffle_pages=True, spare_frac=0.1)
+    _check_gla2(wl, lens, seqs=seqs)
+
+
 def test_gla2_bf16_split_context_and_full_size_samples():
     wl = gen.WORKLOADS["G2"].scaled(batch=2, n_min=5000, n_max=9000)
     _check_gla2(wl, np.array([9000, 5000], dtype=np.int32))

@@ -205,11 +205,11 @@ def test_gqa_baseline(dtype, tol):
     assert err <= tol and np.all(out[0] == 0)
 
 
-def _mla_reference(inp):
+def _mla_reference(inp, seqs=None):
     wl = inp.wl
     v = oracle_views(inp)
     rows = []
-    for b in range(wl.batch):
+    for b in (range(wl.batch) if seqs is None else seqs):
         n = int(v["seq_lens"][b])
         if n == 0:
             rows.append(np.zeros((wl.h, wl.d_h)))
@@ -239,6 +239,23 @@ def test_mla_baseline_edge_shapes(h, lens, page_size):
     assert np.isfinite(out).all() and err <= 1e-2
     for b in np.flatnonzero(lens == 0):
         assert np.all(out[b] == 0)
+
+
+def test_mla_baseline_one_round_ragged_batch_is_cut_by_length():
+    rng = np.random.default_rng(78)
+    lens = rng.integers(1, 3001, size=140).astype(np.int32)
+    lens[[3, 50]] = [0, 3000]
+    wl = gen.WORKLOADS["C5"].scaled(batch=140, n_min=0, n_max=3000)
+    inp = gen.as_single_latent(gen.make_decode_inputs(wl, seq_lens=lens))
+    cache = device_cache(inp)
+    q_nope, q_rope, w_uk, w_uv = device_queries_weights(inp)
+    q_abs = mlra.mlra_absorb_q(q_nope, w_uk)
+    out = host(mlra.mla_decode_attn(cache, q_abs, q_rope, w_uv, wl.tau, out_dtype=torch.float32))
+    seqs = [0, 3, 17, 50, 99, 139, int(np.argmax(lens))]
+    ref = _mla_reference(inp, seqs=seqs)
+    err = max_rel_err(out[seqs], ref)
+    _say(f"[case] MLA baseline, 140 ragged sequences: max rel err {err:.3e}")
+    assert np.isfinite(out).all() and err <= 1e-2 and np.all(out[3] == 0)
 
 
 @pytest.mark.parametrize("h,g,lens,page_size", [
