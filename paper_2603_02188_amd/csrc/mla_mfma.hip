@@ -2,17 +2,21 @@
 // (Section 2.1, Steps 1-3 with d_c = 512; bf16 caches).
 //
 // One workgroup (4 wavefronts) owns one (sequence, context chunk, 64 query heads) and walks the chunk in
-// tiles of 32 tokens [C | K^RoPE] that stream HBM -> LDS with direct-to-LDS loads, three stages deep.
-// The 512 latent channels are split over the waves: wave w owns channels [128 w, 128 w + 128).
-//   * scores: wave w computes the partial S_w^T = C_w Q_w^T (+ one 16-dim slice of the RoPE product) for
-//     all 32 tokens x 64 heads; the four partials are exchanged through LDS and every wave forms the same
-//     full S^T (summed in one fixed order), the same running maxima and the same P^T (the softmax is recomputed four times rather
-//     than exchanged once more: it is cheap next to the MFMAs);
-//   * values: wave w accumulates Z_w^T += C_w^T P^T for its 128 channels, with C_w^T from LDS transpose
-//     reads of the same tile, so the Z accumulators (128 registers) and the queries (72) fit one wave.
-// Two workgroup barriers per tile order the loads, the stage reuse and the exchange buffer.  The two head
-// halves of a sequence are placed on the same XCD (ids 8 apart), so the cache is fetched from HBM once.
-// Partials go to the workspace in the layout of the MLRA path with n_blocks = 1, d_cb = 512.
+// tiles of 32 tokens [C | K^RoPE] that stream HBM -> LDS with direct-to-LDS loads, four stages deep
+// (three tiles in flight while one is worked on).  The two products split the work differently:
+//   * scores and softmax by heads: wave w owns heads [16 w, 16 w + 16) and computes their complete scores
+//     S^T = [C | K^R] [q~ | q^R]^T over all 576 channels with 16x16x32 MFMAs (tokens x heads), so the
+//     softmax of a head is computed once, by one wave, with its running maximum and sum in that wave;
+//   * values by channels: wave w accumulates Z_w^T += C_w^T P^T for channels [128 w, 128 w + 128) and all
+//     64 heads (32x32x16 MFMAs; C_w^T from LDS transpose reads of the same tile), so the 64 x 512
+//     accumulator is spread over the four waves (128 registers each).
+// Between the two, the probabilities P^T (bf16, 4 KiB per tile) go through LDS in the layout of the second
+// product's B operand, together with the factors by which a wave lowered the weight of its heads'
+// history when their running maximum grew (refreshed lazily, so almost always none).  Two workgroup
+// barriers per tile: one hands the landed tile and the freed stage around, one publishes P^T.
+// The two head halves of a sequence are placed on the same XCD (ids 8 apart), so the cache is fetched
+// from HBM once.  Partials go to the workspace in the layout of the MLRA path with n_blocks = 1,
+// d_cb = 512.
 #include "mfma_tile.h"
 
 namespace mlra {
@@ -26,18 +30,42 @@ constexpr int kMHeads = 64;                        // query heads per workgroup
 constexpr int kMLatBytes = kMTok * kMDc * 2;       // 32 KiB
 constexpr int kMRopeBytes = kMTok * kDr * 2;       //  4 KiB
 constexpr int kMStage = kMLatBytes + kMRopeBytes;  // 36 KiB
-constexpr int kMStages = 3;
-constexpr int kMXOff = kMStages * kMStage;         // exchange buffer: [4 waves][8 operands][64 lanes][16 B]
-constexpr int kMXWave = 8 * 1024;
-constexpr int kMLds = kMXOff + 4 * kMXWave;        // 143,360 bytes
+constexpr int kMStages = 4;
+constexpr int kMPOff = kMStages * kMStage;         // P^T: [2 tiles][2 head tiles][2 token halves][64 lanes][16 B]
+constexpr int kMPBytes = 4 * 1024;
+constexpr int kMAOff = kMPOff + 2 * kMPBytes;      // rescale factors: [2 tiles][64 heads] floats, then [2][4] flags
+constexpr int kMFOff = kMAOff + 2 * kMHeads * 4;
+constexpr int kMLds = kMFOff + 2 * 4 * 4;          // 156,192 bytes
 constexpr int kMLoads = 9;                         // direct-to-LDS loads per wave and tile
 
 typedef const __attribute__((address_space(3))) bf16x8* lds_bf16x8_ptr;
 typedef const __attribute__((address_space(3))) unsigned char* lds_byte_ptr;
 
-__device__ __forceinline__ void swap_halves(float& a, float& b) {
-  // exchanges the upper half of a with the lower half of b
+// The four lanes c16, c16 + 16, c16 + 32, c16 + 48 hold parts of one head: these combine them in every
+// lane without a trip through LDS.  v_permlane16_swap exchanges the odd 16-lane rows of its first operand
+// with the even rows of its second, v_permlane32_swap the upper half of the first with the lower half of
+// the second; applied to two copies of a value, every lane ends up with its own and its partner's.
+__device__ __forceinline__ void row_pairs(float& a, float& b) {
+  asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+}
+__device__ __forceinline__ void half_pairs(float& a, float& b) {
   asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+}
+__device__ __forceinline__ float head_max(float v) {
+  float a = v, b = v;
+  row_pairs(a, b);
+  a = fmaxf(a, b);
+  b = a;
+  half_pairs(a, b);
+  return fmaxf(a, b);
+}
+__device__ __forceinline__ float head_sum(float v) {
+  float a = v, b = v;
+  row_pairs(a, b);
+  a += b;
+  b = a;
+  half_pairs(a, b);
+  return a + b;
 }
 
 __global__ __launch_bounds__(256) void mla_mfma_kernel(MfmaParams p) {
@@ -76,29 +104,28 @@ __global__ __launch_bounds__(256) void mla_mfma_kernel(MfmaParams p) {
   const int ntiles = (t1 - t0 + kMTok - 1) / kMTok;
   const int nvalid_last = t1 - t0 - (ntiles - 1) * kMTok;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int g = lane >> 5, c32 = lane & 31;
+  const int g = lane >> 5, c32 = lane & 31;         // 32x32 MFMA roles (values)
+  const int q4 = lane >> 4, c16 = lane & 15;        // 16x16 MFMA roles (scores)
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
   const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
   const float sc = p.scale_log2;
   const int head_base = hgrp * kMHeads;
 
-  // ---- this wave's slice of the absorbed queries (128 of 512 channels) and of the RoPE queries (16 of 64
-  // dims) as MFMA B operands
-  bf16x8 qreg[2][9];
+  // ---- this wave's 16 heads, complete: absorbed (512) and RoPE (64) query channels as B operands of the
+  // 16x16x32 MFMA (lane: head c16, eight channels from 32 ks + 8 q4)
+  bf16x8 qreg[18];
+  {
+    const int head = min(head_base + 16 * wave + c16, p.h - 1);
+    const bf16_t* qa = p.q_abs + ((size_t)seq * p.h + head) * kMDc + q4 * 8;
+    const bf16_t* qr = p.q_rope + ((size_t)seq * p.h + head) * kDr + q4 * 8;
 #pragma unroll
-  for (int nt = 0; nt < 2; ++nt) {
-    const int head = min(head_base + nt * 32 + c32, p.h - 1);
-    const bf16_t* qa = p.q_abs + ((size_t)seq * p.h + head) * kMDc + wave * 128 + g * 8;
-    const bf16_t* qr = p.q_rope + ((size_t)seq * p.h + head) * kDr + wave * 16 + g * 8;
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) qreg[nt][ks] = *(const bf16x8*)(qa + ks * 16);
-    qreg[nt][8] = *(const bf16x8*)qr;
+    for (int ks = 0; ks < 16; ++ks) qreg[ks] = *(const bf16x8*)(qa + ks * 32);
+    qreg[16] = *(const bf16x8*)qr;
+    qreg[17] = *(const bf16x8*)(qr + 32);
   }
   // consumed here, before any direct-to-LDS load is in flight (a compiler-placed wait would drain them)
 #pragma unroll
-  for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-    for (int ks = 0; ks < 9; ++ks) asm volatile("" : "+v"(qreg[nt][ks]));
+  for (int ks = 0; ks < 18; ++ks) asm volatile("" : "+v"(qreg[ks]));
 
   // ---- tile loads.  Latent rows are 1 KiB: one load moves one token row (lane i: 16-byte chunk i, i.e.
   // 256-byte sub-row i / 16, stored at chunk position (i % 16) ^ lat_swz(token) inside the sub-row);
@@ -111,27 +138,47 @@ __global__ __launch_bounds__(256) void mla_mfma_kernel(MfmaParams p) {
   for (int i = 0; i < 8; ++i)
     lat_voff[i] = (lane >> 4) * 256 + (((lane & 15) ^ lat_swz(8 * wave + i)) << 4);
   const int rope_t = 8 * wave + (lane >> 3);
-  auto issue_tile = [&](int jj, int stage) {
+  // A tile is issued in parts so that the parts can sit behind different MFMAs: issue_begin (scalar
+  // address work), nine loads (0..7: latent rows, 8: the RoPE rows).
+  const char* iss_lat = nullptr;
+  const char* iss_rope = nullptr;
+  unsigned iss_dst = 0;
+  int iss_last = 0;
+  auto issue_begin = [&](int jj) {
     const int tok = t0 + jj * kMTok;
     const unsigned page = (unsigned)pt_row[min(tok / p.page_size, p.max_pages - 1)];
     const int slot = tok % p.page_size;
-    const char* lat_tile = (const char*)p.latent + page * lat_page_bytes + (size_t)slot * (kMDc * 2);
-    const char* rope_tile = (const char*)p.rope + page * rope_page_bytes + (size_t)slot * (kDr * 2);
-    const int last = min(kMTok, t1 - tok) - 1;     // rows past it re-read it (finite values, weight 0 later)
-    const unsigned dst = lds_base + stage * kMStage;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    iss_lat = (const char*)p.latent + page * lat_page_bytes + (size_t)slot * (kMDc * 2);
+    iss_rope = (const char*)p.rope + page * rope_page_bytes + (size_t)slot * (kDr * 2);
+    iss_last = min(kMTok, t1 - tok) - 1;     // rows past it re-read it (finite values, weight 0 later)
+    iss_dst = lds_base + (jj % kMStages) * kMStage;
+  };
+  auto issue_part = [&](int i) {
+    if (i < 8) {
       const int t = 8 * wave_u + i;
-      set_m0(dst + t * 1024);
-      lds_dma16<0>(lat_tile + (size_t)min(t, last) * 1024, lat_voff[i]);
+      set_m0(iss_dst + t * 1024);
+      lds_dma16<0>(iss_lat + (size_t)min(t, iss_last) * 1024, lat_voff[i]);
+    } else {
+      set_m0(iss_dst + kMLatBytes + wave_u * 1024);
+      lds_dma16<0>(iss_rope, (unsigned)min(rope_t, iss_last) * (kDr * 2) + (((lane & 7) ^ rope_swz(rope_t)) << 4));
     }
-    set_m0(dst + kMLatBytes + wave_u * 1024);
-    lds_dma16<0>(rope_tile, (unsigned)min(rope_t, last) * (kDr * 2) + (((lane & 7) ^ rope_swz(rope_t)) << 4));
+  };
+  auto issue_tile = [&](int jj) {
+    issue_begin(jj);
+#pragma unroll
+    for (int i = 0; i < kMLoads; ++i) issue_part(i);
   };
 
-  // ---- per-lane LDS read offsets inside a stage (XOR swizzle, see mfma_tile.h and decode_mfma.hip)
-  const unsigned k_lat_off = c32 * 1024 + wave * 256 + ((g ^ lat_swz(c32)) << 4);                       // ^ (ks << 5)
-  const unsigned k_rope_off = kMLatBytes + c32 * (kDr * 2) + (((2 * wave + g) ^ rope_swz(c32)) << 4);
+  // ---- per-lane LDS read offsets inside a stage (XOR swizzle, see mfma_tile.h and decode_mfma.hip).
+  // Scores, A operand of the 16x16x32 MFMA: lane = token c16 (+ 16 th) and eight channels from
+  // 32 ks + 8 q4, i.e. 16-byte chunk 4 ks + q4 of the token row: sub-row ks / 4, chunk 4 (ks % 4) + q4.
+  unsigned k_lat_off[2], k_rope_off[2];
+#pragma unroll
+  for (int th = 0; th < 2; ++th) {
+    const int t = 16 * th + c16;
+    k_lat_off[th] = t * 1024 + ((q4 ^ lat_swz(t)) << 4);                         // ^ ((ks % 4) << 6), + 256 (ks / 4)
+    k_rope_off[th] = kMLatBytes + t * (kDr * 2) + ((q4 ^ rope_swz(t)) << 4);     // ^ (kr << 6)
+  }
   unsigned v_off[2];                                                          // ^ (mt << 6), + 16 KiB ss
   {
     const int k = (lane & 15) >> 2, seg = lane & 3, hb = (lane >> 4) & 1;
@@ -141,9 +188,13 @@ __global__ __launch_bounds__(256) void mla_mfma_kernel(MfmaParams p) {
       v_off[half] = ta * 1024 + wave * 256 + (((2 * hb + (seg >> 1)) ^ lat_swz(ta)) << 4) + ((seg & 1) << 3);
     }
   }
-  unsigned char* xbuf = smem + kMXOff;
+  // P^T: the B operand (head tile w / 2, token half th) pairs with the transposed value operand, whose
+  // lane group g holds tokens 4 g .. 4 g + 3 and 8 + 4 g .. 8 + 4 g + 3 of the 16.  This lane's four
+  // probabilities (tokens 4 q4 .. + 3 of the half, head 16 w + c16) are therefore the first (q4 < 2) or second
+  // four of lane n + 32 (q4 % 2), n = 16 (w % 2) + c16.
+  const unsigned p_wr_off = (wave >> 1) * 2048 + (16 * (wave & 1) + c16 + 32 * (q4 & 1)) * 16 + (q4 >> 1) * 8;  // + 1024 th
 
-  float m_run[2] = {kNegBig, kNegBig}, l_run[2] = {0.f, 0.f};
+  float m_run = kNegBig, l_run = 0.f;      // of head 16 w + c16 (the four lanes of a head hold equal m)
   f32x16 zacc[4][2];
 #pragma unroll
   for (int mt = 0; mt < 4; ++mt)
@@ -152,39 +203,74 @@ __global__ __launch_bounds__(256) void mla_mfma_kernel(MfmaParams p) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) zacc[mt][nt][i] = 0.f;
 
-  for (int jj = 0; jj < kMStages - 1 && jj < ntiles; ++jj) issue_tile(jj, jj);
-  int st_cur = 0;
+  for (int jj = 0; jj < kMStages - 1 && jj < ntiles; ++jj) issue_tile(jj);
   for (int j = 0; j < ntiles; ++j) {
-    // tile j landed for every wave; everyone is done with tile j-1 (its stage, the exchange buffer)
-    if (j + 1 < ntiles) wait_vm_lgkm<kMLoads>(); else wait_vm_lgkm<0>();
+    // tile j landed in this wave's share (the tiles issued after it may still be in flight) ...
+    if (j + 2 < ntiles) wait_vm_lgkm<2 * kMLoads>();
+    else if (j + 1 < ntiles) wait_vm_lgkm<kMLoads>();
+    else wait_vm_lgkm<0>();
+    // ... and in everybody's; every wave is also done with tile j-1, whose stage is refilled now
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    const unsigned base = lds_base + st_cur * kMStage;
+    const bool refill = j + kMStages - 1 < ntiles;     // its loads go out behind the value MFMAs below
+    if (refill) issue_begin(j + kMStages - 1);
+    const unsigned base = lds_base + (j % kMStages) * kMStage;
+    const int par = j & 1;
 
-    // ---- partial scores over this wave's 128 channels and its RoPE slice
-    f32x16 s[2];
-#pragma unroll
-    for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) s[nt][i] = 0.f;
+    // ---- scores of this wave's 16 heads: 36 MFMAs, operand reads twelve ahead
+    f32x4 s[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
     {
-      bf16x8 ka[9];
+      auto k_read = [&](int i) {     // i = 2 ks + th
+        const int ks = i >> 1, th = i & 1;
+        const unsigned addr = ks < 16 ? ((base + k_lat_off[th] + (ks >> 2) * 256) ^ ((ks & 3) << 6))
+                                      : ((base + k_rope_off[th]) ^ ((ks - 16) << 6));
+        return *(lds_bf16x8_ptr)(size_t)addr;
+      };
+      constexpr int kAhead = 12;
+      bf16x8 ka[kAhead];
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) ka[ks] = *(lds_bf16x8_ptr)(size_t)((base + k_lat_off) ^ (ks << 5));
-      ka[8] = *(lds_bf16x8_ptr)(size_t)(base + k_rope_off);
+      for (int i = 0; i < kAhead; ++i) ka[i] = k_read(i);
 #pragma unroll
-      for (int ks = 0; ks < 9; ++ks) {
-        s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[0][ks], s[0], 0, 0, 0);
-        s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[1][ks], s[1], 0, 0, 0);
-        // keeps ka[0] alive past the two MFMAs whose accumulator input is the constant 0, so that the
-        // allocator cannot place their destination on top of it (the build also scans for that)
-        if (ks == 1) asm volatile("" : : "v"(ka[0]));
+      for (int i = 0; i < 36; ++i) {
+        const bf16x8 cur = ka[i % kAhead];
+        if (i + kAhead < 36) ka[i % kAhead] = k_read(i + kAhead);
+        s[i & 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur, qreg[i >> 1], s[i & 1], 0, 0, 0);
       }
     }
-    // ---- while the matrix pipe works: loads of tile j+2 into the stage tile j-1 left (the CU's address
-    // unit takes about 16 cycles per load), and the transposed value operands of this wave's channels
-    __builtin_amdgcn_sched_barrier(0);
-    if (j + kMStages - 1 < ntiles) issue_tile(j + kMStages - 1, (st_cur + kMStages - 1) % kMStages);
+
+    // ---- softmax of the 16 heads (running maximum refreshed lazily, see decode_mfma.hip)
+    float mx = fmaxf(fmaxf(fmaxf(s[0][0], s[0][1]), fmaxf(s[0][2], s[0][3])),
+                     fmaxf(fmaxf(s[1][0], s[1][1]), fmaxf(s[1][2], s[1][3])));
+    mx = head_max(mx);
+    const float cand = mx * sc;
+    const bool grow = cand > m_run + kLazy;
+    const bool any_grow = __any(grow);
+    float alpha = 1.f;
+    if (any_grow) {
+      const float m_new = grow ? cand : m_run;
+      alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+      l_run *= alpha;
+      m_run = m_new;
+    }
+    const int valid = (j == ntiles - 1) ? nvalid_last : kMTok;
+    const float neg_m = -m_run;
+#pragma unroll
+    for (int th = 0; th < 2; ++th) {
+      float pe[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        pe[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[th][i], sc, neg_m));
+        if (16 * th + 4 * q4 + i >= valid) pe[i] = 0.f;     // rows past a ragged end are copies of the last valid row
+        l_run += pe[i];
+      }
+      typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+      const bf16x4 pk = {(__bf16)pe[0], (__bf16)pe[1], (__bf16)pe[2], (__bf16)pe[3]};
+      *(bf16x4*)(smem + kMPOff + par * kMPBytes + th * 1024 + p_wr_off) = pk;
+    }
+    if (q4 == 0) ((float*)(smem + kMAOff))[par * kMHeads + 16 * wave + c16] = alpha;
+    if (lane == 0) ((int*)(smem + kMFOff))[par * 4 + wave] = any_grow ? 1 : 0;
+
+    // ---- the transposed value operands of this wave's channels do not depend on P^T: fetch them first
     bf16x8 va[2][4];
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt) {
@@ -197,84 +283,48 @@ __global__ __launch_bounds__(256) void mla_mfma_kernel(MfmaParams p) {
         va[ss][mt] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
       }
     }
-    __builtin_amdgcn_sched_barrier(0);
-    // ---- exchange: own partial out, the other three in
-#pragma unroll
-    for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        const f32x4 v = {s[nt][r4 * 4], s[nt][r4 * 4 + 1], s[nt][r4 * 4 + 2], s[nt][r4 * 4 + 3]};
-        *(f32x4*)(xbuf + wave * kMXWave + (nt * 4 + r4) * 1024 + lane * 16) = v;
-      }
-    __syncthreads();
-    // every wave sums the four partials in the same order, so all four hold bit-identical S^T and take
-    // identical softmax decisions
-#pragma unroll
-    for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        f32x4 acc = *(const f32x4*)(xbuf + (nt * 4 + r4) * 1024 + lane * 16);
-#pragma unroll
-        for (int w = 1; w < 4; ++w) {
-          const f32x4 v = *(const f32x4*)(xbuf + w * kMXWave + (nt * 4 + r4) * 1024 + lane * 16);
-          acc[0] += v[0]; acc[1] += v[1]; acc[2] += v[2]; acc[3] += v[3];
-        }
-        s[nt][r4 * 4] = acc[0];
-        s[nt][r4 * 4 + 1] = acc[1];
-        s[nt][r4 * 4 + 2] = acc[2];
-        s[nt][r4 * 4 + 3] = acc[3];
-      }
+    __syncthreads();     // P^T, the factors and the flags of every wave are visible
 
-    // ---- online softmax (running maximum refreshed lazily, see decode_mfma.hip) and Z accumulation
-    const int valid = (j == ntiles - 1) ? nvalid_last : kMTok;
-    bf16x8 pb[2][2];
+    // ---- a head's history loses weight when its maximum grew: the owner of the head said by how much
+    {
+      const int4 fl = *(const int4*)(smem + kMFOff + par * 16);
+      if (__builtin_amdgcn_readfirstlane(fl.x | fl.y | fl.z | fl.w)) {
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt) {
-      float mx = fmaxf(fmaxf(s[nt][0], s[nt][1]), s[nt][2]);
+        for (int nt = 0; nt < 2; ++nt) {
+          const float a_h = ((const float*)(smem + kMAOff))[par * kMHeads + nt * 32 + c32];
 #pragma unroll
-      for (int i = 3; i < 15; i += 2) mx = fmaxf(fmaxf(mx, s[nt][i]), s[nt][i + 1]);
-      mx = fmaxf(mx, s[nt][15]);
-      float mx2 = mx;
-      swap_halves(mx, mx2);
-      mx = fmaxf(mx, mx2);
-      const float cand = mx * sc;
-      if (__any(cand > m_run[nt] + kLazy)) {
-        const float m_new = cand > m_run[nt] + kLazy ? cand : m_run[nt];
-        const float alpha = __builtin_amdgcn_exp2f(m_run[nt] - m_new);
+          for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
-        for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) zacc[mt][nt][i] *= alpha;
-        l_run[nt] *= alpha;
-        m_run[nt] = m_new;
-      }
-      const float neg_m = -m_run[nt];
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int tok = (i >> 2) * 8 + g * 4 + (i & 3);
-        float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(s[nt][i], sc, neg_m));
-        if (tok >= valid) pe = 0.f;       // rows past a ragged end are copies of the last valid row
-        l_run[nt] += pe;
-        pb[nt][i >> 3][i & 7] = (__bf16)pe;
+            for (int i = 0; i < 16; ++i) zacc[mt][nt][i] *= a_h;
+        }
       }
     }
+    // ---- values: Z_w^T += C_w^T P^T
+    bf16x8 pb[2][2];
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+      for (int ss = 0; ss < 2; ++ss)
+        pb[nt][ss] = *(const bf16x8*)(smem + kMPOff + par * kMPBytes + (nt * 2 + ss) * 1024 + lane * 16);
 #pragma unroll
     for (int ss = 0; ss < 2; ++ss)
 #pragma unroll
       for (int mt = 0; mt < 4; ++mt) {
         zacc[mt][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[ss][mt], pb[0][ss], zacc[mt][0], 0, 0, 0);
         zacc[mt][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[ss][mt], pb[1][ss], zacc[mt][1], 0, 0, 0);
+        // the loads of tile j+3 into the stage tile j-1 left (free since the barrier at the top), one or
+        // two behind each pair of MFMAs: the CU's address unit takes about 16 cycles per load
+        if (refill) {
+          const int k = ss * 4 + mt;       // 0..7
+          issue_part(k);
+          if (k == 7) issue_part(8);
+        }
+        __builtin_amdgcn_sched_barrier(0);
       }
-    st_cur = (st_cur + 1 == kMStages) ? 0 : st_cur + 1;
   }
 
-  // ---- write the chunk's partial: every wave its 128 channels (the four waves hold identical m and l)
-#pragma unroll
-  for (int nt = 0; nt < 2; ++nt) {
-    float l2 = l_run[nt];
-    swap_halves(l_run[nt], l2);
-    l_run[nt] += l2;
-  }
+  // ---- write the chunk's partial: every wave its 128 channels of all 64 heads, and (m, l) of its 16 heads
+  l_run = head_sum(l_run);
   const size_t unit = (size_t)seq * p.n_splits + split;
 #pragma unroll
   for (int nt = 0; nt < 2; ++nt) {
@@ -289,10 +339,13 @@ __global__ __launch_bounds__(256) void mla_mfma_kernel(MfmaParams p) {
                            zacc[mt][nt][r4 * 4 + 3]};
           *(f32x4*)(dst + mt * 32 + r4 * 8) = v;
         }
-      if (wave == 0 && g == 0) {
-        p.part_ml[(unit * p.h + head) * 2 + 0] = m_run[nt];
-        p.part_ml[(unit * p.h + head) * 2 + 1] = l_run[nt];
-      }
+    }
+  }
+  {
+    const int head = head_base + 16 * wave + c16;
+    if (q4 == 0 && head < p.h) {
+      p.part_ml[(unit * p.h + head) * 2 + 0] = m_run;
+      p.part_ml[(unit * p.h + head) * 2 + 1] = l_run;
     }
   }
 }
