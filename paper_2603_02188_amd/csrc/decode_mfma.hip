@@ -67,14 +67,14 @@ __global__ __launch_bounds__(256) void plan_chunks_kernel(const int32_t* __restr
                                                           int32_t* __restrict__ chunk_tab,
                                                           int32_t* __restrict__ unit_tab, int batch, int target,
                                                           int max_slots, int min_chunk, int single_if_uniform) {
-  __shared__ float part[256];
-  __shared__ int part_max[256];
-  __shared__ int seg_sum[256];
-  __shared__ int n_active;
+  __shared__ float part[4];
+  __shared__ int part_max[4];
+  __shared__ int wave_tot[4];
   extern __shared__ int32_t tab[];             // [batch] lengths, [batch] chunk lengths, [batch] dispatch order
   int32_t* lens = tab;
   int32_t* chunks = tab + batch;
   int32_t* order = tab + 2 * batch;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   float sum = 0.f;
   int longest = 0;
   for (int i = threadIdx.x; i < batch; i += 256) {
@@ -82,18 +82,16 @@ __global__ __launch_bounds__(256) void plan_chunks_kernel(const int32_t* __restr
     sum += (float)lens[i];
     longest = max(longest, lens[i]);
   }
-  part[threadIdx.x] = sum;
-  part_max[threadIdx.x] = longest;
-  __syncthreads();
-  for (int s = 128; s > 0; s >>= 1) {
-    if (threadIdx.x < s) {
-      part[threadIdx.x] += part[threadIdx.x + s];
-      part_max[threadIdx.x] = max(part_max[threadIdx.x], part_max[threadIdx.x + s]);
-    }
-    __syncthreads();
+  // (lengths are integers below 2^31 and their partial sums are added in one fixed order)
+  for (int o = 32; o > 0; o >>= 1) {
+    sum += __shfl_xor(sum, o);
+    longest = max(longest, __shfl_xor(longest, o));
   }
-  const float total = part[0];
-  const bool single = single_if_uniform && (float)part_max[0] * (float)batch <= 1.25f * total;
+  if (lane == 0) { part[wave] = sum; part_max[wave] = longest; }
+  __syncthreads();
+  const float total = (part[0] + part[1]) + (part[2] + part[3]);
+  longest = max(max(part_max[0], part_max[1]), max(part_max[2], part_max[3]));
+  const bool single = single_if_uniform && (float)longest * (float)batch <= 1.25f * total;
   for (int i = threadIdx.x; i < batch; i += 256) {
     const int n = lens[i];
     int s_i = (total > 0.f && !single) ? (int)((float)target * (float)n / total + 0.5f) : 1;
@@ -125,15 +123,17 @@ __global__ __launch_bounds__(256) void plan_chunks_kernel(const int32_t* __restr
     const int i = order[r];
     mine += (lens[i] + chunks[i] - 1) / chunks[i];
   }
-  seg_sum[threadIdx.x] = mine;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    int run = 0;
-    for (int t = 0; t < 256; ++t) { const int v = seg_sum[t]; seg_sum[t] = run; run += v; }
-    n_active = run;
+  // (scan over the 256 threads: inside a wave with shuffles, across the four waves through LDS)
+  int incl = mine;
+  for (int o = 1; o < 64; o <<= 1) {
+    const int v = __shfl_up(incl, o);
+    if (lane >= o) incl += v;
   }
+  if (lane == 63) wave_tot[wave] = incl;
   __syncthreads();
-  int u = seg_sum[threadIdx.x];
+  int u = incl - mine;
+  for (int w = 0; w < wave; ++w) u += wave_tot[w];
+  const int n_active = wave_tot[0] + wave_tot[1] + wave_tot[2] + wave_tot[3];
   for (int r = lo; r < hi; ++r) {
     const int i = order[r];
     const int active = (lens[i] + chunks[i] - 1) / chunks[i];

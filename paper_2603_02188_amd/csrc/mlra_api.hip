@@ -45,9 +45,11 @@ static SplitPlan plan_decode(int batch, int h, int n_blocks, int d_cb, int max_s
   SplitPlan p = plan_splits(batch, groups, max_seq_len);
   // Split mode on the MFMA MLRA shape with long chunks: twice the chunk slots, so that long sequences of
   // a ragged batch can take more chunks than short ones (the decode entry decides per call whether it
-  // uses them).  The planning kernel and the round of idle slots cost a few microseconds, which only
-  // chunks of 128 tiles or more (about 140 us of work) make negligible.
-  if (d_cb == 128 && p.n_splits > 1 && p.chunk_tokens >= 8192 && 2 * p.n_splits * n_blocks <= 128) {
+  // uses them).  The planning kernel and the round of idle slots cost 6-9 us whatever the batch looks
+  // like, and what they save depends on how ragged it is (about a tenth of the kernel for lengths spread
+  // over a factor of two): chunks of 96 tiles or more (about 110 us of work) are where a ragged batch
+  // gains more than a uniform one loses.
+  if (d_cb == 128 && p.n_splits > 1 && p.chunk_tokens >= 6144 && 2 * p.n_splits * n_blocks <= 128) {
     p.target_chunks = p.n_splits * batch;
     p.n_splits *= 2;
   }
