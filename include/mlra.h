@@ -228,6 +228,21 @@ MLRA_API int gqa_decode_attn(const void* k_pool, const void* v_pool, const int32
 MLRA_API int mlra_kernel_timing_begin(int32_t max_calls);
 MLRA_API int mlra_kernel_timing_end(double* main_kernel_ms, double* epilogue_kernel_ms, int32_t* calls);
 
+/* Introspection aid (host logic only, touches no device memory and enqueues nothing): which kernels and
+ * which context split a decode call of this shape takes.  Arguments as for the decode entry points: h is
+ * the total number of query heads, groups is 1 for mlra_decode_attn / mla_decode_attn and 2 for
+ * mlra2_decode_attn, dtype the cache dtype, max_seq_len = max_pages_per_seq * page_size.  info is a HOST
+ * array of 6 values:
+ *   [0] decode kernel: 0 generic, 1 MFMA plain form, 2 MFMA PAIRED form (two blocks per workgroup),
+ *       3 MFMA GLA form (256-channel latent heads), 4 MFMA MLA kernel (one 512-channel latent)
+ *   [1] chunk slots per (sequence, block)     [2] uniform chunk length in tokens
+ *   [3] > 0: chunk lengths may follow the sequence lengths (planning kernel), with this many chunks per block
+ *       as the target                          [4] 1: a batch of nearly equal lengths is then left uncut
+ *   [5] 1: the merge + up-projection epilogue runs on MFMA, 0: generic
+ * Returns MLRA_OK, or MLRA_ERR_NULL / MLRA_ERR_SHAPE / MLRA_ERR_DTYPE as the decode entry points would. */
+MLRA_API int mlra_decode_plan_info(int32_t batch, int32_t h, int32_t d_h, int32_t groups, int32_t n_blocks, int32_t d_cb,
+                                   int32_t d_r, int32_t page_size, int32_t max_seq_len, int32_t dtype, int32_t* info);
+
 #ifdef __cplusplus
 }
 #endif

@@ -24,7 +24,7 @@ EXPORTS = ("mlra_strerror", "mlra_append_kv", "mlra_absorb_q", "mlra_decode_work
            "mlra2_decode_attn", "mlra_decode_attn_gated", "mlra_decode_multi_workspace_bytes", "mlra_decode_attn_multi",
            "mlra_pre_attention_workspace_bytes", "mlra_pre_attention",
            "gqa_decode_workspace_bytes", "gqa_decode_attn", "mlra_kernel_timing_begin",
-           "mlra_kernel_timing_end")
+           "mlra_kernel_timing_end", "mlra_decode_plan_info")
 
 
 class _CacheStruct(ctypes.Structure):
@@ -87,6 +87,8 @@ def load_library() -> ctypes.CDLL:
     lib.mlra_pre_attention.argtypes = [cp, ctypes.POINTER(_PreWeightsStruct), i32, vp, vp, vp, vp, vp, sz, vp]
     lib.mla_decode_attn.restype = ctypes.c_int
     lib.mla_decode_attn.argtypes = [cp, i32, i32, i32, vp, vp, vp, f32, vp, i32, vp, vp, sz, vp]
+    lib.mlra_decode_plan_info.restype = ctypes.c_int
+    lib.mlra_decode_plan_info.argtypes = [i32] * 10 + [ctypes.POINTER(ctypes.c_int32)]
     lib.gqa_decode_workspace_bytes.restype = sz
     lib.gqa_decode_workspace_bytes.argtypes = [i32, i32, i32, i32]
     lib.gqa_decode_attn.restype = ctypes.c_int
@@ -390,6 +392,19 @@ def gqa_decode_attn(k_pool: torch.Tensor, v_pool: torch.Tensor, page_table: torc
                                _dt(out.dtype), _ptr(workspace), workspace.numel() * workspace.element_size(),
                                _stream(stream)), "gqa_decode_attn")
     return out
+
+
+DECODE_KERNELS = ("generic", "mfma", "mfma-paired", "mfma-gla", "mfma-mla")
+
+
+def mlra_decode_plan_info(batch: int, h: int, d_h: int, groups: int, n_blocks: int, d_cb: int, d_r: int,
+                          page_size: int, max_seq_len: int, dtype: torch.dtype) -> dict:
+    """Which kernels and which context split a decode call of this shape takes (host logic only)."""
+    info = (ctypes.c_int32 * 6)()
+    _check(load_library().mlra_decode_plan_info(batch, h, d_h, groups, n_blocks, d_cb, d_r, page_size, max_seq_len,
+                                                _dt(dtype), info), "mlra_decode_plan_info")
+    return {"kernel": DECODE_KERNELS[info[0]], "chunk_slots": info[1], "chunk_tokens": info[2],
+            "target_chunks": info[3], "single_if_uniform": bool(info[4]), "merge_mfma": bool(info[5])}
 
 
 def mlra_kernel_timing_begin(max_calls: int) -> None:

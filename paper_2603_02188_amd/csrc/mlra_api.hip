@@ -337,6 +337,37 @@ int mla_decode_attn(const mlra_cache* cache, int32_t batch, int32_t h, int32_t d
                        workspace, workspace_bytes, stream);
 }
 
+int mlra_decode_plan_info(int32_t batch, int32_t h, int32_t d_h, int32_t groups, int32_t n_blocks, int32_t d_cb,
+                          int32_t d_r, int32_t page_size, int32_t max_seq_len, int32_t dtype, int32_t* info) {
+  if (!info) return MLRA_ERR_NULL;
+  if (!valid_dtype(dtype)) return MLRA_ERR_DTYPE;
+  if (batch <= 0 || h <= 0 || d_h <= 0 || groups <= 0 || n_blocks <= 0 || d_cb <= 0 || d_r <= 0 || page_size <= 0 ||
+      max_seq_len <= 0 || h % groups != 0 || n_blocks % groups != 0)
+    return MLRA_ERR_SHAPE;
+  DecodeArgs a = {};
+  a.batch = batch;
+  a.h = h / groups;          // heads served by one block
+  a.groups = groups;
+  a.d_h = d_h;
+  a.n_blocks = n_blocks;
+  a.d_cb = d_cb;
+  a.d_r = d_r;
+  a.page_size = page_size;
+  a.max_pages = (max_seq_len + page_size - 1) / page_size;
+  a.dtype = dtype;
+  a.plan = plan_decode(batch, a.h, n_blocks, d_cb, a.max_pages * page_size);
+  info[0] = decode_mfma_supported(a) ? (decode_mfma_paired(a.h, n_blocks) ? 2 : 1)
+            : decode_gla_supported(a) ? 3
+            : mla_mfma_supported(a)  ? 4
+                                     : 0;
+  info[1] = a.plan.n_splits;
+  info[2] = a.plan.chunk_tokens;
+  info[3] = a.plan.target_chunks;
+  info[4] = a.plan.single_if_uniform ? 1 : 0;
+  info[5] = merge_upproj_mfma_supported(a) ? 1 : 0;
+  return MLRA_OK;
+}
+
 int mlra_kernel_timing_begin(int32_t max_calls) {
   if (max_calls <= 0 || max_calls > 100000) return MLRA_ERR_SHAPE;
   for (hipEvent_t e : g_events) (void)hipEventDestroy(e);

@@ -124,3 +124,53 @@ def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
     monkeypatch.setattr(mlra, "_LIB_PATH", str(tmp_path / "libmlra.so"))
     with pytest.raises(RuntimeError, match="no CPU or PyTorch fallback"):
         mlra.load_library()
+
+
+def test_workload_shapes_take_the_fast_paths():
+    """Host logic: the benchmark shapes run on the MFMA kernels with the context split they were tuned with
+    (a shape that silently fell back to a generic kernel, or lost its planning mode, would still pass
+    parity)."""
+    import numpy as np
+    import torch
+    from paper_2603_02188_amd import inputs as gen
+
+    def info(key, **kw):
+        wl = gen.WORKLOADS[key]
+        lens = gen.draw_seq_lens(wl)
+        max_seq_len = int(-(-int(lens.max()) // wl.page_size) * wl.page_size)
+        dt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+        args = dict(batch=wl.batch, h=wl.h, d_h=wl.d_h, groups=wl.groups, n_blocks=wl.n_blocks, d_cb=wl.d_cb,
+                    d_r=wl.d_r, page_size=wl.page_size, max_seq_len=max_seq_len, dtype=dt)
+        args.update(kw)
+        return mlra.mlra_decode_plan_info(**args)
+
+    assert info("C1")["kernel"] == "generic"                         # fp32 cache
+    c2 = info("C2")
+    assert (c2["kernel"], c2["chunk_slots"], c2["chunk_tokens"], c2["merge_mfma"]) == ("mfma", 16, 1024, True)
+    c3 = info("C3")
+    assert (c3["kernel"], c3["chunk_slots"], c3["target_chunks"], c3["merge_mfma"]) == ("mfma", 1, 0, True)
+    c4 = info("C4")                                                  # long ragged contexts: planned chunks
+    assert c4["kernel"] == "mfma" and c4["target_chunks"] == 64 and c4["chunk_slots"] == 32 and c4["merge_mfma"]
+    c5 = info("C5")
+    assert (c5["kernel"], c5["chunk_slots"], c5["target_chunks"]) == ("mfma", 1, 0)
+    assert info("C5", page_size=16)["kernel"] == "mfma" and info("C5", page_size=48)["kernel"] == "generic"
+    m2, g2 = info("M2"), info("G2")
+    assert (m2["kernel"], m2["chunk_slots"], m2["target_chunks"]) == ("mfma-paired", 2, 0)
+    assert (g2["kernel"], g2["chunk_slots"], g2["target_chunks"]) == ("mfma-gla", 2, 0)
+    # the comparison kernels on the C5 batch: about one round of workgroups, so chunks are planned
+    mla = info("C5", groups=1, n_blocks=1, d_cb=512, max_seq_len=8192)
+    assert mla["kernel"] == "mfma-mla" and mla["target_chunks"] == 256 and mla["single_if_uniform"]
+    two = info("M2", batch=128, max_seq_len=8192)
+    assert two["kernel"] == "mfma-paired" and two["chunk_slots"] == 4 and two["single_if_uniform"]
+
+
+def test_plan_info_errors():
+    import ctypes
+    import torch
+    lib = mlra.load_library()
+    buf = (ctypes.c_int32 * 6)()
+    assert lib.mlra_decode_plan_info(4, 128, 128, 1, 4, 128, 64, 64, 8192, 0, None) == -1
+    assert lib.mlra_decode_plan_info(0, 128, 128, 1, 4, 128, 64, 64, 8192, 0, buf) == -2
+    assert lib.mlra_decode_plan_info(4, 127, 128, 2, 4, 128, 64, 64, 8192, 0, buf) == -2      # heads do not split into groups
+    assert lib.mlra_decode_plan_info(4, 128, 128, 1, 4, 128, 64, 64, 8192, 7, buf) == -3
+    assert mlra.mlra_decode_plan_info(4, 128, 128, 1, 4, 128, 64, 64, 8192, torch.bfloat16)["kernel"] == "mfma"
