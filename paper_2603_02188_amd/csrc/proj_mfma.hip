@@ -41,12 +41,13 @@ __device__ __forceinline__ short4v lds_tr16(const void* p) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// absorb_q.  One workgroup per (head, block); wave w produces the 32-channel tile ct0 + w of each pass
-// over four tiles.  S^T-free formulation: out[seq][c] = sum_p q[seq][p] W[c][p], so the A operand (rows =
-// sequences) and the B operand (columns = channels) are both contiguous 16-byte global loads.  Sixty-four
-// sequences go through at a time: all of their query loads are issued before the first MFMA (one
-// round trip instead of one per k-step), and the results pass through LDS so that they leave as whole
-// 16-byte pieces of the q_abs rows instead of single elements.
+// absorb_q.  One workgroup per (head, block, 64 sequences); wave w produces the 32-channel tile ct0 + w of
+// each pass over four tiles.  S^T-free formulation: out[seq][c] = sum_p q[seq][p] W[c][p], so the A operand (rows =
+// sequences) and the B operand (columns = channels) are both contiguous 16-byte global loads.  All query
+// loads of the 64 sequences are issued before the first MFMA (one round trip instead of one per k-step),
+// and the results pass through LDS so that they leave as whole 16-byte pieces of the q_abs rows instead
+// of single elements.  Larger batches put their 64-sequence tiles on the grid (the weights of a head are
+// then read once from HBM and again from L2).
 // ------------------------------------------------------------------------------------------------
 constexpr int kAbsPitch = 128 * 2 + 16;   // bytes per staged sequence row (128 channels; +16: rows on different banks)
 
@@ -69,7 +70,8 @@ __global__ __launch_bounds__(256) void absorb_q_mfma_kernel(const bf16_t* __rest
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) breg[ks] = *(const bf16x8*)(wrow + ks * 16);
     const int pass_ch = min(128, d_cb - ct0 * 32);          // channels this pass produces
-    for (int m0 = 0; m0 < batch; m0 += 64) {
+    {
+      const int m0 = blockIdx.z * 64;      // 64 sequences per workgroup
       bf16x8 areg[2][8];
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
@@ -327,7 +329,7 @@ bool absorb_q_mfma_supported(int d_h, int d_cb, int dtype) {
 int launch_absorb_q_mfma(int batch, int h, int d_h, int n_blocks, int groups, int d_cb, const void* q_nope,
                          const void* w_uk, void* q_abs, hipStream_t stream) {
   (void)d_h;
-  dim3 grid(h, n_blocks);
+  dim3 grid(h, n_blocks, (batch + 63) / 64);
   absorb_q_mfma_kernel<<<grid, 256, 0, stream>>>((const bf16_t*)q_nope, (const bf16_t*)w_uk, (bf16_t*)q_abs, batch, h,
                                                  n_blocks, groups, d_cb);
   return check_launch();
