@@ -125,6 +125,7 @@ static int decode_common(const mlra_cache* c, int batch, int h, int groups, int 
   a.chunk_tab = (int32_t*)((char*)a.seq_order + align_up((size_t)batch * sizeof(int32_t), 256));
   a.unit_tab = (int32_t*)((char*)a.chunk_tab + align_up((size_t)batch * sizeof(int32_t), 256));
   a.balanced = false;
+  a.direct = false;
   a.latent = c->latent;
   a.rope = c->rope;
   a.page_table = c->page_table;
@@ -154,6 +155,10 @@ static int decode_common(const mlra_cache* c, int batch, int h, int groups, int 
   if (a.plan.target_chunks > 0 && merge_upproj_mfma_supported(a) &&
       (decode_mfma_supported(a) || decode_gla_supported(a) || mla_mfma_supported(a)))
     a.balanced = launch_plan_chunks(a) == MLRA_OK;
+  // one chunk per sequence on the MFMA kernels: the decode kernel hands the up-projection normalised bf16
+  // rows instead of fp32 partials
+  a.direct = a.plan.n_splits == 1 && !a.balanced && merge_upproj_mfma_supported(a) &&
+             (decode_mfma_supported(a) || decode_gla_supported(a));
   int st = decode_mfma_supported(a) ? launch_decode_mfma(a)
            : decode_gla_supported(a) ? launch_decode_gla(a)
            : mla_mfma_supported(a)  ? launch_mla_mfma(a)

@@ -131,7 +131,7 @@ __global__ __launch_bounds__(256) void merge_upproj_mfma_kernel(
     const float* __restrict__ part_z, const float* __restrict__ part_ml, const int32_t* __restrict__ seq_lens,
     const bf16_t* __restrict__ w_uv, TO* __restrict__ out, float* __restrict__ lse, int batch, int h, int nb_total,
     int d_cb, int n_splits, int chunk, const int32_t* __restrict__ chunk_tab, float out_scale,
-    const bf16_t* __restrict__ gate) {
+    const bf16_t* __restrict__ gate, int direct) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   // blockIdx.z = head group (Eq. (6)); one group of all blocks is Eq. (5).  h: heads per block; this
   // workgroup's head is h * group + head in out, and its branches are blocks [b0, b0 + n_blocks).
@@ -267,7 +267,19 @@ __global__ __launch_bounds__(256) void merge_upproj_mfma_kernel(
       }
     }
   };
-  if (n_splits > 8) merge_items(std::integral_constant<int, 1>{});
+  if (direct) {
+    // one chunk per sequence and the decode kernel wrote z / l as bf16 rows [.][block][head][d_cb]: copy
+    const bf16_t* zn = (const bf16_t*)part_z;
+    for (int item = tid; item < n_items; item += 256) {
+      const int sl = item / items_per_row, r0 = (item % items_per_row) * 8;
+      const int b = r0 / d_cb, c0 = r0 % d_cb;
+      bf16x8 v;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] = (__bf16)0.0f;
+      if (act[sl] > 0) v = *(const bf16x8*)(zn + (((size_t)(m0 + sl) * nb_total + b0 + b) * h + head) * d_cb + c0);
+      *(bf16x8*)(zt + sl * zpitch + r0) = v;
+    }
+  } else if (n_splits > 8) merge_items(std::integral_constant<int, 1>{});
   else if (n_splits > 4) merge_items(std::integral_constant<int, 2>{});
   else if (n_splits > 2) merge_items(std::integral_constant<int, 4>{});
   else merge_items(std::integral_constant<int, 8>{});
@@ -359,12 +371,12 @@ int launch_merge_upproj_mfma(const DecodeArgs& a) {
     merge_upproj_mfma_kernel<bf16_t><<<grid, 256, lds, a.stream>>>(
         a.part_z, a.part_ml, a.seq_lens, (const bf16_t*)a.w_uv, (bf16_t*)a.out, a.lse, a.batch, a.h, a.n_blocks, a.d_cb,
         a.plan.n_splits, a.plan.chunk_tokens, a.balanced ? a.chunk_tab : nullptr, a.out_scale,
-        (const bf16_t*)a.gate);
+        (const bf16_t*)a.gate, a.direct ? 1 : 0);
   else
     merge_upproj_mfma_kernel<float><<<grid, 256, lds, a.stream>>>(
         a.part_z, a.part_ml, a.seq_lens, (const bf16_t*)a.w_uv, (float*)a.out, a.lse, a.batch, a.h, a.n_blocks, a.d_cb,
         a.plan.n_splits, a.plan.chunk_tokens, a.balanced ? a.chunk_tab : nullptr, a.out_scale,
-        (const bf16_t*)a.gate);
+        (const bf16_t*)a.gate, a.direct ? 1 : 0);
   return check_launch();
 }
 
