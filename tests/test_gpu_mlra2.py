@@ -159,6 +159,22 @@ def test_two_group_forms_one_round_batches_are_cut_by_length(uniform):
     _check_gla2(wl, lens, seqs=seqs)
 
 
+def test_two_group_forms_many_short_sequences_single_chunk():
+    # several rounds of workgroups, one chunk per sequence: the decode kernel hands normalised bf16 rows
+    # straight to the up-projection (PAIRED and GLA forms), sequences taken longest first
+    rng = np.random.default_rng(79)
+    lens = rng.integers(0, 201, size=520).astype(np.int32)
+    lens[[0, 7]] = [200, 0]
+    seqs = [0, 7, 100, 333, 519]
+    wl = gen.WORKLOADS["M2"].scaled(batch=520, n_min=0, n_max=200, shuffle_pages=True, spare_frac=0.1)
+    info = mlra.mlra_decode_plan_info(wl.batch, wl.h, wl.d_h, 2, wl.n_blocks, wl.d_cb, wl.d_r, wl.page_size, 256,
+                                      torch.bfloat16)
+    assert info["kernel"] == "mfma-paired" and info["chunk_slots"] == 1 and info["target_chunks"] == 0
+    _check(gen.make_decode_inputs(wl, poison=True, seq_lens=lens), seqs=seqs)
+    wl = gen.WORKLOADS["G2"].scaled(batch=520, n_min=0, n_max=200, shuffle_pages=True, spare_frac=0.1)
+    _check_gla2(wl, lens, seqs=seqs)
+
+
 def test_gla2_bf16_split_context_and_full_size_samples():
     wl = gen.WORKLOADS["G2"].scaled(batch=2, n_min=5000, n_max=9000)
     _check_gla2(wl, np.array([9000, 5000], dtype=np.int32))
