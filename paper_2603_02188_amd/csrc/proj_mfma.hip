@@ -157,6 +157,23 @@ __global__ __launch_bounds__(256) void merge_upproj_mfma_kernel(
       if (row0 + 16 * i < R) wreg[i] = *(const bf16x8*)(wsrc + (size_t)(row0 + 16 * i) * ldw);
   };
   fetch_w(0);
+  // (single-chunk rows, see phase 1b: their loads do not depend on phase 1a, so they go out here as well;
+  // what a sequence without tokens leaves in the workspace is discarded below)
+  constexpr int kZPre = 8;
+  bf16x8 zpre[kZPre];
+  const int items_per_row = R / 8;
+  const int n_valid = min(32, batch - m0);
+  const int n_items = n_valid * items_per_row;
+  const bool z_early = direct && n_items <= kZPre * 256;
+  if (z_early) {
+#pragma unroll
+    for (int u = 0; u < kZPre; ++u) {
+      const int item = min(tid + u * 256, n_items - 1);
+      const int sl = item / items_per_row, r0 = (item % items_per_row) * 8;
+      zpre[u] = *(const bf16x8*)((const bf16_t*)part_z +
+                                 (((size_t)(m0 + sl) * nb_total + b0 + r0 / d_cb) * h + head) * d_cb + r0 % d_cb);
+    }
+  }
 
   // ---- phase 1a: every (sequence, block, chunk) partial's (m, l) goes to LDS with one load per thread,
   // then one thread per (sequence, block) reduces them
@@ -201,9 +218,6 @@ __global__ __launch_bounds__(256) void merge_upproj_mfma_kernel(
   // at a time and KK chunks of each per round trip, U * KK = 16 (32 loads in flight): many chunks (small
   // batches) go one item per thread with sixteen chunks in flight, one or two chunks eight items per
   // thread.
-  const int items_per_row = R / 8;
-  const int n_valid = min(32, batch - m0);
-  const int n_items = n_valid * items_per_row;
   // rows of sequences past the batch feed MFMA rows that are never stored; they only have to be finite
   for (int t = n_items + tid; t < 32 * items_per_row; t += 256) {
     bf16x8 zero;
@@ -267,8 +281,22 @@ __global__ __launch_bounds__(256) void merge_upproj_mfma_kernel(
       }
     }
   };
-  if (direct) {
-    // one chunk per sequence and the decode kernel wrote z / l as bf16 rows [.][block][head][d_cb]: copy
+  if (z_early) {
+    // one chunk per sequence and the decode kernel wrote z / l as bf16 rows [.][block][head][d_cb]: the
+    // rows fetched at the top go to LDS
+    bf16x8 zero;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) zero[e] = (__bf16)0.0f;
+#pragma unroll
+    for (int u = 0; u < kZPre; ++u) {
+      const int item = tid + u * 256;
+      if (item < n_items) {
+        const int sl = item / items_per_row, r0 = (item % items_per_row) * 8;
+        *(bf16x8*)(zt + sl * zpitch + r0) = act[sl] > 0 ? zpre[u] : zero;
+      }
+    }
+  } else if (direct) {
+    // (the same for more rows than a thread prefetches)
     const bf16_t* zn = (const bf16_t*)part_z;
     for (int item = tid; item < n_items; item += 256) {
       const int sl = item / items_per_row, r0 = (item % items_per_row) * 8;
@@ -312,12 +340,19 @@ __global__ __launch_bounds__(256) void merge_upproj_mfma_kernel(
       }
       __syncthreads();
       const int rows = min(kWRowsLds, R - row_base);
-      for (int ks = 0; ks < rows / 16; ++ks) {
+      auto k_step = [&](int ks) {
         const bf16x8 a = *(const bf16x8*)(zt + c32 * zpitch + row_base + ks * 16 + g * 8);
         const short4v lo = lds_tr16(wt + ks * 16 * 256 + tr_off[0]);
         const short4v hi = lds_tr16(wt + ks * 16 * 256 + tr_off[1]);
         const bf16x8 bm = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
         acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bm, acc, 0, 0, 0);
+      };
+      if (rows == kWRowsLds) {
+        // straight-line, so that the LDS reads of later steps are issued ahead of the MFMAs of earlier ones
+#pragma unroll
+        for (int ks = 0; ks < kWRowsLds / 16; ++ks) k_step(ks);
+      } else {
+        for (int ks = 0; ks < rows / 16; ++ks) k_step(ks);
       }
     }
   }
