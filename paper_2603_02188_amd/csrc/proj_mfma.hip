@@ -131,7 +131,7 @@ __global__ __launch_bounds__(256) void merge_upproj_mfma_kernel(
     const float* __restrict__ part_z, const float* __restrict__ part_ml, const int32_t* __restrict__ seq_lens,
     const bf16_t* __restrict__ w_uv, TO* __restrict__ out, float* __restrict__ lse, int batch, int h, int nb_total,
     int d_cb, int n_splits, int chunk, const int32_t* __restrict__ chunk_tab, float out_scale,
-    const bf16_t* __restrict__ gate, int direct) {
+    const bf16_t* __restrict__ gate, int direct, int spw) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   // blockIdx.z = head group (Eq. (6)); one group of all blocks is Eq. (5).  h: heads per block; this
   // workgroup's head is h * group + head in out, and its branches are blocks [b0, b0 + n_blocks).
@@ -144,7 +144,9 @@ __global__ __launch_bounds__(256) void merge_upproj_mfma_kernel(
   float* wtab = (float*)(smem + kWRowsLds * 256 + (size_t)32 * zpitch * 2);   // [32][units_per_seq]
   float* ltab = wtab + 32 * units_per_seq;                 // [32][units_per_seq] row sums of the partials
   int* act = (int*)(ltab + 32 * units_per_seq);           // [32] active chunks per sequence
-  const int head = blockIdx.x, m0 = blockIdx.y * 32;
+  // spw: sequences per workgroup (32, or fewer for small batches so that more workgroups share the merge;
+  // the rest of the 32 MFMA rows is zero padding)
+  const int head = blockIdx.x, m0 = blockIdx.y * spw;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, c32 = lane & 31;
   const size_t ldw = (size_t)h * kDh;
 
@@ -162,7 +164,7 @@ __global__ __launch_bounds__(256) void merge_upproj_mfma_kernel(
   constexpr int kZPre = 8;
   bf16x8 zpre[kZPre];
   const int items_per_row = R / 8;
-  const int n_valid = min(32, batch - m0);
+  const int n_valid = min(spw, batch - m0);
   const int n_items = n_valid * items_per_row;
   const bool z_early = direct && n_items <= kZPre * 256;
   if (z_early) {
@@ -180,7 +182,7 @@ __global__ __launch_bounds__(256) void merge_upproj_mfma_kernel(
   for (int t = tid; t < 32 * units_per_seq; t += 256) {
     const int sl = t / units_per_seq, seq = m0 + sl, k = t % n_splits;
     float2 ml = make_float2(kNegBig, 0.f);
-    if (seq < batch) {
+    if (sl < n_valid) {
       const int ch = chunk_tab ? chunk_tab[seq] : chunk;
       const int active = min(n_splits, (seq_lens[seq] + ch - 1) / ch);
       if (k < active)
@@ -195,7 +197,7 @@ __global__ __launch_bounds__(256) void merge_upproj_mfma_kernel(
     float* wrow = wtab + sl * units_per_seq + b * n_splits;
     const float* lrow = ltab + sl * units_per_seq + b * n_splits;
     int active = 0;
-    if (seq < batch) {
+    if (sl < n_valid) {
       const int ch = chunk_tab ? chunk_tab[seq] : chunk;
       active = min(n_splits, (seq_lens[seq] + ch - 1) / ch);
       float m_star = kNegBig;
@@ -359,8 +361,8 @@ __global__ __launch_bounds__(256) void merge_upproj_mfma_kernel(
   const int j = wave * 32 + c32;
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
-    const int s = m0 + (r >> 2) * 8 + g * 4 + (r & 3);
-    if (s < batch) {
+    const int sl = (r >> 2) * 8 + g * 4 + (r & 3), s = m0 + sl;
+    if (sl < n_valid) {
       const size_t o = ((size_t)s * h * gridDim.z + blockIdx.z * h + head) * kDh + j;
       store_f32(out, o, acc[r] * out_scale * (gate ? bf16_to_f32(gate[o]) : 1.f));   // gate: Appendix E
     }
@@ -401,17 +403,20 @@ int launch_merge_upproj_mfma(const DecodeArgs& a) {
       return MLRA_ERR_LAUNCH;
     setup.done(setup_dev);
   }
-  dim3 grid(a.h, (a.batch + 31) / 32, a.groups);
+  // small batches: fewer sequences per workgroup while that brings more workgroups onto idle CUs
+  int spw = 32;
+  while (spw > 8 && (long)a.h * a.groups * ((a.batch + spw - 1) / spw) < device_cu_count()) spw /= 2;
+  dim3 grid(a.h, (a.batch + spw - 1) / spw, a.groups);
   if (a.out_dtype == MLRA_BF16)
     merge_upproj_mfma_kernel<bf16_t><<<grid, 256, lds, a.stream>>>(
         a.part_z, a.part_ml, a.seq_lens, (const bf16_t*)a.w_uv, (bf16_t*)a.out, a.lse, a.batch, a.h, a.n_blocks, a.d_cb,
         a.plan.n_splits, a.plan.chunk_tokens, a.balanced ? a.chunk_tab : nullptr, a.out_scale,
-        (const bf16_t*)a.gate, a.direct ? 1 : 0);
+        (const bf16_t*)a.gate, a.direct ? 1 : 0, spw);
   else
     merge_upproj_mfma_kernel<float><<<grid, 256, lds, a.stream>>>(
         a.part_z, a.part_ml, a.seq_lens, (const bf16_t*)a.w_uv, (float*)a.out, a.lse, a.batch, a.h, a.n_blocks, a.d_cb,
         a.plan.n_splits, a.plan.chunk_tokens, a.balanced ? a.chunk_tab : nullptr, a.out_scale,
-        (const bf16_t*)a.gate, a.direct ? 1 : 0);
+        (const bf16_t*)a.gate, a.direct ? 1 : 0, spw);
   return check_launch();
 }
 
