@@ -19,6 +19,7 @@ namespace {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) short short4v;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 constexpr int kColsWG = 128;     // output columns per workgroup (32 per wave)
 constexpr int kRowsChunk = 128;  // weight rows per LDS stage (32 KiB)
@@ -42,10 +43,27 @@ __device__ __forceinline__ short4v lds_tr16(const void* p) {
 // of weight row r sits at chunk position c ^ swz(r & 7) of its 256-byte LDS row (what the transpose
 // reads want), chunk c of A row r at c ^ (r & 15) (so that the 16 lanes a 128-bit read serves together
 // hit 16 different bank groups).
-template <int MT>   // 32-row tiles of A per workgroup (1..kMaxMTiles)
+// Rotation of the 2-D block (x0, x1) by the angle of (position, frequency index l) held as (cos, sin).
+__device__ __forceinline__ void rotate(float x0, float x1, float c, float s, float& y0, float& y1) {
+  y0 = x0 * c - x1 * s;
+  y1 = x0 * s + x1 * c;
+}
+
+// Epilogue of the query up-projection when K is not cut into slices (nothing is left to sum): segment 0
+// (W^UQ) leaves as q_nope, segment 1 (W^QR) is rotated (RoPE, angles from the table that the
+// down-projection's finishing kernel wrote) and leaves as q_rope, both in the storage dtype.
+struct GemmFinishUp {
+  const float* cs_tab;   // [M][d_r / 2] (cos, sin)
+  bf16_t* q_nope;        // [M][cols of segment 0]
+  bf16_t* q_rope;        // [M][cols of segment 1]
+  int d_r;
+};
+
+template <int MT, bool FINISH_UP>   // MT: 32-row tiles of A per workgroup (1..kMaxMTiles)
 __global__ __launch_bounds__(256) void skinny_gemm_mfma_kernel(const bf16_t* __restrict__ A, int lda, int M,
                                                                GemmSegments segs, int K, int rows_per_slice,
-                                                               float* __restrict__ out_part, int ld_out) {
+                                                               float* __restrict__ out_part, int ld_out,
+                                                               GemmFinishUp fin) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   constexpr int kStages = gemm_stages(MT);
   constexpr int kStageB = gemm_stage_bytes(MT);
@@ -162,7 +180,44 @@ __global__ __launch_bounds__(256) void skinny_gemm_mfma_kernel(const bf16_t* __r
   }
   mfma_tile::wait_vmcnt<0>();   // the loads past the slice target this workgroup's LDS: let them land
   const int j = wave * 32 + c32;
-  if (j < n_valid) {
+  if (FINISH_UP) {
+    // The tile's sums go through LDS (the stages are free now) so that a thread finishes eight neighbouring
+    // columns of a row: four RoPE 2-D blocks [2l, 2l+1] with their angles side by side in the table, one
+    // 16-byte store.
+    constexpr int kPitch = kColsWG + 4;          // floats per staged row (+4: rows start on different banks)
+    float* tile = (float*)smem;
+    __syncthreads();                             // every wave is past its last read of the stages
+#pragma unroll
+    for (int t = 0; t < MT; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        tile[(t * 32 + (r >> 2) * 8 + g * 4 + (r & 3)) * kPitch + j] = acc[t][r];
+    __syncthreads();
+    bf16_t* dst = seg == 0 ? fin.q_nope : fin.q_rope;
+    for (int id = tid; id < 32 * MT * (kColsWG / 8); id += 256) {
+      const int row = id / (kColsWG / 8), pc = id % (kColsWG / 8), m = m_base + row, col = n0 + pc * 8;
+      if (m >= M || pc * 8 >= n_valid) continue;
+      const f32x4 lo = *(const f32x4*)(tile + row * kPitch + pc * 8), hi = *(const f32x4*)(tile + row * kPitch + pc * 8 + 4);
+      float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+      if (seg != 0) {
+        const int l0 = (col % fin.d_r) >> 1;     // d_r is a multiple of 8: the four blocks share the head
+        const float* cs = fin.cs_tab + ((size_t)m * (fin.d_r / 2) + l0) * 2;
+        const f32x4 c01 = *(const f32x4*)cs, c23 = *(const f32x4*)(cs + 4);
+        const float cv[4] = {c01[0], c01[2], c23[0], c23[2]}, sv[4] = {c01[1], c01[3], c23[1], c23[3]};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          float y0, y1;
+          rotate(v[2 * q], v[2 * q + 1], cv[q], sv[q], y0, y1);
+          v[2 * q] = y0;
+          v[2 * q + 1] = y1;
+        }
+      }
+      bf16x8 packed;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) packed[e] = (__bf16)v[e];
+      *(bf16x8*)(dst + (size_t)m * ldw + col) = packed;
+    }
+  } else if (j < n_valid) {
 #pragma unroll
     for (int t = 0; t < MT; ++t) {
 #pragma unroll
@@ -200,11 +255,6 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
   return s;
 }
 
-// Rotation of the 2-D block (x0, x1) by the angle of (position, frequency index l) held as (cos, sin).
-__device__ __forceinline__ void rotate(float x0, float x1, float c, float s, float& y0, float& y1) {
-  y0 = x0 * c - x1 * s;
-  y1 = x0 * s + x1 * c;
-}
 
 // Step 2.  One workgroup per sequence.  Columns of the summed down-projection: [0, d_cq) C^Q,
 // [d_cq, d_cq + d_c) C^KV, then d_r RoPE-key channels.
@@ -328,20 +378,26 @@ bool gemm_mfma_ok(int dtype, int M, int K, int lda, const GemmSegments& segs) {
   return true;
 }
 
+// fin != nullptr (one K slice, MFMA path): the up-projection epilogue instead of partial sums
 int launch_gemm(int dtype, const void* A, int lda, int M, const GemmSegments& segs, int K, int n_slices,
-                int rows_per_slice, float* part, int ld_out, hipStream_t stream) {
+                int rows_per_slice, float* part, int ld_out, hipStream_t stream, const GemmFinishUp* fin = nullptr) {
   if (gemm_mfma_ok(dtype, M, K, lda, segs)) {
     static PerDeviceSetup setup;
     int setup_dev = -1;
     if (setup.needed(&setup_dev)) {
-      if (hipFuncSetAttribute((const void*)skinny_gemm_mfma_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                              gemm_stages(1) * gemm_stage_bytes(1)) != hipSuccess ||
-          hipFuncSetAttribute((const void*)skinny_gemm_mfma_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                              gemm_stages(2) * gemm_stage_bytes(2)) != hipSuccess ||
-          hipFuncSetAttribute((const void*)skinny_gemm_mfma_kernel<3>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                              gemm_stages(3) * gemm_stage_bytes(3)) != hipSuccess ||
-          hipFuncSetAttribute((const void*)skinny_gemm_mfma_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                              gemm_stages(4) * gemm_stage_bytes(4)) != hipSuccess)
+      bool ok = true;
+#define MLRA_GEMM_LDS(MT)                                                                                            \
+  ok = ok &&                                                                                                         \
+       hipFuncSetAttribute((const void*)skinny_gemm_mfma_kernel<MT, false>, hipFuncAttributeMaxDynamicSharedMemorySize, \
+                           gemm_stages(MT) * gemm_stage_bytes(MT)) == hipSuccess &&                                   \
+       hipFuncSetAttribute((const void*)skinny_gemm_mfma_kernel<MT, true>, hipFuncAttributeMaxDynamicSharedMemorySize,  \
+                           gemm_stages(MT) * gemm_stage_bytes(MT)) == hipSuccess
+      MLRA_GEMM_LDS(1);
+      MLRA_GEMM_LDS(2);
+      MLRA_GEMM_LDS(3);
+      MLRA_GEMM_LDS(4);
+#undef MLRA_GEMM_LDS
+      if (!ok)
         return MLRA_ERR_LAUNCH;
       setup.done(setup_dev);
     }
@@ -351,10 +407,18 @@ int launch_gemm(int dtype, const void* A, int lda, int M, const GemmSegments& se
     dim3 grid(tiles, n_slices, (M + 32 * mt - 1) / (32 * mt));
     const size_t lds = (size_t)gemm_stages(mt) * gemm_stage_bytes(mt);
     const bf16_t* a = (const bf16_t*)A;
-    if (mt == 1) skinny_gemm_mfma_kernel<1><<<grid, 256, lds, stream>>>(a, lda, M, segs, K, rows_per_slice, part, ld_out);
-    else if (mt == 2) skinny_gemm_mfma_kernel<2><<<grid, 256, lds, stream>>>(a, lda, M, segs, K, rows_per_slice, part, ld_out);
-    else if (mt == 3) skinny_gemm_mfma_kernel<3><<<grid, 256, lds, stream>>>(a, lda, M, segs, K, rows_per_slice, part, ld_out);
-    else skinny_gemm_mfma_kernel<4><<<grid, 256, lds, stream>>>(a, lda, M, segs, K, rows_per_slice, part, ld_out);
+    GemmFinishUp f = {};
+    if (fin) f = *fin;
+#define MLRA_GEMM_LAUNCH(MT)                                                                                          \
+  if (fin)                                                                                                            \
+    skinny_gemm_mfma_kernel<MT, true><<<grid, 256, lds, stream>>>(a, lda, M, segs, K, rows_per_slice, part, ld_out, f); \
+  else                                                                                                                \
+    skinny_gemm_mfma_kernel<MT, false><<<grid, 256, lds, stream>>>(a, lda, M, segs, K, rows_per_slice, part, ld_out, f)
+    if (mt == 1) { MLRA_GEMM_LAUNCH(1); }
+    else if (mt == 2) { MLRA_GEMM_LAUNCH(2); }
+    else if (mt == 3) { MLRA_GEMM_LAUNCH(3); }
+    else { MLRA_GEMM_LAUNCH(4); }
+#undef MLRA_GEMM_LAUNCH
   } else {
     dim3 grid((ld_out + 255) / 256, M);
     if (dtype == MLRA_BF16)
@@ -438,6 +502,11 @@ int launch_pre_attention(const mlra_cache* c, const mlra_pre_weights* w, int bat
   s2.w[0] = w->w_uq; s2.cols[0] = w->h * w->d_h;  s2.out_col[0] = 0;
   s2.w[1] = w->w_qr; s2.cols[1] = w->h * c->d_r;  s2.out_col[1] = w->h * w->d_h;
   s2.w[2] = nullptr; s2.cols[2] = 0;              s2.out_col[2] = 0;
+  if (p.mfma2 && p.slices2 == 1 && c->d_r % 8 == 0) {
+    // one K slice: the GEMM's own epilogue writes q_nope and the rotated q_rope
+    const GemmFinishUp fin = {cs_tab, (bf16_t*)q_nope, (bf16_t*)q_rope, c->d_r};
+    return launch_gemm(w->dtype, c_q, w->d_cq, batch, s2, w->d_cq, 1, p.rows2, part2, p.n2, stream, &fin);
+  }
   st = launch_gemm(w->dtype, c_q, w->d_cq, batch, s2, w->d_cq, p.slices2, p.rows2, part2, p.n2, stream);
   if (st != MLRA_OK) return st;
 

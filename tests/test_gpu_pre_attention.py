@@ -96,6 +96,16 @@ def test_pre_attention_bf16_row_counts_off_the_chunk():
     _run_and_check(wl, d=1024 + 16, d_cq=384 + 8, lens=lens)
 
 
+@pytest.mark.parametrize("batch", [3, 100, 130])
+def test_pre_attention_bf16_single_slice_up_projection(batch):
+    # enough column tiles that the up-projection keeps K in one slice: its GEMM writes q_nope and the rotated
+    # q_rope itself (1, 4 and 4 + 1 accumulator tiles; 121 heads leave a ragged last column tile)
+    wl = gen.WORKLOADS["C3"].scaled(name="pre-fused", batch=batch, h=121, n_min=1, n_max=3000)
+    rng = np.random.default_rng(11 + batch)
+    lens = rng.integers(1, 3001, size=batch).astype(np.int32)
+    _run_and_check(wl, d=256, d_cq=256, lens=lens)
+
+
 def test_pre_attention_bf16_paper_shape_unit_gains():
     # hidden size 7168 and 128 heads as in the paper's decode benchmark (Section 4.5); d_c' = 1536
     wl = gen.WORKLOADS["C3"].scaled(name="pre-paper-shape", batch=8, n_min=1, n_max=131072)
