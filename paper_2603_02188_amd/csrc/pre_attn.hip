@@ -272,27 +272,29 @@ __global__ __launch_bounds__(256) void pre_finish_down_kernel(
   const int n1 = d_cq + d_c + d_r;
   const int pos = positions[s];
   float ss_q = 0.f, ss_kv = 0.f;
-  // eight columns per thread at a time, so that eight loads per slice are in flight (one column at a
-  // time would pay one memory round trip per slice and column)
-  for (int j0 = 0; j0 < n1; j0 += 8 * 256) {
-    float v[8];
+  // kU columns per thread and kKK slices at a time, all loads of such a round in flight together: the
+  // kernel is a chain of memory round trips (one workgroup per sequence), so it wants as few rounds as
+  // possible (the benchmark shape, 2112 columns in 14 slices, takes one)
+  constexpr int kU = 9, kKK = 16;
+  for (int j0 = 0; j0 < n1; j0 += kU * 256) {
+    float v[kU];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) v[u] = 0.f;
-    for (int k = 0; k < n_slices; k += 4) {
-      float t[4][8];
+    for (int u = 0; u < kU; ++u) v[u] = 0.f;
+    for (int k = 0; k < n_slices; k += kKK) {
+      float t[kKK][kU];
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
+      for (int kk = 0; kk < kKK; ++kk) {
         const float* src = part + ((size_t)min(k + kk, n_slices - 1) * batch + s) * n1;
 #pragma unroll
-        for (int u = 0; u < 8; ++u) t[kk][u] = src[min(j0 + u * 256 + tid, n1 - 1)];   // unconditional: all in flight
+        for (int u = 0; u < kU; ++u) t[kk][u] = src[min(j0 + u * 256 + tid, n1 - 1)];   // unconditional: all in flight
       }
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk)
+      for (int kk = 0; kk < kKK; ++kk)
 #pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] += (k + kk < n_slices) ? t[kk][u] : 0.f;   // slices summed in order
+        for (int u = 0; u < kU; ++u) v[u] += (k + kk < n_slices) ? t[kk][u] : 0.f;   // slices summed in order
     }
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
+    for (int u = 0; u < kU; ++u) {
       const int j = j0 + u * 256 + tid;
       if (j < n1) {
         row[j] = v[u];
