@@ -111,14 +111,15 @@ __global__ __launch_bounds__(256) void absorb_q_mfma_kernel(const bf16_t* __rest
 }
 
 // ------------------------------------------------------------------------------------------------
-// merge + up-projection.  One workgroup per (head, tile of 32 sequences).
+// merge + up-projection.  One workgroup per (head, tile of up to 32 sequences).
 //   phase 0: the loads of the first 512 rows of this head's W^UV slice are issued into registers, so
-//            that they are in flight while phase 1 runs;
+//            that they are in flight while phase 1 runs (and, when every sequence has a single chunk, the
+//            loads of the rows that the decode kernel already normalised and rounded: see `direct`);
 //   phase 1a: one thread per (sequence, block) turns the chunk partials' (m, l) into normalised merge
 //            weights w_k = 2^(m_k - m*) / L in LDS and writes the log-sum-exp;
 //   phase 1b: merged z = sum_k w_k z_k of the 32 sequences for all R = n_blocks*d_cb latent channels,
 //            rounded to bf16, is built in LDS (row = sequence), four independent items per thread at a
-//            time so that their loads overlap;
+//            time so that their loads overlap (`direct`: the rows arrive merged, they are only copied);
 //   phase 2: out[seq][j] = sum_r z[seq][r] W^UV[r][head*128 + j]; W^UV goes through LDS 256 rows at a
 //            time and reaches the MFMA B operand through transpose reads; wave w owns output columns
 //            [32 w, 32 w + 32).
