@@ -276,8 +276,8 @@ def main():
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / a.steps
 
-    # the same loop again with HIP events around the decode kernels (recorded inside the library on
-    # the launch stream), for the roofline of the dominant kernel
+    # the same loop again with a start and a stop event on each decode kernel launch (inside the library,
+    # on the launch stream: the kernel's own execution interval), for the roofline of the dominant kernel
     mlra.mlra_kernel_timing_begin(a.steps)
     for i in range(a.steps):
         step(a.warmup + a.steps + i)

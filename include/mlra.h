@@ -220,11 +220,13 @@ MLRA_API int gqa_decode_attn(const void* k_pool, const void* v_pool, const int32
                     int32_t out_dtype, void* workspace, size_t workspace_bytes, void* stream);
 
 /* Measurement aid (host-side state, not thread-safe).  Between begin and end, every mlra_decode_attn /
- * mla_decode_attn call records HIP events on its stream before its main decode kernel, between that
- * kernel and the merge + up-projection epilogue kernel, and after the epilogue, for at most max_calls
- * calls.  mlra_kernel_timing_end waits for those events, stores the average duration in milliseconds
- * of the two kernels and the number of calls measured into the given HOST pointers, and releases the
- * events.  begin allocates host event objects; neither call belongs in a latency-critical loop. */
+ * mla_decode_attn call records, for at most max_calls calls, the start and the end of its main decode
+ * kernel and of its merge + up-projection epilogue kernel into HIP events: the kernel's own execution
+ * interval on the bf16 fast paths (what a kernel trace reports as its duration; planning kernels that
+ * precede the decode kernel are not part of it), stream markers around the kernel on the generic paths.
+ * mlra_kernel_timing_end waits for those events, stores the average duration in milliseconds of the two
+ * kernels and the number of calls measured into the given HOST pointers, and releases the events.
+ * begin allocates host event objects; neither call belongs in a latency-critical loop. */
 MLRA_API int mlra_kernel_timing_begin(int32_t max_calls);
 MLRA_API int mlra_kernel_timing_end(double* main_kernel_ms, double* epilogue_kernel_ms, int32_t* calls);
 

@@ -887,7 +887,7 @@ int launch_decode_gla(const DecodeArgs& a) {
   const long long n_wg = (long long)a.plan.n_splits * a.n_blocks * ((a.h + 63) / 64) * a.batch;
   if (n_wg <= 0 || n_wg > 0x7fffffffLL) return MLRA_ERR_SHAPE;
   if (!a.balanced && n_wg > device_cu_count() && launch_seq_order(a) == MLRA_OK) p.seq_order = a.seq_order;
-  decode_mfma_kernel<kStagesGla, 2><<<dim3((unsigned)n_wg), 256, lds, a.stream>>>(p);
+  MLRA_LAUNCH_TIMED(a.t_main, (decode_mfma_kernel<kStagesGla, 2>), dim3((unsigned)n_wg), dim3(256), lds, a.stream, p);
   return check_launch();
 }
 
@@ -932,8 +932,10 @@ int launch_decode_mfma(const DecodeArgs& a) {
   p.chunk_tab = a.balanced ? a.chunk_tab : nullptr;
   p.unit_tab = a.balanced ? a.unit_tab : nullptr;
   if (!a.balanced && n_wg > device_cu_count() && launch_seq_order(a) == MLRA_OK) p.seq_order = a.seq_order;
-  if (paired) decode_mfma_kernel<kStagesPaired, 1><<<dim3((unsigned)n_wg), 256, lds, a.stream>>>(p);
-  else decode_mfma_kernel<kStages, 0><<<dim3((unsigned)n_wg), 256, lds, a.stream>>>(p);
+  if (paired)
+    MLRA_LAUNCH_TIMED(a.t_main, (decode_mfma_kernel<kStagesPaired, 1>), dim3((unsigned)n_wg), dim3(256), lds, a.stream, p);
+  else
+    MLRA_LAUNCH_TIMED(a.t_main, (decode_mfma_kernel<kStages, 0>), dim3((unsigned)n_wg), dim3(256), lds, a.stream, p);
   return check_launch();
 }
 

@@ -399,7 +399,7 @@ int launch_mla_mfma(const DecodeArgs& a) {
   const long long n_wg = (long long)a.plan.n_splits * n_hg * a.batch;
   if (n_wg <= 0 || n_wg > 0x7fffffffLL) return MLRA_ERR_SHAPE;
   if (!a.balanced && n_wg > device_cu_count() && launch_seq_order(a) == MLRA_OK) p.seq_order = a.seq_order;
-  mla_mfma_kernel<<<dim3((unsigned)n_wg), 256, kMLds, a.stream>>>(p);
+  MLRA_LAUNCH_TIMED(a.t_main, mla_mfma_kernel, dim3((unsigned)n_wg), dim3(256), kMLds, a.stream, p);
   return check_launch();
 }
 

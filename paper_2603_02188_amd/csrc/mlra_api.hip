@@ -13,8 +13,15 @@ namespace mlra {
 static std::vector<hipEvent_t> g_events;
 static int g_timing_cap = 0, g_timing_calls = 0;
 
-static void timing_mark(int which, hipStream_t stream) {
-  if (g_timing_calls < g_timing_cap) (void)hipEventRecord(g_events[3 * g_timing_calls + which], stream);
+// four events per timed call: start / stop of the decode kernel, start / stop of the merge + up-projection
+static bool timing_on() { return g_timing_calls < g_timing_cap; }
+static KernelTimer timing_pair(int which) {
+  KernelTimer t;
+  if (timing_on()) {
+    t.start = g_events[4 * g_timing_calls + 2 * which];
+    t.stop = g_events[4 * g_timing_calls + 2 * which + 1];
+  }
+  return t;
 }
 
 int device_cu_count() {
@@ -150,7 +157,8 @@ static int decode_common(const mlra_cache* c, int batch, int h, int groups, int 
   a.gate = gate;
   a.dtype = c->dtype;
   a.stream = (hipStream_t)stream;
-  timing_mark(0, a.stream);
+  a.t_main = timing_pair(0);
+  a.t_epi = timing_pair(1);
   // chunk lengths that follow the sequence lengths need both MFMA kernels (they read the table)
   if (a.plan.target_chunks > 0 && merge_upproj_mfma_supported(a) &&
       (decode_mfma_supported(a) || decode_gla_supported(a) || mla_mfma_supported(a)))
@@ -159,15 +167,20 @@ static int decode_common(const mlra_cache* c, int batch, int h, int groups, int 
   // rows instead of fp32 partials
   a.direct = a.plan.n_splits == 1 && !a.balanced && merge_upproj_mfma_supported(a) &&
              (decode_mfma_supported(a) || decode_gla_supported(a));
+  // the MFMA launchers record their kernel's own start and end; the generic kernels are bracketed by stream markers
+  const bool main_fast = decode_mfma_supported(a) || decode_gla_supported(a) || mla_mfma_supported(a);
+  const bool epi_fast = merge_upproj_mfma_supported(a);
+  if (a.t_main.on() && !main_fast) (void)hipEventRecord(a.t_main.start, a.stream);
   int st = decode_mfma_supported(a) ? launch_decode_mfma(a)
            : decode_gla_supported(a) ? launch_decode_gla(a)
            : mla_mfma_supported(a)  ? launch_mla_mfma(a)
                                     : launch_decode_generic(a);
   if (st != MLRA_OK) return st;
-  timing_mark(1, a.stream);
-  st = merge_upproj_mfma_supported(a) ? launch_merge_upproj_mfma(a) : launch_merge_upproj_generic(a);
-  timing_mark(2, a.stream);
-  if (g_timing_calls < g_timing_cap) ++g_timing_calls;
+  if (a.t_main.on() && !main_fast) (void)hipEventRecord(a.t_main.stop, a.stream);
+  if (a.t_epi.on() && !epi_fast) (void)hipEventRecord(a.t_epi.start, a.stream);
+  st = epi_fast ? launch_merge_upproj_mfma(a) : launch_merge_upproj_generic(a);
+  if (a.t_epi.on() && !epi_fast) (void)hipEventRecord(a.t_epi.stop, a.stream);
+  if (st == MLRA_OK && timing_on()) ++g_timing_calls;
   return st;
 }
 
@@ -376,7 +389,7 @@ int mlra_decode_plan_info(int32_t batch, int32_t h, int32_t d_h, int32_t groups,
 int mlra_kernel_timing_begin(int32_t max_calls) {
   if (max_calls <= 0 || max_calls > 100000) return MLRA_ERR_SHAPE;
   for (hipEvent_t e : g_events) (void)hipEventDestroy(e);
-  g_events.assign((size_t)3 * max_calls, nullptr);
+  g_events.assign((size_t)4 * max_calls, nullptr);
   for (hipEvent_t& e : g_events)
     if (hipEventCreate(&e) != hipSuccess) return MLRA_ERR_LAUNCH;
   g_timing_calls = 0;
@@ -390,9 +403,9 @@ int mlra_kernel_timing_end(double* main_kernel_ms, double* epilogue_kernel_ms, i
   int st = MLRA_OK;
   for (int i = 0; i < g_timing_calls; ++i) {
     float ms0 = 0.f, ms1 = 0.f;
-    if (hipEventSynchronize(g_events[3 * i + 2]) != hipSuccess ||
-        hipEventElapsedTime(&ms0, g_events[3 * i], g_events[3 * i + 1]) != hipSuccess ||
-        hipEventElapsedTime(&ms1, g_events[3 * i + 1], g_events[3 * i + 2]) != hipSuccess) {
+    if (hipEventSynchronize(g_events[4 * i + 3]) != hipSuccess ||
+        hipEventElapsedTime(&ms0, g_events[4 * i], g_events[4 * i + 1]) != hipSuccess ||
+        hipEventElapsedTime(&ms1, g_events[4 * i + 2], g_events[4 * i + 3]) != hipSuccess) {
       st = MLRA_ERR_LAUNCH;
       break;
     }

@@ -1,6 +1,7 @@
 // Internal helpers shared by the HIP sources of libmlra (not part of the public ABI).
 #pragma once
 
+#include <hip/hip_ext.h>
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -60,6 +61,22 @@ SplitPlan plan_splits(int batch, int n_blocks, int max_seq_len);
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // ---- launchers implemented in the kernel sources -----------------------------------------------
+// Optional timing of one kernel.  With both events set, a launch through MLRA_LAUNCH_TIMED records the
+// kernel's own start and end into them (the interval a kernel trace reports as its duration), not stream
+// markers around it, which would add the marker packets' own latency to short kernels.
+struct KernelTimer {
+  hipEvent_t start = nullptr, stop = nullptr;
+  bool on() const { return start && stop; }
+};
+#define MLRA_LAUNCH_TIMED(timer, kernel, grid, block, lds, stream, ...)                                       \
+  do {                                                                                                        \
+    if ((timer).on())                                                                                         \
+      hipExtLaunchKernelGGL(HIP_KERNEL_NAME(kernel), grid, block, lds, stream, (timer).start, (timer).stop, 0, \
+                            __VA_ARGS__);                                                                     \
+    else                                                                                                      \
+      hipLaunchKernelGGL(HIP_KERNEL_NAME(kernel), grid, block, lds, stream, __VA_ARGS__);                     \
+  } while (0)
+
 struct DecodeArgs {
   const void* latent;
   const void* rope;
@@ -87,6 +104,7 @@ struct DecodeArgs {
   SplitPlan plan;
   int dtype;
   hipStream_t stream;
+  KernelTimer t_main, t_epi;   // set by mlra_kernel_timing_begin: the decode kernel and the merge / up-projection
 };
 
 int launch_append_kv(const mlra_cache* c, int batch, const void* c_kv_new, const void* k_rope_new, int src_dtype,

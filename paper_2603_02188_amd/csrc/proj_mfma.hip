@@ -408,16 +408,18 @@ int launch_merge_upproj_mfma(const DecodeArgs& a) {
   int spw = 32;
   while (spw > 8 && (long)a.h * a.groups * ((a.batch + spw - 1) / spw) < device_cu_count()) spw /= 2;
   dim3 grid(a.h, (a.batch + spw - 1) / spw, a.groups);
+  const int32_t* const chunk_tab = a.balanced ? a.chunk_tab : nullptr;
+  const int direct = a.direct ? 1 : 0;
   if (a.out_dtype == MLRA_BF16)
-    merge_upproj_mfma_kernel<bf16_t><<<grid, 256, lds, a.stream>>>(
-        a.part_z, a.part_ml, a.seq_lens, (const bf16_t*)a.w_uv, (bf16_t*)a.out, a.lse, a.batch, a.h, a.n_blocks, a.d_cb,
-        a.plan.n_splits, a.plan.chunk_tokens, a.balanced ? a.chunk_tab : nullptr, a.out_scale,
-        (const bf16_t*)a.gate, a.direct ? 1 : 0, spw);
+    MLRA_LAUNCH_TIMED(a.t_epi, merge_upproj_mfma_kernel<bf16_t>, grid, dim3(256), lds, a.stream, (const float*)a.part_z,
+                      (const float*)a.part_ml, a.seq_lens, (const bf16_t*)a.w_uv, (bf16_t*)a.out, a.lse, a.batch, a.h,
+                      a.n_blocks, a.d_cb, a.plan.n_splits, a.plan.chunk_tokens, chunk_tab, a.out_scale,
+                      (const bf16_t*)a.gate, direct, spw);
   else
-    merge_upproj_mfma_kernel<float><<<grid, 256, lds, a.stream>>>(
-        a.part_z, a.part_ml, a.seq_lens, (const bf16_t*)a.w_uv, (float*)a.out, a.lse, a.batch, a.h, a.n_blocks, a.d_cb,
-        a.plan.n_splits, a.plan.chunk_tokens, a.balanced ? a.chunk_tab : nullptr, a.out_scale,
-        (const bf16_t*)a.gate, a.direct ? 1 : 0, spw);
+    MLRA_LAUNCH_TIMED(a.t_epi, merge_upproj_mfma_kernel<float>, grid, dim3(256), lds, a.stream, (const float*)a.part_z,
+                      (const float*)a.part_ml, a.seq_lens, (const bf16_t*)a.w_uv, (float*)a.out, a.lse, a.batch, a.h,
+                      a.n_blocks, a.d_cb, a.plan.n_splits, a.plan.chunk_tokens, chunk_tab, a.out_scale,
+                      (const bf16_t*)a.gate, direct, spw);
   return check_launch();
 }
 
