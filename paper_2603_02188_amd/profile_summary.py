@@ -1,6 +1,9 @@
 """Condense rocprofv3 CSV output of `bench.py` into the short text summaries kept under profiles/.
 
     python3 -m paper_2603_02188_amd.profile_summary trace   <dir>            # --kernel-trace --stats run
+    python3 -m paper_2603_02188_amd.profile_summary trace   <dir> <kernel> <first> <count>
+                      # ... and the mean over launches first .. first+count-1 (in start order, from 0) of the
+                      # kernels whose name contains <kernel>: the launches that bench.py's own events timed
     python3 -m paper_2603_02188_amd.profile_summary counters <fetch_dir> <write_dir> [<sq_dir>]
 
 `<dir>` is the `-d` directory given to rocprofv3 (searched recursively for the CSV files).
@@ -42,6 +45,17 @@ def trace_summary(root):
         out.append(f"| {_short(r['Name'])} | {r['Calls']} | {float(r['AverageNs']) / 1e3:.1f} | "
                    f"{float(r['MinNs']) / 1e3:.1f} | {float(r['MaxNs']) / 1e3:.1f} | {r['Percentage']} |")
     return "\n".join(out)
+
+
+def window_mean(root, kernel, first, count):
+    rows = [r for r in csv.DictReader(open(_find(root, "_kernel_trace.csv"))) if kernel in r["Kernel_Name"]]
+    rows.sort(key=lambda r: int(r["Start_Timestamp"]))
+    sel = rows[first:first + count]
+    if len(sel) < count:
+        raise SystemExit(f"only {len(rows)} launches of {kernel}")
+    us = [(int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e3 for r in sel]
+    return (f"launches {first}..{first + count - 1} of {len(rows)} of {_short(sel[0]['Kernel_Name'])}: "
+            f"mean {sum(us) / len(us):.1f} us (min {min(us):.1f}, max {max(us):.1f})")
 
 
 def _per_kernel(root):
@@ -92,6 +106,9 @@ def counters_summary(fetch_root, write_root, sq_root=None):
 def main(argv):
     if len(argv) >= 2 and argv[0] == "trace":
         print(trace_summary(argv[1]))
+        if len(argv) >= 5:
+            print()
+            print(window_mean(argv[1], argv[2], int(argv[3]), int(argv[4])))
     elif len(argv) >= 3 and argv[0] == "counters":
         print(counters_summary(argv[1], argv[2], argv[3] if len(argv) > 3 else None)[0])
     else:
