@@ -24,8 +24,9 @@ sys.path.insert(0, ROOT)
 def _args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=100,
+                    help="untimed steps first (the first 30-50 steps after start-up run up to 15 %% slower)")
     ap.add_argument("--workload", default="C3", choices=["C2", "C3", "C4", "C5", "M2", "G2"])
     ap.add_argument("--copies", type=int, default=0, help="cache copies to rotate over (0 = enough for ~3 GB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")

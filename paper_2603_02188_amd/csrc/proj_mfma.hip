@@ -42,71 +42,108 @@ __device__ __forceinline__ short4v lds_tr16(const void* p) {
 
 // ------------------------------------------------------------------------------------------------
 // absorb_q.  One workgroup per (head, block, 64 sequences); wave w produces the 32-channel tile ct0 + w of
-// each pass over four tiles.  S^T-free formulation: out[seq][c] = sum_p q[seq][p] W[c][p], so the A operand (rows =
-// sequences) and the B operand (columns = channels) are both contiguous 16-byte global loads.  All query
-// loads of the 64 sequences are issued before the first MFMA (one round trip instead of one per k-step),
-// and the results pass through LDS so that they leave as whole 16-byte pieces of the q_abs rows instead
-// of single elements.  Larger batches put their 64-sequence tiles on the grid (the weights of a head are
-// then read once from HBM and again from L2).
+// each pass over four tiles: out[seq][c] = sum_p q[seq][p] W[c][p].  An MFMA operand wants sixteen bytes of
+// each of 32 rows per lane group, and rows of q (one per sequence) and of W (one per channel) lie 32 KiB
+// apart: read in that shape, every load instruction touches 64 cache lines for 1 KiB.  So both are fetched
+// as whole 256-byte rows (sixteen lanes a row), laid into LDS with a chunk swizzle, and the operands are
+// read from there; the 64 query rows are fetched once per workgroup instead of once per wave.  The results
+// pass through LDS as well, so that they leave as whole 16-byte pieces of the q_abs rows.  Larger batches
+// put their 64-sequence tiles on the grid (the weights of a head are then read once from HBM and again
+// from L2).
 // ------------------------------------------------------------------------------------------------
 constexpr int kAbsPitch = 128 * 2 + 16;   // bytes per staged sequence row (128 channels; +16: rows on different banks)
+constexpr int kAbsQ = 64 * 256;           // LDS: the 64 query rows of the head ...
+constexpr int kAbsW = 4 * 32 * 256;       // ... and 32 weight rows per wave (the result staging reuses this part)
+static_assert(64 * kAbsPitch <= kAbsW, "the staged results must fit the weight rows' space");
 
 __global__ __launch_bounds__(256) void absorb_q_mfma_kernel(const bf16_t* __restrict__ q_nope,
                                                             const bf16_t* __restrict__ w_uk,
                                                             bf16_t* __restrict__ q_abs, int batch, int h,
                                                             int n_blocks, int groups, int d_cb) {
   // h: heads per block; q_nope holds groups * h heads and block b reads those of its group (Eq. (6))
-  __shared__ __attribute__((aligned(16))) unsigned char stage[64 * kAbsPitch];
+  __shared__ __attribute__((aligned(16))) unsigned char smem[kAbsQ + kAbsW];
+  unsigned char* const qs = smem;
+  unsigned char* const ws = smem + kAbsQ;
+  unsigned char* const stage = ws;
   const int head = blockIdx.x, b = blockIdx.y;
   const int q_head = (b / (n_blocks / groups)) * h + head, q_heads = h * groups;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, c32 = lane & 31;
   const size_t ldw = (size_t)h * kDh;
+  const int m0 = blockIdx.z * 64;      // 64 sequences per workgroup
+  // rows are stored with 16-byte chunk c at position c ^ (row % 16): the sixteen lanes that a 128-bit LDS
+  // read serves together (rows 0-3, 12-15, 20-27 of one chunk column, and so on) then hit sixteen positions
+  const int ld_chunk = tid & 15, ld_row = tid >> 4;          // loads: thread = (row % 16 of its pass, chunk)
+  bf16x8 qld[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int seq = min(m0 + 16 * i + ld_row, batch - 1);
+    qld[i] = *(const bf16x8*)(q_nope + ((size_t)seq * q_heads + q_head) * kDh + ld_chunk * 8);
+  }
+  bf16x8 areg[2][8];
   for (int ct0 = 0; ct0 * 32 < d_cb; ct0 += 4) {
     const int ct = ct0 + wave;
     const bool live = ct * 32 < d_cb;                       // (uniform per wave)
-    const int c = min(ct * 32 + c32, d_cb - 1);
-    const bf16_t* wrow = w_uk + ((size_t)b * d_cb + c) * ldw + (size_t)head * kDh + g * 8;
+    // this wave's 32 weight rows (a wave past the last channel tile repeats the last row and stores nothing)
+    bf16x8 wld[8];
+    {
+      const int wl_chunk = lane & 15, wl_row = lane >> 4;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int c = min(ct * 32 + 4 * i + wl_row, d_cb - 1);
+        wld[i] = *(const bf16x8*)(w_uk + ((size_t)b * d_cb + c) * ldw + (size_t)head * kDh + wl_chunk * 8);
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int r = 4 * i + wl_row;
+        *(bf16x8*)(ws + wave * (32 * 256) + r * 256 + ((wl_chunk ^ (r & 15)) << 4)) = wld[i];
+      }
+    }
+    if (ct0 == 0) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int r = 16 * i + ld_row;
+        *(bf16x8*)(qs + r * 256 + ((ld_chunk ^ (r & 15)) << 4)) = qld[i];
+      }
+    }
+    __syncthreads();
     bf16x8 breg[8];
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) breg[ks] = *(const bf16x8*)(wrow + ks * 16);
-    const int pass_ch = min(128, d_cb - ct0 * 32);          // channels this pass produces
-    {
-      const int m0 = blockIdx.z * 64;      // 64 sequences per workgroup
-      bf16x8 areg[2][8];
+    for (int ks = 0; ks < 8; ++ks)
+      breg[ks] = *(const bf16x8*)(ws + wave * (32 * 256) + c32 * 256 + (((2 * ks + g) ^ (c32 & 15)) << 4));
+    if (ct0 == 0) {
 #pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        const int seq = min(m0 + 32 * t + c32, batch - 1);
-        const bf16_t* qrow = q_nope + ((size_t)seq * q_heads + q_head) * kDh + g * 8;
+      for (int t = 0; t < 2; ++t)
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) areg[t][ks] = *(const bf16x8*)(qrow + ks * 16);
-      }
-      __builtin_amdgcn_sched_barrier(0);   // every load above is in flight before the first MFMA waits
-      f32x16 acc[2] = {opaque_zero(), opaque_zero()};
-#pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {   // (a wave past the last channel tile repeats it and stores nothing)
-        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(areg[0][ks], breg[ks], acc[0], 0, 0, 0);
-        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(areg[1][ks], breg[ks], acc[1], 0, 0, 0);
-      }
-      if (live) {
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int row = 32 * t + (r >> 2) * 8 + g * 4 + (r & 3);
-            *(bf16_t*)(stage + row * kAbsPitch + (wave * 32 + c32) * 2) = f32_to_bf16(acc[t][r]);
-          }
-      }
-      __syncthreads();
-      // 64 rows x (pass_ch / 8) 16-byte pieces, one piece per thread and step
-      const int pieces = pass_ch >> 3;
-      for (int id = tid; id < 64 * pieces; id += 256) {
-        const int row = id / pieces, pc = id - row * pieces, s_ = m0 + row;
-        if (s_ < batch)
-          *(bf16x8*)(q_abs + (((size_t)s_ * n_blocks + b) * h + head) * d_cb + ct0 * 32 + pc * 8) =
-              *(const bf16x8*)(stage + row * kAbsPitch + pc * 16);
-      }
-      __syncthreads();
+        for (int ks = 0; ks < 8; ++ks)
+          areg[t][ks] = *(const bf16x8*)(qs + (32 * t + c32) * 256 + (((2 * ks + g) ^ (c32 & 15)) << 4));
     }
+    __syncthreads();      // every wave holds its operands: the weight rows' space becomes the result staging
+    const int pass_ch = min(128, d_cb - ct0 * 32);          // channels this pass produces
+    f32x16 acc[2] = {opaque_zero(), opaque_zero()};
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(areg[0][ks], breg[ks], acc[0], 0, 0, 0);
+      acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(areg[1][ks], breg[ks], acc[1], 0, 0, 0);
+    }
+    if (live) {
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int row = 32 * t + (r >> 2) * 8 + g * 4 + (r & 3);
+          *(bf16_t*)(stage + row * kAbsPitch + (wave * 32 + c32) * 2) = f32_to_bf16(acc[t][r]);
+        }
+    }
+    __syncthreads();
+    // 64 rows x (pass_ch / 8) 16-byte pieces, one piece per thread and step
+    const int pieces = pass_ch >> 3;
+    for (int id = tid; id < 64 * pieces; id += 256) {
+      const int row = id / pieces, pc = id - row * pieces, s_ = m0 + row;
+      if (s_ < batch)
+        *(bf16x8*)(q_abs + (((size_t)s_ * n_blocks + b) * h + head) * d_cb + ct0 * 32 + pc * 8) =
+            *(const bf16x8*)(stage + row * kAbsPitch + pc * 16);
+    }
+    __syncthreads();
   }
 }
 
