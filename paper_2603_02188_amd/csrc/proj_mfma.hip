@@ -221,10 +221,13 @@ __global__ __launch_bounds__(256) void merge_upproj_mfma_kernel(
     const int sl = t / units_per_seq, seq = m0 + sl, k = t % n_splits;
     float2 ml = make_float2(kNegBig, 0.f);
     if (sl < n_valid) {
+      // the slot exists in the workspace whether or not its chunk ran: loaded without waiting for the
+      // sequence length (one round trip instead of two), kept only if the chunk is active
+      const float2 got =
+          *(const float2*)(part_ml + ((((size_t)seq * nb_total + b0) * n_splits + t % units_per_seq) * h + head) * 2);
       const int ch = chunk_tab ? chunk_tab[seq] : chunk;
       const int active = min(n_splits, (seq_lens[seq] + ch - 1) / ch);
-      if (k < active)
-        ml = *(const float2*)(part_ml + ((((size_t)seq * nb_total + b0) * n_splits + t % units_per_seq) * h + head) * 2);
+      if (k < active) ml = got;
     }
     wtab[t] = ml.x;
     ltab[t] = ml.y;
