@@ -166,7 +166,7 @@ def _baselines(inp, mlra_decode_us):
             "gqa_kernel": "MFMA streaming kernel",
             "mla_decode_us": mla_us, "mla_over_mlra4": mla_us / mlra_decode_us,
             "mla_kernel": "MFMA kernel (32-token tiles; scores split by heads, values by channels; not pipelined across tiles)",
-            "paper_context": "H100, Section 4.3: MLRA-4 1.05-1.26x faster than GQA, about 2.8x faster than MLA "
+            "paper_context": "H100, Section 4.5: MLRA-4 1.05-1.26x faster than GQA, about 2.8x faster than MLA "
                              "(MLRA-4 measured as one 4-way-TP device's share)"}
 
 

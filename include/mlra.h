@@ -14,7 +14,7 @@
  * partial-RoPE dim, d_c the KV latent dim cut into n_blocks channel blocks of d_cb = d_c/n_blocks
  * (Section 2.1 "Block Multiplications"), tau = 1/sqrt(d_h + d_r) the softmax scale.
  * MLRA-4 is n_blocks = 4; one device's share of 4-way tensor parallelism is n_blocks = 1 with that
- * block's pool and weights (Section 3.1: the branches are independent up to a final sum).
+ * block's pool and weights (closing paragraph of Section 3.2: the branches are independent up to a final sum).
  *
  * Layouts (row-major, last index fastest):
  *   latent pool  [num_pages][n_blocks][page_size][d_cb]   C^KV, channel block b of a token in plane b
@@ -164,7 +164,7 @@ MLRA_API int mlra2_decode_attn(const mlra_cache* cache, int32_t batch, int32_t h
                       const void* q_rope, const void* w_uv, float softmax_scale, float out_scale, void* out,
                       int32_t out_dtype, float* lse, void* workspace, size_t workspace_bytes, void* stream);
 
-/* Pre-attention of the newest token of every sequence (Section 2.1 and Appendix B.1, which MLRA keeps from
+/* Pre-attention of the newest token of every sequence (Section 2.1 and Appendix C, subsection "Multi-Head Latent Attention (MLA)", which MLRA keeps from
  * MLA; scaling factors of Eq. (9)).  With x = hidden[s] and t = positions[s]:
  *   C^Q  = alpha_q  RMSNorm(x W^DQ)      q_nope[s][i] = (C^Q W^UQ)[i d_h : (i+1) d_h]
  *   C^KV = alpha_kv RMSNorm(x W^DKV)     q_rope[s][i] = RoPE((C^Q W^QR)[i d_r : (i+1) d_r], t)

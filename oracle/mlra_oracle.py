@@ -26,7 +26,7 @@ What each function follows (all citations are to the MLRA paper):
   * gqa_decode              -- Appendix C, MQA/GQA: query head i reads KV head floor(i/r),
     r = h/g.
   * rms_norm / rope / pre_attention -- the projections that produce one new token's queries
-    and cache row (Section 2.1 and Appendix B.1 "MLA": C^Q = alpha_q RMSNorm(H W^DQ), Q^NoPE = C^Q W^UQ,
+    and cache row (Section 2.1 and Appendix C, subsection "Multi-Head Latent Attention (MLA)": C^Q = alpha_q RMSNorm(H W^DQ), Q^NoPE = C^Q W^UQ,
     Q^RoPE = RoPE(C^Q W^QR), C^KV = alpha_kv RMSNorm(H W^DKV), K^RoPE = RoPE(H W^KR); the scaling
     factors are those of Eq. (9)); RoPE rotates the 2-D blocks [2l, 2l+1] by t theta_l as in the
     proof of the paper's RoPE theorem (Appendix B).
@@ -317,7 +317,7 @@ def gqa_decode(q, K, V, scale):
 
 
 # --------------------------------------------------------------------------------------
-# Pre-attention of one new token per sequence (Section 2.1; Appendix B.1; Eq. (9))
+# Pre-attention of one new token per sequence (Section 2.1; Appendix C, subsection MLA; Eq. (9))
 # --------------------------------------------------------------------------------------
 def rms_norm(x, gain=None, eps=0.0):
     """RMSNorm over the last axis: x / sqrt(mean(x^2) + eps) * gain (the paper cites the standard

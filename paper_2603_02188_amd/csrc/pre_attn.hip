@@ -1,4 +1,4 @@
-// Pre-attention of the new token of every sequence (Section 2.1; Appendix B.1, MLA form, which MLRA
+// Pre-attention of the new token of every sequence (Section 2.1; Appendix C, subsection "Multi-Head Latent Attention (MLA)", the form MLRA
 // keeps; scaling factors of Eq. (9)):
 //   C^Q  = alpha_q  RMSNorm(H W^DQ),   Q^NoPE = C^Q W^UQ,   Q^RoPE = RoPE(C^Q W^QR)
 //   C^KV = alpha_kv RMSNorm(H W^DKV),  K^RoPE = RoPE(H W^KR);   C^KV and K^RoPE go into the cache.

@@ -425,22 +425,30 @@ int launch_absorb_q_mfma(int batch, int h, int d_h, int n_blocks, int groups, in
   return check_launch();
 }
 
+// Dynamic LDS of the merge + up-projection kernel: the weight rows, the normalised z rows of 32 sequences,
+// the merge weights of every (sequence, block, chunk), the active-chunk counts.
+static size_t merge_upproj_lds_bytes(const DecodeArgs& a) {
+  const int bpg = a.n_blocks / a.groups, R = bpg * a.d_cb;
+  return (size_t)kWRowsLds * 256 + (size_t)32 * (R + 8) * 2 + (size_t)64 * bpg * a.plan.n_splits * sizeof(float) +
+         32 * sizeof(int);
+}
+constexpr size_t kMergeLdsLimit = 160 * 1024;
+
+// (shapes whose tables would not fit the 160 KiB of LDS take the generic epilogue instead of failing at launch)
 bool merge_upproj_mfma_supported(const DecodeArgs& a) {
   return a.dtype == MLRA_BF16 && a.d_h == kDh && a.d_cb % 32 == 0 && a.n_blocks / a.groups * a.d_cb <= 1024 &&
-         a.n_blocks / a.groups * a.plan.n_splits <= 128;
+         a.n_blocks / a.groups * a.plan.n_splits <= 128 && merge_upproj_lds_bytes(a) <= kMergeLdsLimit;
 }
 
 int launch_merge_upproj_mfma(const DecodeArgs& a) {
-  const int bpg = a.n_blocks / a.groups, R = bpg * a.d_cb;
-  const size_t lds = (size_t)kWRowsLds * 256 + (size_t)32 * (R + 8) * 2 +
-                     (size_t)64 * bpg * a.plan.n_splits * sizeof(float) + 32 * sizeof(int);
+  const size_t lds = merge_upproj_lds_bytes(a);
   static PerDeviceSetup setup;
   int setup_dev = -1;
   if (setup.needed(&setup_dev)) {
     if (hipFuncSetAttribute((const void*)merge_upproj_mfma_kernel<bf16_t>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            160 * 1024) != hipSuccess ||
+                            (int)kMergeLdsLimit) != hipSuccess ||
         hipFuncSetAttribute((const void*)merge_upproj_mfma_kernel<float>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            160 * 1024) != hipSuccess)
+                            (int)kMergeLdsLimit) != hipSuccess)
       return MLRA_ERR_LAUNCH;
     setup.done(setup_dev);
   }

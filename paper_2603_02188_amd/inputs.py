@@ -324,7 +324,7 @@ def make_gqa_inputs(wl: Workload, poison: bool = True,
 
 @dataclass
 class PreInputs:
-    """The new token's hidden states and the projection weights of Appendix B.1 (MLA form, kept by MLRA)."""
+    """The new token's hidden states and the projection weights of Appendix C, subsection "Multi-Head Latent Attention (MLA)" (the form MLRA keeps)."""
 
     wl: Workload
     d: int                   # hidden size

@@ -28,6 +28,9 @@ MUTS = [
  ("mlra2 unabsorbed: drop rope", "            s = tau * (K_bi @ q_nope[i]) + tau * (KR @ q_rope[i])\n", "            s = tau * (K_bi @ q_nope[i])\n"),
  ("rope_angles: +2l/d_r", "** (-2.0 * np.arange(d_r // 2) / d_r)", "** (2.0 * np.arange(d_r // 2) / d_r)"),
  ("rope_angles: l/d_r", "** (-2.0 * np.arange(d_r // 2) / d_r)", "** (-1.0 * np.arange(d_r // 2) / d_r)"),
+ ("rope_angles: starts at l = 1", "** (-2.0 * np.arange(d_r // 2) / d_r)", "** (-2.0 * (np.arange(d_r // 2) + 1) / d_r)"),
+ ("rope_angles: 2l/(d_r/2)", "** (-2.0 * np.arange(d_r // 2) / d_r)", "** (-2.0 * np.arange(d_r // 2) / (d_r // 2))"),
+ ("gated: divide instead of multiply", "return np.asarray(O, np.float64) * np.asarray(G, np.float64)", "return np.asarray(O, np.float64) / np.asarray(G, np.float64)"),
  ("gated: add instead of multiply", "return np.asarray(O, np.float64) * np.asarray(G, np.float64)", "return np.asarray(O, np.float64) + np.asarray(G, np.float64)"),
  ("mla: out_scale 0.5", "return mlra_decode_absorbed(q_nope, q_rope, C, KR, W_UK, W_UV, 1, tau, 1.0)", "return mlra_decode_absorbed(q_nope, q_rope, C, KR, W_UK, W_UV, 1, tau, 0.5)"),
 ]

@@ -162,6 +162,10 @@ def test_workload_shapes_take_the_fast_paths():
     assert mla["kernel"] == "mfma-mla" and mla["target_chunks"] == 256 and mla["single_if_uniform"]
     two = info("M2", batch=128, max_seq_len=8192)
     assert two["kernel"] == "mfma-paired" and two["chunk_slots"] == 4 and two["single_if_uniform"]
+    # 8 blocks x 16 chunks: the MFMA epilogue's LDS tables would exceed 160 KiB, so the generic epilogue runs
+    big = info("C3", batch=2, n_blocks=8, max_seq_len=2048)
+    assert (big["kernel"], big["chunk_slots"], big["merge_mfma"]) == ("mfma", 16, False)
+    assert info("C3", batch=2, n_blocks=4, max_seq_len=2048)["merge_mfma"]
 
 
 def test_plan_info_errors():

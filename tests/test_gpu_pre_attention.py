@@ -1,5 +1,9 @@
-"""GPU parity of mlra_pre_attention (Appendix B.1 projections, RMSNorm, Eq. (9) scaling, RoPE, cache
-append) against the fp64 oracle.  Bars: max|gpu - ref| / max|ref| <= 1e-2 for bf16, <= 1e-5 for fp32."""
+"""GPU parity of mlra_pre_attention (projections of the appendix "Attention Mechanism", subsection
+Multi-Head Latent Attention; RMSNorm, Eq. (9) scaling, RoPE, cache append) against the fp64 oracle.
+Bars: max|gpu - ref| / max|ref| <= 1e-2 for bf16, <= 1e-5 for fp32, taken against the exact oracle (no
+intermediate rounding on the oracle's side: the kernel's rounding of C^Q to the storage type is part of
+what the budget covers).  As a diagnostic, the same outputs must also lie within half of the budget of
+the oracle evaluated with C^Q rounded where the kernel rounds it."""
 import sys
 
 import numpy as np
@@ -41,16 +45,17 @@ def _run_and_check(wl, d, d_cq, lens, unit_gains=False):
     f = lambda a: gen.to_f64(a, tag)
     round_cq = orc.round_bf16 if tag == "bf16" else (lambda v: np.asarray(v, np.float32).astype(np.float64))
     ps = wl.page_size
-    worst = 0.0
+    worst = worst_rounded = 0.0
     untouched_lat = np.ones(lat.shape, bool)
     untouched_rope = np.ones(rope.shape, bool)
     for s in range(wl.batch):
         pos = int(inp.positions[s])
-        c_kv, k_rope, qn, qr = orc.pre_attention(f(pre.hidden)[s], max(pos, 0), f(pre.w_dq), f(pre.w_dkv),
-                                                 f(pre.w_kr), f(pre.w_uq), f(pre.w_qr), wl.h, pre.alpha_q,
-                                                 pre.alpha_kv, f(pre.gain_q), f(pre.gain_kv), pre.eps,
-                                                 pre.rope_base, round_cq=round_cq)
+        args = (f(pre.hidden)[s], max(pos, 0), f(pre.w_dq), f(pre.w_dkv), f(pre.w_kr), f(pre.w_uq), f(pre.w_qr),
+                wl.h, pre.alpha_q, pre.alpha_kv, f(pre.gain_q), f(pre.gain_kv), pre.eps, pre.rope_base)
+        c_kv, k_rope, qn, qr = orc.pre_attention(*args)                  # the exact definition
         worst = max(worst, max_rel_err(q_nope[s], qn), max_rel_err(q_rope[s], qr))
+        _, _, qn_r, qr_r = orc.pre_attention(*args, round_cq=round_cq)   # diagnostic only
+        worst_rounded = max(worst_rounded, max_rel_err(q_nope[s], qn_r), max_rel_err(q_rope[s], qr_r))
         if pos < 0:
             continue
         page, slot = int(inp.page_table[s, pos // ps]), pos % ps
@@ -58,8 +63,10 @@ def _run_and_check(wl, d, d_cq, lens, unit_gains=False):
         worst = max(worst, max_rel_err(got_row, c_kv), max_rel_err(rope[page, slot], k_rope))
         untouched_lat[page, :, slot, :] = False
         untouched_rope[page, slot, :] = False
-    _say(f"       max rel err {worst:.3e} (tol {TOL[tag]:g})")
+    _say(f"       max rel err {worst:.3e} (tol {TOL[tag]:g}); against the oracle with C^Q rounded to the "
+         f"storage type {worst_rounded:.3e}")
     assert worst <= TOL[tag]
+    assert worst_rounded <= 0.5 * TOL[tag]
     # nothing but the new rows was written (bitwise; NaN poison compares through the raw bits)
     raw = lambda t: t.view(torch.int16) if t.dtype == torch.bfloat16 else t.view(torch.int32)
     assert torch.equal(raw(cache.latent)[torch.from_numpy(untouched_lat).cuda()],

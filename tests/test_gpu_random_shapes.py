@@ -87,3 +87,27 @@ def _one(seed):
 def test_random_shapes_match_the_oracle(first):
     for seed in range(first, first + 16):
         assert _one(seed) <= 1e-2, f"seed {seed}"
+
+
+def test_eight_blocks_sixteen_chunks_epilogue_tables_exceed_lds():
+    """8 blocks x 128 channels with 16 chunks per sequence: the MFMA epilogue's tables (1024 latent channels
+    of z rows plus 128 merge weights per sequence) would need more than the 160 KiB of LDS, so the call has
+    to take the generic merge + up-projection (and must not fail at launch)."""
+    wl = gen.WORKLOADS["C3"].scaled(name="eight-blocks", batch=2, n_min=1500, n_max=2048, n_blocks=8, index=2001)
+    lens = np.array([2048, 1501], dtype=np.int32)
+    info = mlra.mlra_decode_plan_info(wl.batch, wl.h, wl.d_h, 1, wl.n_blocks, wl.d_cb, wl.d_r, wl.page_size, 2048,
+                                      torch.bfloat16)
+    assert info["kernel"] == "mfma" and info["chunk_slots"] == 16 and not info["merge_mfma"]
+    inp = gen.make_decode_inputs(wl, poison=True, seq_lens=lens)
+    assert inp.page_table.shape[1] * wl.page_size == 2048
+    cache = device_cache(inp)
+    q_nope, q_rope, w_uk, w_uv = device_queries_weights(inp)
+    q_abs = mlra.mlra_absorb_q(q_nope, w_uk)
+    out = mlra.mlra_decode_attn(cache, q_abs, q_rope, w_uv, wl.tau, 1.0, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    v = oracle_views(inp)
+    ref = orc.mlra_decode_batch(v["latent_pool"], v["rope_pool"], v["page_table"], v["seq_lens"], v["q_nope"],
+                                v["q_rope"], v["w_uk"], v["w_uv"], wl.tau, 1.0)
+    err = max_rel_err(host(out), ref)
+    print(f"[case] eight blocks, sixteen chunks: max rel err {err:.3e}", flush=True)
+    assert err <= 1e-2

@@ -512,6 +512,38 @@ def test_rope_matches_the_complex_form_of_the_papers_theorem():
     assert abs(r[0] - math.cos(3.0)) <= 1e-12 and abs(r[1] - math.sin(3.0)) <= 1e-12 and np.all(r[2:] == 0.0)
 
 
+def test_rope_frequencies_hand_values_and_read_back_angles():
+    """The frequency law theta_l = base^(-2l/d_r) (the usual reading; the paper leaves the constants open)
+    pinned by hand-computed values, not by its own expression: base 100 makes every frequency a power of
+    sqrt(10).  The angles are also read back from rope() itself: unit vector e_{2l} at t = 1 is rotated
+    to (cos theta_l, sin theta_l) in its 2-D block, so atan2 recovers theta_l, and consecutive
+    frequencies keep the constant ratio base^(-2/d_r)."""
+    # d_r = 4: theta = 100^0, 100^(-1/2);  d_r = 8: 100^0, 100^(-1/4), 100^(-1/2), 100^(-3/4)
+    hand = {4: [1.0, 0.1], 8: [1.0, 0.31622776601683794, 0.1, 0.031622776601683794]}
+    for d_r, want in hand.items():
+        got = orc.rope_angles(d_r, 100.0)
+        assert got.shape == (d_r // 2,)
+        assert np.max(np.abs(got - np.array(want))) <= 1e-15
+        for l in range(d_r // 2):
+            e = np.zeros(d_r); e[2 * l] = 1.0
+            r = orc.rope(e, 1, 100.0)
+            assert abs(math.atan2(r[2 * l + 1], r[2 * l]) - want[l]) <= 1e-15      # the angle of block l at t = 1
+            assert np.all(np.delete(r, [2 * l, 2 * l + 1]) == 0.0)                 # nothing leaks into other blocks
+            e = np.zeros(d_r); e[2 * l + 1] = 1.0                                   # second axis of the block: +90 degrees
+            r = orc.rope(e, 1, 100.0)
+            assert abs(math.atan2(-r[2 * l], r[2 * l + 1]) - want[l]) <= 1e-15
+    # the default base 10000 at d_r = 64 (the benchmark shape): first, middle and last frequency by hand:
+    # 10000^0, 10000^(-32/64) = 0.01, 10000^(-62/64) = 10^(-3.875)
+    th = orc.rope_angles(64, 10000.0)
+    assert th[0] == 1.0 and abs(th[16] - 0.01) <= 1e-17 and abs(th[31] - 1.3335214321633240e-4) <= 1e-18
+    ratios = th[1:] / th[:-1]
+    assert np.max(np.abs(ratios - 0.74989420933245582)) <= 1e-14                    # 10^(-1/8), constant
+    # angles add up over positions: t = 7 is seven times the t = 1 rotation (read back below one turn)
+    e = np.zeros(8); e[2] = 1.0
+    r = orc.rope(e, 7, 100.0)
+    assert abs(math.atan2(r[3], r[2]) - 7 * 0.31622776601683794) <= 1e-14
+
+
 def test_rms_norm_against_library_and_invariants():
     rng = np.random.default_rng(72)
     x = rng.standard_normal((5, 48)) * 3.0
@@ -524,7 +556,7 @@ def test_rms_norm_against_library_and_invariants():
 
 
 def test_pre_attention_scalar_loops_and_scaling():
-    """Appendix B.1 written out with scalar sums on a tiny case; alpha factors are those of Eq. (9)."""
+    """The MLA projections of Appendix C (subsection "Multi-Head Latent Attention (MLA)") written out with scalar sums on a tiny case; alpha factors are those of Eq. (9)."""
     rng = np.random.default_rng(73)
     d, d_cq, d_c, d_r, h, d_h = 6, 4, 8, 4, 2, 3
     x = rng.standard_normal(d)
@@ -559,7 +591,7 @@ def test_pre_attention_scalar_loops_and_scaling():
 
 def test_pre_attention_scores_depend_on_relative_position_only():
     """The RoPE part of the logit between a query made at position tq and a key made at position tk
-    depends on tq - tk only (semi-translation equivariance, Appendix B.1 remark)."""
+    depends on tq - tk only (semi-translation equivariance: the remark that closes the MLA subsection of Appendix C, by the RoPE theorem of Appendix B)."""
     rng = np.random.default_rng(74)
     d, d_cq, d_c, d_r, h, d_h = 12, 6, 8, 8, 3, 4
     Ws = [rng.standard_normal(s) for s in ((d, d_cq), (d, d_c), (d, d_r), (d_cq, h * d_h), (d_cq, h * d_r))]
@@ -623,12 +655,26 @@ def test_multi_token_decode_causality_and_single_token_case():
 
 
 def test_gated_output_is_the_elementwise_product():
+    """Appendix E: the gate multiplies the attention output element by element.  Pinned by hand values, by
+    the cases that have closed forms (all-ones gate, zero gate, one-hot gate, sigmoid of zero), by
+    linearity in each argument, and by a library product; a matrix product or a broadcast over the wrong
+    axis fails the one-hot and the shape cases."""
+    got = orc.gated_output([[2.0, -3.0, 0.5], [4.0, 8.0, -1.0]], [[0.5, 0.25, 1.0], [0.0, 0.125, 2.0]])
+    assert np.array_equal(got, np.array([[1.0, -0.75, 0.5], [0.0, 1.0, -2.0]]))
     rng = np.random.default_rng(91)
     O, G = rng.standard_normal((3, 4)), 1.0 / (1.0 + np.exp(-rng.standard_normal((3, 4))))
-    got = orc.gated_output(O, G)
-    for i in range(3):
-        for p in range(4):
-            assert got[i][p] == O[i][p] * G[i][p]
+    assert np.array_equal(orc.gated_output(O, np.ones_like(O)), O)
+    assert np.all(orc.gated_output(O, np.zeros_like(O)) == 0.0)
+    assert np.array_equal(orc.gated_output(O, np.full_like(O, 0.5)), 0.5 * O)      # sigma(0) = 1/2 everywhere
+    onehot = np.zeros_like(O); onehot[1, 2] = 1.0
+    picked = orc.gated_output(O, onehot)
+    assert picked[1, 2] == O[1, 2] and np.count_nonzero(picked) == 1                # (head 1, channel 2) only
+    G2 = rng.standard_normal((3, 4))
+    assert np.max(np.abs(orc.gated_output(O, G + G2) - orc.gated_output(O, G) - orc.gated_output(O, G2))) <= 1e-15
+    assert np.max(np.abs(orc.gated_output(O + G2, G) - orc.gated_output(O, G) - orc.gated_output(G2, G))) <= 1e-15
+    lib = torch.mul(torch.from_numpy(O), torch.from_numpy(G)).numpy()
+    assert np.array_equal(orc.gated_output(O, G), lib)
+    assert orc.gated_output(O, G).shape == (3, 4)
 
 
 def test_gla2_against_library_sdpa_on_materialised_keys_and_values():
