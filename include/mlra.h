@@ -110,6 +110,21 @@ MLRA_API int mlra_decode_attn(const mlra_cache* cache, int32_t batch, int32_t h,
                      const void* q_rope, const void* w_uv, float softmax_scale, float out_scale, void* out,
                      int32_t out_dtype, float* lse, void* workspace, size_t workspace_bytes, void* stream);
 
+/* mlra_decode_attn for callers that cannot allocate device memory or pass a workspace (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): same arguments without the
+ * workspace, same kernels, same results.  The scratch memory is a fixed array of
+ * MLRA_STATIC_SCRATCH_BYTES inside the library's device image (each GPU the library runs on holds its
+ * own copy until the process ends); the call allocates and frees nothing.  Shapes whose
+ * mlra_decode_workspace_bytes exceeds MLRA_STATIC_SCRATCH_BYTES return MLRA_ERR_WORKSPACE and enqueue
+ * nothing (the five benchmark configurations need at most 32.6 MiB).  All calls on one GPU share that
+ * GPU's array: calls that may overlap on one GPU (different streams, different threads) race on it and
+ * must be serialised by the caller; calls on one stream are ordered and safe.  The first call on a
+ * device looks up the array's address (hipGetSymbolAddress), later calls reuse it. */
+#define MLRA_STATIC_SCRATCH_BYTES (40u << 20)
+MLRA_API int mlra_decode_attn_static(const mlra_cache* cache, int32_t batch, int32_t h, int32_t d_h, const void* q_abs,
+                            const void* q_rope, const void* w_uv, float softmax_scale, float out_scale, void* out,
+                            int32_t out_dtype, float* lse, void* stream);
+
 /* Gated attention output (Appendix E, "Gated Attention": O^attn = Attention(H') . G with
  * G = sigma(H W^G) in R^{h d_h}): mlra_decode_attn with its output multiplied elementwise by
  *   gate [batch][h][d_h] of the cache dtype, the values of G (the nonlinearity is applied upstream).

@@ -20,7 +20,7 @@ _lib: Optional[ctypes.CDLL] = None
 MLRA_BF16, MLRA_F32 = 0, 1
 
 EXPORTS = ("mlra_strerror", "mlra_append_kv", "mlra_absorb_q", "mlra_decode_workspace_bytes",
-           "mlra_decode_attn", "mla_decode_attn", "mlra2_absorb_q", "mlra2_decode_workspace_bytes",
+           "mlra_decode_attn", "mlra_decode_attn_static", "mla_decode_attn", "mlra2_absorb_q", "mlra2_decode_workspace_bytes",
            "mlra2_decode_attn", "mlra_decode_attn_gated", "mlra_decode_multi_workspace_bytes", "mlra_decode_attn_multi",
            "mlra_pre_attention_workspace_bytes", "mlra_pre_attention",
            "gqa_decode_workspace_bytes", "gqa_decode_attn", "mlra_kernel_timing_begin",
@@ -69,6 +69,8 @@ def load_library() -> ctypes.CDLL:
     lib.mlra_decode_workspace_bytes.argtypes = [i32, i32, i32, i32, i32]
     lib.mlra_decode_attn.restype = ctypes.c_int
     lib.mlra_decode_attn.argtypes = [cp, i32, i32, i32, vp, vp, vp, f32, f32, vp, i32, vp, vp, sz, vp]
+    lib.mlra_decode_attn_static.restype = ctypes.c_int
+    lib.mlra_decode_attn_static.argtypes = [cp, i32, i32, i32, vp, vp, vp, f32, f32, vp, i32, vp, vp]
     lib.mlra2_absorb_q.restype = ctypes.c_int
     lib.mlra2_absorb_q.argtypes = lib.mlra_absorb_q.argtypes
     lib.mlra2_decode_workspace_bytes.restype = sz
@@ -210,6 +212,22 @@ def mlra_decode_attn(cache: Cache, q_abs: torch.Tensor, q_rope: torch.Tensor, w_
                      workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
     return _decode("mlra_decode_attn", cache, q_abs, q_rope, w_uv, softmax_scale, out_scale, out, out_dtype, lse,
                    workspace, stream)
+
+
+def mlra_decode_attn_static(cache: Cache, q_abs: torch.Tensor, q_rope: torch.Tensor, w_uv: torch.Tensor,
+                            softmax_scale: float, out_scale: float, out: torch.Tensor,
+                            lse: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """mlra_decode_attn on the library's built-in scratch memory: the caller passes every buffer (out
+    included) and nothing is allocated, here or in the library."""
+    lib = load_library()
+    cs = cache.struct()
+    batch, n_blocks, h, d_cb = q_abs.shape
+    d_h = w_uv.shape[2] // h
+    assert w_uv.shape == (n_blocks, d_cb, h * d_h) and q_rope.shape[:2] == (batch, h) and out.shape == (batch, h, d_h)
+    _check(lib.mlra_decode_attn_static(ctypes.byref(cs), batch, h, d_h, _ptr(q_abs), _ptr(q_rope), _ptr(w_uv),
+                                       float(softmax_scale), float(out_scale), _ptr(out), _dt(out.dtype), _ptr(lse),
+                                       _stream(stream)), "mlra_decode_attn_static")
+    return out
 
 
 def mla_decode_attn(cache: Cache, q_abs: torch.Tensor, q_rope: torch.Tensor, w_uv: torch.Tensor,

@@ -98,6 +98,31 @@ SplitPlan plan_splits(int batch, int n_blocks, int max_seq_len) {
 
 static bool valid_dtype(int d) { return d == MLRA_BF16 || d == MLRA_F32; }
 
+// Scratch memory of mlra_decode_attn_static: one copy per GPU the library runs on, held until the process
+// ends.  In host code the array's name is only a handle for the runtime; its device address on the
+// current GPU comes from hipGetSymbolAddress, once per device, and that pointer is what the kernels get.
+constexpr size_t kStaticScratchBytes = (size_t)MLRA_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+static std::atomic<void*> g_scratch_ptr[64];   // per device, null = not asked yet
+
+static int static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) {
+    (void)hipGetLastError();
+    return MLRA_ERR_LAUNCH;
+  }
+  void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!ptr) {
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+      (void)hipGetLastError();
+      return MLRA_ERR_LAUNCH;
+    }
+    g_scratch_ptr[dev].store(ptr, std::memory_order_release);
+  }
+  *out = ptr;
+  return MLRA_OK;
+}
+
 static size_t decode_ws_bytes(int batch, int h, int n_blocks, int d_cb, const SplitPlan& p) {
   const size_t units = (size_t)batch * n_blocks * p.n_splits;
   return align_up(units * h * d_cb * sizeof(float), 256) + align_up(units * h * 2 * sizeof(float), 256) +
@@ -234,6 +259,26 @@ int mlra_decode_attn(const mlra_cache* cache, int32_t batch, int32_t h, int32_t 
                      int32_t out_dtype, float* lse, void* workspace, size_t workspace_bytes, void* stream) {
   return decode_common(cache, batch, h, 1, d_h, q_abs, q_rope, w_uv, softmax_scale, out_scale, out, out_dtype, lse,
                        workspace, workspace_bytes, stream);
+}
+
+int mlra_decode_attn_static(const mlra_cache* cache, int32_t batch, int32_t h, int32_t d_h, const void* q_abs,
+                            const void* q_rope, const void* w_uv, float softmax_scale, float out_scale, void* out,
+                            int32_t out_dtype, float* lse, void* stream) {
+  if (!cache) return MLRA_ERR_NULL;
+  if (batch <= 0 || h <= 0 || cache->n_blocks <= 0 || cache->d_cb <= 0 || cache->page_size <= 0 ||
+      cache->max_pages_per_seq <= 0 || (long)cache->max_pages_per_seq * cache->page_size > 0x7fffffffL)
+    return MLRA_ERR_SHAPE;
+  const size_t need = mlra_decode_workspace_bytes(batch, h, cache->n_blocks, cache->d_cb,
+                                                  cache->max_pages_per_seq * cache->page_size);
+  if (need == 0) return MLRA_ERR_SHAPE;
+  if (need > kStaticScratchBytes) return MLRA_ERR_WORKSPACE;   // beyond the built-in scratch: use mlra_decode_attn
+  void* ptr = nullptr;
+  const int st = static_scratch(&ptr);
+  if (st != MLRA_OK) return st;
+  // (every partial, table and row that the kernels read from the scratch is written earlier in the same
+  // call, so what the previous call left there is never read and nothing needs clearing)
+  return decode_common(cache, batch, h, 1, d_h, q_abs, q_rope, w_uv, softmax_scale, out_scale, out, out_dtype, lse,
+                       ptr, kStaticScratchBytes, stream);
 }
 
 size_t mlra_decode_multi_workspace_bytes(int32_t batch, int32_t q_len, int32_t h, int32_t n_blocks, int32_t d_cb,

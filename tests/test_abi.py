@@ -168,6 +168,19 @@ def test_workload_shapes_take_the_fast_paths():
     assert info("C3", batch=2, n_blocks=4, max_seq_len=2048)["merge_mfma"]
 
 
+def test_static_entry_point_refuses_what_its_scratch_cannot_hold():
+    """mlra_decode_attn_static checks sizes before it touches the device: a shape whose workspace exceeds the
+    built-in 40 MiB returns MLRA_ERR_WORKSPACE, invalid sizes MLRA_ERR_SHAPE, a null cache MLRA_ERR_NULL."""
+    import ctypes
+    lib = mlra.load_library()
+    cs = mlra._CacheStruct(1, 1, 1, 1, 1 << 20, 64, 256, 4, 128, 64, 0)       # dummy non-null pointers, 16384 tokens
+    assert mlra.mlra_decode_workspace_bytes(512, 128, 4, 128, 16384) > 40 << 20
+    st = lib.mlra_decode_attn_static(ctypes.byref(cs), 512, 128, 128, None, None, None, 0.07, 1.0, None, 0, None, None)
+    assert st == -4
+    assert lib.mlra_decode_attn_static(ctypes.byref(cs), 0, 128, 128, None, None, None, 0.07, 1.0, None, 0, None, None) == -2
+    assert lib.mlra_decode_attn_static(None, 4, 128, 128, None, None, None, 0.07, 1.0, None, 0, None, None) == -1
+
+
 def test_plan_info_errors():
     import ctypes
     import torch
