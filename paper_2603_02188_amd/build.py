@@ -15,9 +15,9 @@ import sys
 from concurrent.futures import ThreadPoolExecutor
 
 try:
-    from .check_isa import find_overlaps
+    from .check_isa import find_overlaps, find_reserved_acc_uses
 except ImportError:  # run as a script
-    from check_isa import find_overlaps
+    from check_isa import find_overlaps, find_reserved_acc_uses
 
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
@@ -62,10 +62,16 @@ def build(verbose: bool = False, jobs: int = 8) -> str:
         # device assembly of the same translation unit, scanned for MFMA register overlaps
         asm = obj[:-2] + ".s"
         _run([hipcc, *HIP_FLAGS, *inc, "-DMLRA_BUILDING", "--cuda-device-only", "-S", src, "-o", asm])
-        bad = find_overlaps(open(asm).read())
+        text = open(asm).read()
+        bad = find_overlaps(text)
         if bad:
             raise RuntimeError(f"{src}: MFMA destination overlaps a source operand:\n" +
                                "\n".join(f"  {asm}:{ln}: {text}" for ln, text in bad))
+        # the decode kernel's value accumulators (a0..a135) belong to its inline asm alone
+        bad = find_reserved_acc_uses(text, r"decode_mfma_kernel", 136)
+        if bad:
+            raise RuntimeError(f"{src}: compiler-generated code touches the reserved accumulation registers:\n" +
+                               "\n".join(f"  {asm}:{ln}: {text}" for ln, text in bad[:20]))
         return obj
 
     with ThreadPoolExecutor(max_workers=max(1, min(jobs, len(srcs)))) as ex:

@@ -33,6 +33,39 @@ def find_overlaps(asm_text: str):
     return bad
 
 
+_AREG = re.compile(r"\ba(\d+)\b|\ba\[(\d+):(\d+)\]")
+
+
+def find_reserved_acc_uses(asm_text: str, kernel_pattern: str, reserved: int):
+    """Kernels whose name matches kernel_pattern keep state in accumulation registers a0 .. a(reserved-1)
+    that only their inline asm may touch (the compiler never sees those registers as values).  Returns the
+    instructions OUTSIDE inline-asm blocks (the ;;#ASMSTART ... ;;#ASMEND regions of the emitted assembly)
+    that name one of them."""
+    bad = []
+    in_kernel = in_asm = False
+    for ln, line in enumerate(asm_text.splitlines(), 1):
+        text = line.strip()
+        if re.match(r"^[A-Za-z_.$][\w.$]*:", text):               # a label
+            if not text.startswith(".L"):
+                in_kernel = re.search(kernel_pattern, text) is not None
+            continue
+        if text.startswith(";;#ASMSTART"):
+            in_asm = True
+            continue
+        if text.startswith(";;#ASMEND"):
+            in_asm = False
+            continue
+        if not in_kernel or in_asm or not text or text.startswith((";", ".")):
+            continue
+        code = text.split(";")[0]
+        for m in _AREG.finditer(code):
+            lo = int(m.group(1)) if m.group(1) is not None else int(m.group(2))
+            if lo < reserved:
+                bad.append((ln, text))
+                break
+    return bad
+
+
 if __name__ == "__main__":
     total = 0
     for path in sys.argv[1:]:

@@ -142,6 +142,66 @@ __global__ __launch_bounds__(256) void plan_chunks_kernel(const int32_t* __restr
   for (int u = n_active + threadIdx.x; u < batch * max_slots; u += 256) unit_tab[u] = -1;
 }
 
+
+// ---- value accumulators in fixed accumulation registers ---------------------------------------------
+// Z^T (four 32-channel x two 32-head tiles of fp32, 128 registers per lane) and the row sums l (two
+// 16x16 tiles, 8 registers) live in a[0:135] for the whole chunk and are touched only by the inline asm
+// below, by register NAME: tile (mt, nt) is a[16 (2 mt + nt) : +15], the row sums of head tile nt are
+// a[128 + 4 nt : +3].  The compiler never sees them as values (left to it, it moved the 16-register
+// tuples between loops with copies placed right behind MFMAs it cannot see, and ran out of accumulation
+// registers for the queries); the clobber list keeps its own values out of these registers, and the
+// build checks that no instruction outside the asm blocks names them.  An MFMA writes its result several
+// passes after it issues: acc_settle() lets the last one retire before acc_read / acc_scale.
+#define MLRA_ACC_CLOBBERS "a0","a1","a2","a3","a4","a5","a6","a7","a8","a9","a10","a11","a12","a13","a14","a15","a16","a17","a18","a19","a20","a21","a22","a23","a24","a25","a26","a27","a28","a29","a30","a31","a32","a33","a34","a35","a36","a37","a38","a39","a40","a41","a42","a43","a44","a45","a46","a47","a48","a49","a50","a51","a52","a53","a54","a55","a56","a57","a58","a59","a60","a61","a62","a63","a64","a65","a66","a67","a68","a69","a70","a71","a72","a73","a74","a75","a76","a77","a78","a79","a80","a81","a82","a83","a84","a85","a86","a87","a88","a89","a90","a91","a92","a93","a94","a95","a96","a97","a98","a99","a100","a101","a102","a103","a104","a105","a106","a107","a108","a109","a110","a111","a112","a113","a114","a115","a116","a117","a118","a119","a120","a121","a122","a123","a124","a125","a126","a127","a128","a129","a130","a131","a132","a133","a134","a135"
+constexpr int kAccRegs = 136;
+template <int TILE>
+__device__ __forceinline__ void acc_pv_mfma(const bf16x8& vt, const bf16x8& pt) {   // Z^T tile += V^T P^T
+  asm volatile("v_mfma_f32_32x32x16_bf16 a[%c2:%c3], %0, %1, a[%c2:%c3]"
+               : : "v"(vt), "v"(pt), "n"(16 * TILE), "n"(16 * TILE + 15) : MLRA_ACC_CLOBBERS);
+}
+template <int NT>
+__device__ __forceinline__ void acc_row_sum_mfma(const bf16x8& sel, const bf16x8& pt) {
+  asm volatile("v_mfma_f32_16x16x32_bf16 a[%c2:%c3], %0, %1, a[%c2:%c3]"
+               : : "v"(sel), "v"(pt), "n"(128 + 4 * NT), "n"(128 + 4 * NT + 3) : MLRA_ACC_CLOBBERS);
+}
+// all 136 registers to zero: products of a zero operand, no accumulator input
+__device__ __forceinline__ void acc_zero(const bf16x8& zero) {
+  // (the leading wait: the zero operand may have been written by the instruction just before this asm, and
+  // nothing orders a vector write before an MFMA read that the compiler cannot see; measured: without it
+  // the first tile came out as garbage)
+  asm volatile(
+      "s_nop 7\n\t"
+      "v_mfma_f32_32x32x16_bf16 a[0:15], %0, %0, 0\n\tv_mfma_f32_32x32x16_bf16 a[16:31], %0, %0, 0\n\t"
+      "v_mfma_f32_32x32x16_bf16 a[32:47], %0, %0, 0\n\tv_mfma_f32_32x32x16_bf16 a[48:63], %0, %0, 0\n\t"
+      "v_mfma_f32_32x32x16_bf16 a[64:79], %0, %0, 0\n\tv_mfma_f32_32x32x16_bf16 a[80:95], %0, %0, 0\n\t"
+      "v_mfma_f32_32x32x16_bf16 a[96:111], %0, %0, 0\n\tv_mfma_f32_32x32x16_bf16 a[112:127], %0, %0, 0\n\t"
+      "v_mfma_f32_16x16x32_bf16 a[128:131], %0, %0, 0\n\tv_mfma_f32_16x16x32_bf16 a[132:135], %0, %0, 0\n\t"
+      "s_nop 15\n\ts_nop 15"
+      : : "v"(zero) : MLRA_ACC_CLOBBERS);
+}
+template <int REG>
+__device__ __forceinline__ float acc_read() {
+  float x;
+  asm volatile("v_accvgpr_read_b32 %0, a%c1" : "=v"(x) : "n"(REG));
+  return x;
+}
+// a[REG .. REG + COUNT) *= factor (per lane), one register at a time through one ordinary register
+template <int REG, int COUNT>
+__device__ __forceinline__ void acc_scale(float factor) {
+  if constexpr (COUNT > 0) {
+    float t;
+    asm volatile("v_accvgpr_read_b32 %0, a%c2\n\tv_mul_f32 %0, %1, %0\n\tv_accvgpr_write_b32 a%c2, %0"
+                 : "=&v"(t) : "v"(factor), "n"(REG) : MLRA_ACC_CLOBBERS);
+    acc_scale<REG + 1, COUNT - 1>(factor);
+  }
+}
+// four consecutive registers of tile (MT, NT) starting at element 4 R4
+template <int MT, int NT, int R4>
+__device__ __forceinline__ f32x4 acc_read4() {
+  constexpr int base = 16 * (2 * MT + NT) + 4 * R4;
+  return f32x4{acc_read<base>(), acc_read<base + 1>(), acc_read<base + 2>(), acc_read<base + 3>()};
+}
+
 template <int STAGES, int MODE>   // MODE 0: plain, 1: PAIRED, 2: GLA (see the head of the file)
 __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
@@ -247,6 +307,11 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
   const int ntiles = (t1 - t0 + kTile - 1) / kTile;
   const int nvalid_last = t1 - t0 - (ntiles - 1) * kTile;
 
+  // ---- tile order.  Only the chunk's last tile can be ragged, and softmax does not care about the order
+  // of the tokens, so that tile is processed FIRST: it is issued and masked in the prologue, and every
+  // tile that the main loop issues is a full one (straight-line code, no masks in the loop).  Processing
+  // index 0 is the chunk's last tile, processing index jj >= 1 its tile jj - 1.
+
   // ---- page ids: scalar loads through the constant address space (the table is read-only here), so
   // that the compiler's vector-memory wait counts never see a load inside the main loop: a wait for one
   // would also drain every direct-to-LDS load in flight.  The id of the next tile's page is fetched one
@@ -270,25 +335,23 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
   const size_t lat_plane_bytes = (size_t)p.page_size * kLatRow;        // one block's rows inside a page
   const size_t lat_half_step = GLA ? kDcb * 2 : lat_plane_bytes;       // from the first latent tile's source to the second's
   const char* lat_blk = (const char*)p.latent + (size_t)blk0 * lat_plane_bytes;
-  // slot, inside its page, of this wave's first row of the next tile to issue (tiles go in order)
+  // slot, inside its page, of this wave's first row of the next full tile to issue (they go in order)
   int issue_slot = (t0 + 16 * (int)wave_u) % p.page_size;
   int issue_stage = 0;
 
-  // A tile is issued in parts so that the parts can sit behind different MFMAs: issue_begin (scalar
+  // A full tile is issued in parts so that the parts can sit behind different MFMAs: issue_begin (scalar
   // address work), six loads, issue_end (bookkeeping, next page id).
   const char* iss_lat = nullptr;
   const char* iss_rope = nullptr;
   unsigned iss_stage = 0;
-  int iss_last = kTile - 1;
-  auto issue_begin = [&](int jj) {
+  auto issue_begin = [&]() {
     const unsigned page = (unsigned)issue_page;
-    iss_last = min(kTile, t1 - t0 - jj * kTile) - 1;
     // start of this wave's 16 latent rows (block plane blk0) and RoPE rows of the tile inside the page
     iss_lat = lat_blk + page * lat_page_bytes + (unsigned)issue_slot * (unsigned)kLatRow;
     iss_rope = (const char*)p.rope + page * rope_page_bytes + (unsigned)issue_slot * (unsigned)(kDr * 2);
     iss_stage = lds_base + issue_stage * kStageB;
   };
-  // full tile: parts 0..3 = latent loads (PAIRED: 4..7 = the second block's), then two RoPE loads
+  // parts 0..3 = latent loads (PAIRED: 4..7 = the second block's), then two RoPE loads
   auto issue_full_part = [&](int part) {
     if (part < 4 * kBlocksWG) {
       const int jb = part >> 2, q = part & 3;
@@ -305,39 +368,6 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
       if (q == 1) lds_dma16<1024>(iss_rope, rope_voff[1]);
     }
   };
-  // ragged end of the chunk: rows past it re-read its last row (finite values, weight 0 later).  The
-  // rows of this wave that exist lie in its own page; if none exists, every lane reads the tile's last
-  // valid row, whose page may be another one (pages shorter than a tile).
-  auto issue_ragged = [&]() {
-    const int w0 = 16 * (int)wave_u;                 // first tile row of this wave
-    int first = w0;                                  // the tile row that src_lat / src_rope point at
-    const char* src_lat = iss_lat;
-    const char* src_rope = iss_rope;
-    if (w0 > iss_last) {
-      first = iss_last;
-      const int tok = issue_page_idx * p.page_size + issue_slot - w0 + iss_last;   // the last valid token
-      const int idx = tok / p.page_size, slot = tok - idx * p.page_size;
-      const unsigned page = (unsigned)pt_row[idx];
-      src_lat = lat_blk + page * lat_page_bytes + (unsigned)slot * (unsigned)kLatRow;
-      src_rope = (const char*)p.rope + page * rope_page_bytes + (unsigned)slot * (unsigned)(kDr * 2);
-    }
-#pragma unroll
-    for (int jb = 0; jb < kBlocksWG; ++jb)
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int t = (wave * 4 + q) * 4 + (lane >> 4);          // 0..63
-        const unsigned row = (unsigned)(min(t, iss_last) - first);   // rows from src_lat, never negative
-        set_m0(iss_stage + jb * kLatBytes + wave_u * 4096 + q * 1024);
-        lds_dma16<0>(src_lat + jb * lat_half_step, row * kLatRow + (((lane & 15) ^ lat_swz(t)) << 4));
-      }
-#pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      const int t = (wave * 2 + q) * 8 + (lane >> 3);          // 0..63
-      const unsigned row = (unsigned)(min(t, iss_last) - first);
-      set_m0(iss_stage + kRopeOff + wave_u * 2048 + q * 1024);
-      lds_dma16<0>(src_rope, row * (kDr * 2) + (((lane & 7) ^ rope_swz(t)) << 4));
-    }
-  };
   auto issue_end = [&]() {
     issue_slot += kTile;
     if (issue_slot >= p.page_size) {
@@ -349,15 +379,43 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
     }
     issue_stage = (issue_stage + 1 == STAGES) ? 0 : issue_stage + 1;
   };
-  auto issue_tile = [&](int jj) {   // whole tile at once (prologue, and the steps near the end of a chunk)
-    issue_begin(jj);
-    if (iss_last == kTile - 1) {
+  auto issue_tile = [&]() {   // a whole full tile at once (prologue)
+    issue_begin();
 #pragma unroll
-      for (int part = 0; part < kLoadsTile; ++part) issue_full_part(part);
-    } else {
-      issue_ragged();
-    }
+    for (int part = 0; part < kLoadsTile; ++part) issue_full_part(part);
     issue_end();
+  };
+  // The chunk's last tile, into the current stage: rows past the chunk's end re-read its last valid row
+  // (finite values; their probabilities are masked to zero).  The rows of this wave that exist lie in its
+  // own page; if none exists, every lane reads the tile's last valid row, whose page may be another one
+  // (pages shorter than a tile).  Leaves the page bookkeeping of the full tiles untouched.
+  auto issue_last_tile = [&]() {
+    const int last = nvalid_last - 1;                // last valid row of the tile, 0..63
+    const int w0 = 16 * (int)wave_u;                 // first tile row of this wave
+    const int first = w0 > last ? last : w0;         // the tile row that src_lat / src_rope point at
+    const int tok = t0 + (ntiles - 1) * kTile + first;
+    const int idx = tok / p.page_size, slot = tok - idx * p.page_size;
+    const unsigned page = (unsigned)pt_row[idx];
+    const char* src_lat = lat_blk + page * lat_page_bytes + (unsigned)slot * (unsigned)kLatRow;
+    const char* src_rope = (const char*)p.rope + page * rope_page_bytes + (unsigned)slot * (unsigned)(kDr * 2);
+    const unsigned stage = lds_base + issue_stage * kStageB;
+#pragma unroll
+    for (int jb = 0; jb < kBlocksWG; ++jb)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int t = (wave * 4 + q) * 4 + (lane >> 4);          // 0..63
+        const unsigned row = (unsigned)(min(t, last) - first);   // rows from src_lat, never negative
+        set_m0(stage + jb * kLatBytes + wave_u * 4096 + q * 1024);
+        lds_dma16<0>(src_lat + jb * lat_half_step, row * kLatRow + (((lane & 15) ^ lat_swz(t)) << 4));
+      }
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      const int t = (wave * 2 + q) * 8 + (lane >> 3);          // 0..63
+      const unsigned row = (unsigned)(min(t, last) - first);
+      set_m0(stage + kRopeOff + wave_u * 2048 + q * 1024);
+      lds_dma16<0>(src_rope, row * (kDr * 2) + (((lane & 7) ^ rope_swz(t)) << 4));
+    }
+    issue_stage = (issue_stage + 1 == STAGES) ? 0 : issue_stage + 1;
   };
 
   // ---- per-lane LDS read offsets inside a stage.  The swizzle is an XOR on the chunk index, so the
@@ -378,13 +436,17 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
     }
   }
 
-  float m_run[2] = {kNegBig, kNegBig};
+  // Running reference maximum of each head column (log2 domain) and, as 16-register vectors, its negative:
+  // the first score MFMA of a tile takes that vector as its accumulator input, so the scores come out of
+  // the matrix pipe already relative to the reference and feed exp2 directly.  (GLA: the two waves whose
+  // partial scores are added each start from half of it; halving is exact.)
+  float m_run[2] = {0.f, 0.f};
+  f32x16 negm[2];
   // Row sums l = sum_t P[t][head] come from the matrix pipe as well: one 16x16x32 MFMA per P^T operand
   // with a 0/1 selector as A.  Read as a 16x16x32 B operand, lane (16 b + c) of a P^T register holds head
   // c + 16 (b & 1), eight tokens; selector row 4 q has ones where (b & 1) == (q & 1), every other row is
   // zero, so accumulator register 0 of lane (16 q + c) ends up with the sum over the operand's 16 tokens
   // of that lane's own head, both token halves included.
-  f32x4 lacc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
   bf16x8 row_sel;
   {
     const int i = lane & 15, b = lane >> 4;
@@ -392,14 +454,6 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
 #pragma unroll
     for (int e = 0; e < 8; ++e) row_sel[e] = v;
   }
-  f32x16 zacc[4][2];
-#pragma unroll
-  for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-    for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) zacc[mt][nt][i] = 0.f;
-
   const float sc = p.scale_log2;
 
   typedef const __attribute__((address_space(3))) bf16x8* lds_bf16x8_ptr;
@@ -424,53 +478,116 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
     va[ss][mt] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
   };
   // Column maxima.  In the accumulator layout a lane holds 16 of the 32 token rows of its head column
-  // and the lane 32 away holds the other 16.  max4 folds four more rows into a running maximum;
+  // and the lane 32 away holds the other 16.  max8 folds eight more rows into a running maximum;
   // cross_max finishes both head tiles at once with two half-wave swaps (v_permlane32_swap exchanges
   // the upper half of its first operand with the lower half of its second).
   // (v_max3 through asm: the library fmaxf would first canonicalise every operand, one more
-  // instruction each.  Its operands are score accumulators whose MFMAs retired several MFMAs earlier.)
-  auto max3 = [&](float a, float b, float c) {
-    float r;
-    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
-    return r;
+  // instruction each; four of them in one statement, because the compiler separates dependent asm
+  // statements by a wait state each.  The operands are score accumulators whose MFMAs retired several
+  // MFMAs earlier.)
+  auto max8 = [&](float mx, const f32x16& sv, int r) {
+    float res;
+    asm("v_max3_f32 %0, %1, %2, %3\n\t"
+        "v_max3_f32 %0, %0, %4, %5\n\t"
+        "v_max3_f32 %0, %0, %6, %7\n\t"
+        "v_max3_f32 %0, %0, %8, %9"
+        : "=&v"(res)
+        : "v"(mx), "v"(sv[r]), "v"(sv[r + 1]), "v"(sv[r + 2]), "v"(sv[r + 3]), "v"(sv[r + 4]), "v"(sv[r + 5]),
+          "v"(sv[r + 6]), "v"(sv[r + 7]));
+    return res;
   };
-  auto max4 = [&](float mx, const f32x16& sv, int r) { return max3(max3(mx, sv[r], sv[r + 1]), sv[r + 2], sv[r + 3]); };
   auto swap_halves = [&](float& a, float& b) {
     asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
   };
   auto cross_max = [&](float& mx0, float& mx1) {
     swap_halves(mx0, mx1);            // mx0 = {tile 0 lower, tile 1 lower}, mx1 = {tile 0 upper, tile 1 upper}
-    mx0 = max3(mx0, mx1, mx1);        // lanes 0..31: column maxima of head tile 0, lanes 32..63: of head tile 1
+    asm("v_max_f32 %0, %0, %1" : "+v"(mx0) : "v"(mx1));   // lanes 0..31: maxima of head tile 0, 32..63: of head tile 1
     mx1 = mx0;
     swap_halves(mx0, mx1);            // mx0 = tile 0 maxima in both halves, mx1 = tile 1 maxima in both halves
   };
   auto col_max2 = [&](const f32x16& s0, const f32x16& s1, float& mx0, float& mx1) {
-    mx0 = max4(max4(max4(max4(s0[0], s0, 0), s0, 4), s0, 8), s0, 12);
-    mx1 = max4(max4(max4(max4(s1[0], s1, 0), s1, 4), s1, 8), s1, 12);
+    mx0 = max8(max8(s0[0], s0, 0), s0, 8);
+    mx1 = max8(max8(s1[0], s1, 0), s1, 8);
     cross_max(mx0, mx1);
   };
-  auto rescale = [&](int nt, float m_new) {
-    const float alpha = __builtin_amdgcn_exp2f(m_run[nt] - m_new);   // 1 for heads that keep their max
+  // Operands of the PV MFMAs (transposed value tiles, bf16 probabilities).  They live at function scope
+  // because of a hardware rule the compiler cannot apply to asm: an MFMA goes on reading its source
+  // registers for a while after it has issued, so nothing may be written to them for the next few MFMAs
+  // (measured: exponentials landing in a K operand two instructions after its last score MFMA corrupted
+  // that MFMA's result).  hold() marks a register as still in use at the point where it is written: the
+  // allocator cannot hand it to another value before that.  Every asm MFMA's source is held until at
+  // least four MFMAs after the instruction that reads it last, across step boundaries too.
+  bf16x8 va[2][4], pb0[2], pb1[2];
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) zacc[mt][nt][i] *= alpha;
-    lacc[nt][0] *= alpha;
-    m_run[nt] = m_new;
+  for (int e = 0; e < 8; ++e) {
+    const __bf16 zero = (__bf16)0.0f;
+    va[1][2][e] = zero; va[1][3][e] = zero; pb0[1][e] = zero; pb1[1][e] = zero;
+  }
+  acc_zero(pb0[1]);
+  auto hold = [&](const bf16x8& x) { asm volatile("" : : "v"(x)); };
+  auto settle_acc = [&]() {   // (the operands of the last PV MFMAs stay put meanwhile)
+    asm volatile("s_nop 15\n\ts_nop 15" : : "v"(va[1][2]), "v"(va[1][3]), "v"(pb0[1]), "v"(pb1[1]) : MLRA_ACC_CLOBBERS);
   };
-  // P^T = 2^(s*sc - m) for two consecutive accumulator rows of head tile nt (prob_exp) and the rounding
-  // to bf16 into the PV B operand (prob_pack): two pieces, so that they can sit behind different MFMAs.
-  auto prob_exp = [&](int nt, const f32x16& sv, int r, float& p0, float& p1) {
-    const float neg_m = -m_run[nt];
-    p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[r], sc, neg_m));
-    p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[r + 1], sc, neg_m));
+  // Moves the reference maximum of head tile nt up by d >= 0 (per lane: 0 for heads that keep theirs):
+  // the history (Z, l) is weighted down by 2^-d, and the scores of the next tile, which the matrix pipe
+  // has already produced relative to the old reference, are shifted.  (Rare; call settle_acc first.)
+  auto rescale = [&](auto nt_tag, float d, f32x16& next_scores) {
+    constexpr int nt = decltype(nt_tag)::value;
+    const float alpha = __builtin_amdgcn_exp2f(-d);
+    acc_scale<16 * (0 + nt), 16>(alpha);
+    acc_scale<16 * (2 + nt), 16>(alpha);
+    acc_scale<16 * (4 + nt), 16>(alpha);
+    acc_scale<16 * (6 + nt), 16>(alpha);
+    acc_scale<128 + 4 * nt, 1>(alpha);
+    asm volatile("s_nop 7" : : : MLRA_ACC_CLOBBERS);   // the register writes above precede the next MFMA that reads them
+    const float dh = GLA ? 0.5f * d : d;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      next_scores[i] -= d;
+      negm[nt][i] -= dh;
+    }
+    m_run[nt] += d;
+    asm volatile("s_nop 7" : "+v"(negm[nt]));   // written just now, read by the next step's first score MFMA
+  };
+  // P^T = 2^score for two consecutive accumulator rows of a head tile (the scores are already relative to
+  // the reference maximum) and their rounding to bf16 into the PV B operand: two pieces, so that the
+  // rounding can sit one MFMA after the exponentials it consumes.
+  auto prob_exp = [&](const f32x16& sv, int r, float& p0, float& p1) {
+    p0 = __builtin_amdgcn_exp2f(sv[r]);
+    p1 = __builtin_amdgcn_exp2f(sv[r + 1]);
     asm volatile("" : "+v"(p0), "+v"(p1));   // computed here, not sunk to the first use
   };
-  // (asm, so that the sums and the selector live in accumulation registers while every other MFMA result
-  // stays in the ordinary file.  The operands were written by VALU instructions many cycles earlier; the
-  // next access to acc is the same instruction eight 32x32 MFMAs later, or the step's end.)
-  auto row_sum_mfma = [&](f32x4& acc, const bf16x8& pt) {
-    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "a"(row_sel), "v"(pt));
+  // Row sums and Z^T += V^T P^T on the fixed accumulation registers (see acc_pv_mfma).  A tile is read and
+  // written only by its own MFMAs (eight MFMAs apart); the A operand comes from LDS reads that the compiler
+  // waits for (it sees the register dependence), the B operand from conversions issued at least eight
+  // MFMAs earlier.
+  auto row_sum_mfma = [&](int nt, const bf16x8& pt) {
+    if (nt == 0) acc_row_sum_mfma<0>(row_sel, pt); else acc_row_sum_mfma<1>(row_sel, pt);
+  };
+  auto pv_mfma = [&](int mt, int nt, const bf16x8& vt, const bf16x8& pt) {
+    switch (2 * mt + nt) {   // (a constant once the step is unrolled)
+      case 0: acc_pv_mfma<0>(vt, pt); break;
+      case 1: acc_pv_mfma<1>(vt, pt); break;
+      case 2: acc_pv_mfma<2>(vt, pt); break;
+      case 3: acc_pv_mfma<3>(vt, pt); break;
+      case 4: acc_pv_mfma<4>(vt, pt); break;
+      case 5: acc_pv_mfma<5>(vt, pt); break;
+      case 6: acc_pv_mfma<6>(vt, pt); break;
+      default: acc_pv_mfma<7>(vt, pt); break;
+    }
+  };
+  // S^T += K Q^T for one 32-token x 32-head tile and 16 channels.  asm, so that the register classes are
+  // fixed: the K operand and the scores in ordinary registers, the query operand in the accumulation file
+  // (left to itself the allocator spreads LDS results over both files and then has no accumulation
+  // registers left for the queries).  score_first starts a tile's chain from minus the reference maximum.
+  // The scores are next read eight or more MFMAs after the chain's last instruction (column maxima) and a
+  // whole step later (exponentials), so no wait is needed here; the GLA form, which stores them to LDS at
+  // once, waits explicitly.
+  auto score_mfma = [&](f32x16& acc, const bf16x8& kt, const bf16x8& qt) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(kt), "a"(qt));
+  };
+  auto score_first = [&](f32x16& acc, const bf16x8& kt, const bf16x8& qt, const f32x16& init) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(acc) : "v"(kt), "a"(qt), "v"(init));
   };
   auto prob_pack = [&](int r, float p0, float p1, bf16x8 (&pb)[2]) {
     bf16x2 pp = {(__bf16)p0, (__bf16)p1};
@@ -488,34 +605,48 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
 
   // ---- prologue: every stage gets a tile; scores and column maxima of tile 0; K operands of tile 1 ----
   bf16x8 qreg[2][12];
-  for (int jj = 0; jj < STAGES - kQStages && jj < ntiles; ++jj) issue_tile(jj);
+  issue_last_tile();
+  for (int jj = 1; jj < STAGES - kQStages && jj < ntiles; ++jj) issue_tile();
   if (GLA && tid < 4) ((float*)(smem + STAGES * kStageB))[tid] = 0.f;   // the zeros some RoPE reads below take
   // queries landed (they are older than the tile loads; vector-memory operations retire in order) ...
   if (ntiles >= STAGES - kQStages) wait_vmcnt<kLoadsTile * (STAGES - kQStages)>(); else wait_vmcnt<0>();
   __builtin_amdgcn_s_barrier();   // ... in every wave's share
+  // The factor tau * log2(e) goes into the queries, once, so that the matrix pipe delivers scores in the
+  // log2 domain: each query element is multiplied in fp32 and rounded to bf16 again (queries that arrive
+  // already multiplied, scale_log2 == 1, go straight from LDS into the accumulation registers).
+  const bool q_ready = sc == 1.0f;
 #pragma unroll
   for (int nt = 0; nt < 2; ++nt) {
     const int row = hw * 64 + nt * 32 + c32;                       // q_abs row of this lane's head column
     const int rrow = PAIRED ? nt * 32 + c32 : row;                 // its RoPE row
+    unsigned qaddr[12];
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      const unsigned addr = q_lds + row * (kDcb * 2) + (((2 * ks + g) ^ (row & 15)) << 4);
-      asm volatile("ds_read_b128 %0, %1" : "=a"(qreg[nt][ks]) : "v"(addr) : "memory");
-    }
+    for (int ks = 0; ks < 8; ++ks) qaddr[ks] = q_lds + row * (kDcb * 2) + (((2 * ks + g) ^ (row & 15)) << 4);
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
       const unsigned addr = q_lds + kHeadsWG * (kDcb * 2) + rrow * (kDr * 2) + (((2 * ks + g) ^ ((rrow >> 1) & 7)) << 4);
       // GLA: the RoPE channels are split between the two waves whose partial scores are added, so that
       // the RoPE term is counted once; the other wave's channels are read from 16 bytes of zeros
-      const unsigned src = (!GLA || (ks >> 1) == hw) ? addr : lds_base + STAGES * kStageB;
-      asm volatile("ds_read_b128 %0, %1" : "=a"(qreg[nt][8 + ks]) : "v"(src) : "memory");
+      qaddr[8 + ks] = (!GLA || (ks >> 1) == hw) ? addr : lds_base + STAGES * kStageB;
+    }
+    bf16x8 raw[12];
+#pragma unroll
+    for (int ks = 0; ks < 12; ++ks) raw[ks] = *(lds_bf16x8_ptr)(size_t)qaddr[ks];
+    if (!q_ready) {
+#pragma unroll
+      for (int ks = 0; ks < 12; ++ks)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) raw[ks][e] = (__bf16)((float)raw[ks][e] * sc);
+    }
+#pragma unroll
+    for (int ks = 0; ks < 12; ++ks) {
+      asm volatile("" : "+a"(raw[ks]));   // into the accumulation file, where the score MFMAs read it
+      qreg[nt][ks] = raw[ks];
     }
   }
-  // the reads above are asm, invisible to the compiler's wait counts: wait for them here (the tile loads
-  // may stay in flight), then let every wave finish before the stages under the queries are refilled
-  wait_vm_lgkm<63>();
+  // every wave has its queries in registers before the stages under them are refilled
   __builtin_amdgcn_s_barrier();
-  for (int jj = STAGES - kQStages; jj < STAGES && jj < ntiles; ++jj) issue_tile(jj);
+  for (int jj = STAGES - kQStages; jj < STAGES && jj < ntiles; ++jj) issue_tile();
   if (ntiles >= STAGES) wait_vmcnt<kLoadsTile * (STAGES - 2)>(); else wait_vmcnt<0>();
   __builtin_amdgcn_s_barrier();   // tiles 0 and 1 landed for every wave
   f32x16 sa0, sa1, sb0, sb1;
@@ -543,7 +674,8 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
       __syncthreads();
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const f32x4 x0 = xb[((wave ^ 1) * 8 + i) * 64 + lane], x1 = xb[((wave ^ 1) * 8 + 4 + i) * 64 + lane];
+        f32x4 x0 = xb[((wave ^ 1) * 8 + i) * 64 + lane], x1 = xb[((wave ^ 1) * 8 + 4 + i) * 64 + lane];
+        asm volatile("" : "+v"(x0), "+v"(x1));
 #pragma unroll
         for (int e = 0; e < 4; ++e) { sa0[4 * i + e] += x0[e]; sa1[4 * i + e] += x1[e]; }
       }
@@ -551,8 +683,19 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
     }
     float mx0, mx1;
     col_max2(sa0, sa1, mx0, mx1);
-    m_run[0] = mx0 * sc;
-    m_run[1] = mx1 * sc;
+    m_run[0] = mx0;
+    m_run[1] = mx1;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      sa0[i] -= mx0;
+      sa1[i] -= mx1;
+      negm[0][i] = GLA ? -0.5f * mx0 : -mx0;
+      negm[1][i] = GLA ? -0.5f * mx1 : -mx1;
+    }
+    // Rows past the end of the ragged tile hold copies of its last valid row: their scores equal a valid
+    // score, so the maxima above were right without a mask (and finite even for a wave none of whose rows
+    // exists); their probabilities are what has to vanish.
+    if (nvalid_last < kTile) { mask_tail(sa0); mask_tail(sa1); }
     __builtin_amdgcn_sched_barrier(0);
     load_k(1 % STAGES, ka);   // (a stale stage if the chunk has a single tile: those scores are never used)
   }
@@ -566,46 +709,43 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
   //            tile j+STAGES into the stage tile j leaves, K operands of tile j+2, column maxima of
   //            tile j+1.
   // The barrier says two things: tile j+2 is visible to every wave, and every wave has finished its LDS
-  // reads of tile j (V, this step) and tile j+1 (K, previous step).  FAST steps issue a tile that is
-  // known to exist and to be full, so they are straight-line code; the last steps of a chunk run the
-  // generic form.  sched_barrier(0) pins the interleaving. ----
+  // reads of tile j (V, this step) and tile j+1 (K, previous step).  (Tiles are counted in processing
+  // order: tile 0 is the chunk's last one.)  Issuing steps load a tile that exists and is full, so they are
+  // straight-line code; the last STAGES steps of a chunk issue nothing.  sched_barrier(0) pins the
+  // interleaving. ----
   int st_cur = 0;
-  auto step = [&](auto fast_tag, int j, f32x16& c0, f32x16& c1, f32x16& n0, f32x16& n1) {
-    constexpr bool FAST = decltype(fast_tag)::value;
+  auto step = [&](auto issue_tag, int j, f32x16& c0, f32x16& c1, f32x16& n0, f32x16& n1) {
+    constexpr bool ISSUE = decltype(issue_tag)::value;   // tile j + STAGES exists (and is a full one)
     const bool has_next = j + 1 < ntiles;
-    // Rows past the end of a ragged last tile hold copies of its last valid row: their scores equal a
-    // valid score, so the column maxima (taken one step earlier) were right without a mask; their
-    // probabilities are what has to vanish.
-    if (!FAST && j == ntiles - 1 && nvalid_last < kTile) { mask_tail(c0); mask_tail(c1); }
     const int st_k2 = (st_cur + 2 >= STAGES) ? st_cur + 2 - STAGES : st_cur + 2;   // stage of tile j+2
 
-    bf16x8 va[2][4], pb0[2], pb1[2];
     __builtin_amdgcn_sched_barrier(0);
-    // ---- block A: 24 score MFMAs.  MFMA i < 16 carries the exponentials of probability pair i (pairs
-    // 0..7: head tile 0, 8..15: head tile 1); MFMA 16+q carries the bf16 packing of pairs 2q, 2q+1 and
-    // the LDS transpose reads of V operand q.
-#pragma unroll
-    for (int i = 0; i < 16; ++i) { n0[i] = 0.f; n1[i] = 0.f; }
-    float pr[32];
+    // ---- block A: 24 score MFMAs; the first of each head tile starts from minus the reference maximum.
+    // MFMA i < 16 carries the exponentials of probability pair i (pairs 0..7: head tile 0, 8..15: head
+    // tile 1) and the bf16 rounding of pair i-1; MFMA 16+q carries the LDS transpose reads of V operand q.
+    float pr[4];
 #pragma unroll
     for (int i = 0; i < 24; ++i) {
       const int ks = i >> 1;
-      if ((i & 1) == 0) n0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[0][ks], n0, 0, 0, 0);
-      else n1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[1][ks], n1, 0, 0, 0);
-      // keeps ka[0] alive past the two MFMAs whose accumulator input is the constant 0, so that the
-      // allocator cannot place their destination on top of it (the build also scans for that)
-      if (i == 3) asm volatile("" : : "v"(ka[0]));
+      if (i == 0) score_first(n0, ka[0], qreg[0][0], negm[0]);
+      else if (i == 1) score_first(n1, ka[0], qreg[1][0], negm[1]);
+      else if ((i & 1) == 0) score_mfma(n0, ka[ks], qreg[0][ks]);
+      else score_mfma(n1, ka[ks], qreg[1][ks]);
+      // sources of earlier MFMAs that may be reused from here on (see hold above): the PV operands of the
+      // previous step's last MFMAs, and each K operand four MFMAs after the pair that read it
+      if (i == 3) { hold(va[1][2]); hold(va[1][3]); hold(pb0[1]); hold(pb1[1]); }
+      if (i >= 5 && (i & 1) == 1) hold(ka[(i >> 1) - 2]);
       if (i < 16) {
-        if (i < 8) prob_exp(0, c0, 2 * i, pr[2 * i], pr[2 * i + 1]);
-        else prob_exp(1, c1, 2 * (i - 8), pr[2 * i], pr[2 * i + 1]);
+        if (i < 8) prob_exp(c0, 2 * i, pr[2 * (i & 1)], pr[2 * (i & 1) + 1]);
+        else prob_exp(c1, 2 * (i - 8), pr[2 * (i & 1)], pr[2 * (i & 1) + 1]);
+      }
+      if (i >= 1 && i <= 16) {
+        const int pi = i - 1;   // the pair whose exponentials went out behind the previous MFMA
+        if (pi < 8) prob_pack(2 * pi, pr[2 * (pi & 1)], pr[2 * (pi & 1) + 1], pb0);
+        else prob_pack(2 * (pi - 8), pr[2 * (pi & 1)], pr[2 * (pi & 1) + 1], pb1);
       }
       if (i >= 16) {
         const int q = i - 16;
-#pragma unroll
-        for (int pi = 2 * q; pi < 2 * q + 2; ++pi) {
-          if (pi < 8) prob_pack(2 * pi, pr[2 * pi], pr[2 * pi + 1], pb0);
-          else prob_pack(2 * (pi - 8), pr[2 * pi], pr[2 * pi + 1], pb1);
-        }
         load_v_part(st_cur, q >> 2, q & 3, va);
       }
       __builtin_amdgcn_sched_barrier(0);
@@ -615,6 +755,7 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
     // stores wait for the last score MFMA); the partner's are added behind MFMAs 2..5 below
     f32x4* const xbuf = (f32x4*)(smem + STAGES * kStageB);   // [4 waves][8][64 lanes] x 16 bytes
     if (GLA) {
+      asm volatile("s_nop 15\n\ts_nop 15" : "+v"(n0), "+v"(n1));   // the last score MFMAs have retired
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         xbuf[(wave * 8 + i) * 64 + lane] = f32x4{n0[4 * i], n0[4 * i + 1], n0[4 * i + 2], n0[4 * i + 3]};
@@ -626,71 +767,98 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
 #pragma unroll
     for (int m = 0; m < 16; ++m) {
       const int ss = m >> 3, mt = (m >> 1) & 3;
-      if ((m & 1) == 0) zacc[mt][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[ss][mt], pb0[ss], zacc[mt][0], 0, 0, 0);
-      else zacc[mt][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[ss][mt], pb1[ss], zacc[mt][1], 0, 0, 0);
+      if ((m & 1) == 0) pv_mfma(mt, 0, va[ss][mt], pb0[ss]);
+      else pv_mfma(mt, 1, va[ss][mt], pb1[ss]);
       if (m == 0 || m == 8) {
-        row_sum_mfma(lacc[0], pb0[ss]);
-        row_sum_mfma(lacc[1], pb1[ss]);
+        row_sum_mfma(0, pb0[ss]);
+        row_sum_mfma(1, pb1[ss]);
       }
       if (m == 1) {
         // this wave's LDS reads of V(j) have returned (so has everything older) before it tells the
         // others that the stage may be overwritten
-        if (FAST || j + STAGES - 1 <= ntiles - 1) wait_vm_lgkm<kLoadsTile * (STAGES - 3)>(); else wait_vm_lgkm<0>();
+        // (while tiles are still being issued, STAGES - 3 of them may stay in flight behind tile j+2; the
+        // last steps of a chunk simply wait for everything that is left)
+        if (ISSUE) wait_vm_lgkm<kLoadsTile * (STAGES - 3)>(); else wait_vm_lgkm<0>();
         __builtin_amdgcn_s_barrier();
-        if (FAST) issue_begin(j + STAGES);
-        else if (j + STAGES < ntiles) issue_tile(j + STAGES);
+        if (ISSUE) issue_begin();
       }
-      if (FAST && m >= 2 && m < 2 + kLoadsTile / 2) { issue_full_part(2 * (m - 2)); issue_full_part(2 * (m - 2) + 1); }
-      if (FAST && m == 2 + kLoadsTile / 2) issue_end();
+      if (ISSUE && m >= 2 && m < 2 + kLoadsTile / 2) { issue_full_part(2 * (m - 2)); issue_full_part(2 * (m - 2) + 1); }
+      if (ISSUE && m == 2 + kLoadsTile / 2) issue_end();
       // (the last K read is three MFMAs from the end of the step: the first wait of the next step, which
       // covers every LDS read because a scalar load is in flight, then finds them all returned)
       if (GLA && m >= 2 && m <= 5) {
         // partner = the wave with the other channel half and the same token half (the barrier behind MFMA 1
         // made its stores visible); after MFMA 5 every wave has its sums and the buffer may be rewritten
         const f32x4* px = xbuf + ((wave ^ 1) * 8 + 2 * (m - 2)) * 64 + lane;
-        const f32x4 x0 = px[0], x1 = px[64];
+        f32x4 x0 = px[0], x1 = px[64];
+        asm volatile("" : "+v"(x0), "+v"(x1));   // ordinary registers (the additions below cannot read the other file)
         f32x16& dst = (m < 4) ? n0 : n1;
         const int r0 = 8 * ((m - 2) & 1);
 #pragma unroll
         for (int e = 0; e < 4; ++e) { dst[r0 + e] += x0[e]; dst[r0 + 4 + e] += x1[e]; }
         if (m == 5) __builtin_amdgcn_s_barrier();
       }
+      if (m == 1) hold(ka[10]);
+      if (m == 3) hold(ka[11]);
+      if (m >= 5 && m <= 11 && (m & 1) == 1) hold(va[0][(m - 5) >> 1]);   // last read by MFMA m - 4
+      if (m == 13) hold(va[1][0]);
+      if (m == 15) hold(va[1][1]);
+      if (m == 10) hold(pb0[0]);
+      if (m == 11) hold(pb1[0]);
       if (m >= 2 && m <= 13) load_k_part(st_k2, m - 2, ka);
-      if (m == 6) mx0 = max4(max4(n0[0], n0, 0), n0, 4);
-      if (m == 8) mx0 = max4(max4(mx0, n0, 8), n0, 12);
-      if (m == 10) mx1 = max4(max4(n1[0], n1, 0), n1, 4);
-      if (m == 12) mx1 = max4(max4(mx1, n1, 8), n1, 12);
+      if (m == 6) mx0 = max8(n0[0], n0, 0);
+      if (m == 8) mx0 = max8(mx0, n0, 8);
+      if (m == 10) mx1 = max8(n1[0], n1, 0);
+      if (m == 12) mx1 = max8(mx1, n1, 8);
       if (m == 14) cross_max(mx0, mx1);
       __builtin_amdgcn_sched_barrier(0);
     }
-    const float cand0 = mx0 * sc, cand1 = mx1 * sc;
-    const bool need0 = has_next && cand0 > m_run[0] + kLazy;
-    const bool need1 = has_next && cand1 > m_run[1] + kLazy;
+    // the maxima are relative to the reference: it moves only when a head's scores outgrow it by 2^kLazy
+    const bool need0 = has_next && mx0 > kLazy;
+    const bool need1 = has_next && mx1 > kLazy;
     if (__any(need0 || need1)) {
-      rescale(0, need0 ? cand0 : m_run[0]);
-      rescale(1, need1 ? cand1 : m_run[1]);
+      settle_acc();
+      rescale(std::integral_constant<int, 0>{}, need0 ? mx0 : 0.f, n0);
+      rescale(std::integral_constant<int, 1>{}, need1 ? mx1 : 0.f, n1);
     }
     st_cur = (st_cur + 1 == STAGES) ? 0 : st_cur + 1;
   };
   {
-    const std::integral_constant<bool, true> fast;
-    const std::integral_constant<bool, false> generic;
+    const std::integral_constant<bool, true> issuing;
+    const std::integral_constant<bool, false> draining;
+    // steps 0 .. ntiles - STAGES - 1 issue a tile each, the last STAGES steps only drain the pipeline
+    const int n_issue = ntiles > STAGES ? ntiles - STAGES : 0;
     int j = 0;
-    // a FAST step j issues tile j + STAGES, which must not be the (possibly ragged) last tile
-    for (; j + 1 + STAGES <= ntiles - 2; j += 2) {
-      step(fast, j, sa0, sa1, sb0, sb1);
-      step(fast, j + 1, sb0, sb1, sa0, sa1);
+    for (; j + 2 <= n_issue; j += 2) {
+      step(issuing, j, sa0, sa1, sb0, sb1);
+      step(issuing, j + 1, sb0, sb1, sa0, sa1);
+    }
+    if (j < n_issue) {   // an odd number of issuing steps: one more, then the score registers trade places
+      step(issuing, j, sa0, sa1, sb0, sb1);
+      ++j;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) { sa0[i] = sb0[i]; sa1[i] = sb1[i]; }
     }
     for (; j < ntiles; j += 2) {
-      step(generic, j, sa0, sa1, sb0, sb1);
-      if (j + 1 < ntiles) step(generic, j + 1, sb0, sb1, sa0, sa1);
+      step(draining, j, sa0, sa1, sb0, sb1);
+      if (j + 1 < ntiles) step(draining, j + 1, sb0, sb1, sa0, sa1);
     }
   }
 
   // ---- merge the two token halves of each head half through LDS, write the chunk's partial ----
+  {
+  settle_acc();   // the last PV MFMAs have retired before ordinary code reads the accumulators
+  // (the lane's indices are derived again from a thread id the compiler cannot connect to the first one:
+  // otherwise it keeps a dozen of them alive across the main loop, spilled to scratch memory)
+  int tid_again = threadIdx.x;
+  asm volatile("" : "+v"(tid_again));
+  const int tid = tid_again, wave = tid >> 6, lane = tid & 63, hw = wave & 1, tw = wave >> 1, g = lane >> 5,
+            c32 = lane & 31;
+  const int blk = (PAIRED && !GLA) ? blk0 + hw : blk0;
+  const int wave_head0 = PAIRED ? hgrp * 64 : hgrp * kHeadsWG + hw * 64;
   float l_run[2];
-#pragma unroll
-  for (int nt = 0; nt < 2; ++nt) l_run[nt] = lacc[nt][0];   // already summed over both token halves of the wave
+  l_run[0] = acc_read<128>();   // (already summed over both token halves of the wave)
+  l_run[1] = acc_read<132>();
   __builtin_amdgcn_s_barrier();     // every wave is past its last tile read: the stages can be reused
   float* mbuf = (float*)smem;                 // [4 waves][64 heads]
   float* lbuf = mbuf + 256;
@@ -703,7 +871,7 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
     }
   }
   __syncthreads();
-  float m_out[2], l_out[2];
+  float m_out[2], l_out[2], w_mine[2];
 #pragma unroll
   for (int nt = 0; nt < 2; ++nt) {
     const float mp = mbuf[(wave ^ 2) * 64 + nt * 32 + c32];
@@ -713,41 +881,52 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
     const float w_par = __builtin_amdgcn_exp2f(mp - ms);
     m_out[nt] = ms;
     l_out[nt] = l_run[nt] * w_own + lp * w_par;
-#pragma unroll
-    for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) zacc[mt][nt][i] *= w_own;
+    w_mine[nt] = w_own;
   }
+  // this wave's Z^T, four registers at a time, weighted for the merge of the two token halves
+  auto z4 = [&](auto nt_tag, auto mt_tag, auto r4_tag) {
+    constexpr int nt = decltype(nt_tag)::value;
+    f32x4 v = acc_read4<decltype(mt_tag)::value, nt, decltype(r4_tag)::value>();
+    const float w = w_mine[nt];
+    return f32x4{v[0] * w, v[1] * w, v[2] * w, v[3] * w};
+  };
+  // (compile-time loops over head tile, channel tile and register quad: the register names are immediates)
+  auto for_each_quad = [&](auto&& fn) {
+    auto quads = [&](auto nt_tag, auto mt_tag) {
+      fn(nt_tag, mt_tag, std::integral_constant<int, 0>{});
+      fn(nt_tag, mt_tag, std::integral_constant<int, 1>{});
+      fn(nt_tag, mt_tag, std::integral_constant<int, 2>{});
+      fn(nt_tag, mt_tag, std::integral_constant<int, 3>{});
+    };
+    auto tiles = [&](auto nt_tag) {
+      quads(nt_tag, std::integral_constant<int, 0>{});
+      quads(nt_tag, std::integral_constant<int, 1>{});
+      quads(nt_tag, std::integral_constant<int, 2>{});
+      quads(nt_tag, std::integral_constant<int, 3>{});
+    };
+    tiles(std::integral_constant<int, 0>{});
+    tiles(std::integral_constant<int, 1>{});
+  };
   auto zrow = [&](int nt, int mt, int r4) {
     return zbuf + (hw * 64 + nt * 32 + c32) * kZPitch + mt * 32 + r4 * 8 + g * 4;
   };
   if (tw == 1) {
-#pragma unroll
-    for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-      for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-          f32x4 v = {zacc[mt][nt][r4 * 4], zacc[mt][nt][r4 * 4 + 1], zacc[mt][nt][r4 * 4 + 2],
-                     zacc[mt][nt][r4 * 4 + 3]};
-          *(f32x4*)zrow(nt, mt, r4) = v;
-        }
+    for_each_quad([&](auto nt_tag, auto mt_tag, auto r4_tag) {
+      *(f32x4*)zrow(decltype(nt_tag)::value, decltype(mt_tag)::value, decltype(r4_tag)::value) = z4(nt_tag, mt_tag, r4_tag);
+    });
   }
   __syncthreads();
   if (tw == 0) {
-#pragma unroll
-    for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-      for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-          f32x4 v = *(f32x4*)zrow(nt, mt, r4);
-          v[0] += zacc[mt][nt][r4 * 4];
-          v[1] += zacc[mt][nt][r4 * 4 + 1];
-          v[2] += zacc[mt][nt][r4 * 4 + 2];
-          v[3] += zacc[mt][nt][r4 * 4 + 3];
-          *(f32x4*)zrow(nt, mt, r4) = v;
-        }
+    for_each_quad([&](auto nt_tag, auto mt_tag, auto r4_tag) {
+      f32x4* const row = (f32x4*)zrow(decltype(nt_tag)::value, decltype(mt_tag)::value, decltype(r4_tag)::value);
+      const f32x4 own = z4(nt_tag, mt_tag, r4_tag);
+      f32x4 v = *row;
+      v[0] += own[0];
+      v[1] += own[1];
+      v[2] += own[2];
+      v[3] += own[3];
+      *row = v;
+    });
     // (direct form: 1 / l of the row's head goes into the padding behind its 128 channels)
     if (p.direct && g == 0) {
 #pragma unroll
@@ -801,6 +980,7 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
         p.part_ml[(unit * p.h + head) * 2 + 1] = l_out[nt];
       }
     }
+  }
   }
 }
 
