@@ -30,7 +30,8 @@ def _args():
     ap.add_argument("--workload", default="C3", choices=["C2", "C3", "C4", "C5", "M2", "G2"])
     ap.add_argument("--copies", type=int, default=0, help="cache copies to rotate over (0 = enough for ~3 GB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--parity", action="store_true", help="also compare the GPU output with the oracle")
+    ap.add_argument("--parity", action="store_true",
+                    help="(kept for old command lines: the comparison with the oracle is always made with the CPU baseline)")
     ap.add_argument("--baselines", action="store_true",
                     help="C5 only: also time the GQA and MLA decode baselines on the same lengths and page table")
     ap.add_argument("--pre-attention", action="store_true",
@@ -41,6 +42,12 @@ def _args():
                          "the step appends only the newest one)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain 1 GiB device copies (reference dispatches for rocprofv3 byte counters)")
+    ap.add_argument("--max-settle", type=int, default=400,
+                    help="upper bound of the untimed settle phase (steps run before --warmup until the decode "
+                         "kernel's time has stopped falling: the chip raises its clocks over the first milliseconds "
+                         "of load); 0 switches it off")
+    ap.add_argument("--no-probes", action="store_true",
+                    help="skip the streaming-read ceiling and shader-clock probes (profiling runs)")
     return ap.parse_args()
 
 
@@ -79,18 +86,38 @@ def _cpu_baseline(inp, max_seconds=25.0):
                       f"{dt:.1f} s of fp64 numpy, scaled to the whole batch by token count"}, np.stack(outs)
 
 
+def _kernel_sources_digest():
+    """sha256 over the library's HIP sources and headers (what the counter profiles were measured on)."""
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    for path in sorted(glob.glob(os.path.join(ROOT, "paper_2603_02188_amd", "csrc", "*")) +
+                       glob.glob(os.path.join(ROOT, "include", "*.h"))):
+        h.update(os.path.basename(path).encode())
+        h.update(open(path, "rb").read())
+    return h.hexdigest()[:16]
+
+
 def _measured_traffic(workload):
     """HBM bytes per launch of the decode kernel from the committed rocprofv3 counter summary (FETCH_SIZE and
-    WRITE_SIZE runs, scaled by a plain copy of known size), or None if no summary covers this workload."""
+    WRITE_SIZE runs, scaled by a plain copy of known size).  The summary names the digest of the kernel
+    sources it was measured on: (None, reason) if no summary covers this workload or the sources changed."""
     path = os.path.join(ROOT, "profiles", f"decode_step_{workload}_counters.md")
+    value, digest = None, None
     try:
         for line in open(path):
+            if line.startswith("kernel sources digest:"):
+                digest = line.split(":", 1)[1].strip()
             cells = [c.strip() for c in line.strip().strip("|").split("|")]
             if len(cells) == 7 and cells[0].startswith("decode_mfma_kernel"):
-                return float(cells[6])
+                value = float(cells[6])
     except OSError:
-        pass
-    return None
+        return None, "no counter profile for this workload"
+    if value is None:
+        return None, "no decode kernel row in the counter profile"
+    if digest != _kernel_sources_digest():
+        return None, "the counter profile was measured on other kernel sources (digest %s)" % digest
+    return value, "profiles/decode_step_%s_counters.md" % workload
 
 
 def _time_us(fn, iters):
@@ -268,6 +295,27 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    # Untimed settle phase: the chip raises its clocks over the first milliseconds of load, so a run of a few
+    # steps would time that transient.  Steps run in batches of 20 until the decode kernel's own time (events on
+    # its launch) has not improved by 1 % for two batches in a row, or --max-settle steps have run.
+    settle_steps, settle_trace = 0, []
+    if a.max_settle > 0:
+        best, stale, batch_n = float("inf"), 0, 20
+        while settle_steps < a.max_settle:
+            mlra.mlra_kernel_timing_begin(batch_n)
+            for i in range(batch_n):
+                step(settle_steps + i)
+            torch.cuda.synchronize()
+            batch_ms = mlra.mlra_kernel_timing_end()[0]
+            settle_steps += batch_n
+            settle_trace.append(round(batch_ms * 1e3, 1))
+            if batch_ms < 0.99 * best:
+                best, stale = batch_ms, 0
+            else:
+                stale += 1
+                if stale >= 2:
+                    break
+
     for i in range(a.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -285,6 +333,23 @@ def main():
     torch.cuda.synchronize()
     main_ms, epi_ms, calls = mlra.mlra_kernel_timing_end()
 
+    # shader clock under this load: one wavefront on a second stream (default priority) counts shader cycles
+    # against the 100 MHz counter while a few more, untimed, steps run (it shares a SIMD with a decode
+    # workgroup, so these steps are not part of any figure)
+    shader_clock_ghz = None
+    if not a.no_probes:
+        clock_out = torch.zeros(2, dtype=torch.int64, device=dev)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        n_probe = max(10, min(a.steps, 50))
+        for i in range(n_probe):
+            if i == 2:
+                mlra.mlra_probe_shader_clock(clock_out, max(200, int(0.6 * (n_probe - 2) * ms_per_step * 1e3)), stream=side)
+            step(i)
+        torch.cuda.synchronize()
+        cyc, ticks = [int(v) for v in clock_out.cpu().tolist()]
+        shader_clock_ghz = cyc / (ticks * 10.0) if ticks > 0 else None
+
     # decode-attention-only latency (per-step samples with events on the launch stream)
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(a.steps)]
     for i, (e0, e1) in enumerate(evs):
@@ -293,6 +358,23 @@ def main():
         e1.record()
     torch.cuda.synchronize()
     dec = np.array([e0.elapsed_time(e1) for e0, e1 in evs]) * 1e3
+
+    # streaming-read ceiling of this machine: a plain read of the rotated cache copies (>= 3 GB, so the
+    # memory-side cache cannot serve it), best of three passes
+    stream_gbps = None
+    if not a.no_probes:
+        sink = torch.zeros(4096, dtype=torch.int32, device=dev)
+        bufs = [c.latent for c in caches]
+        total = sum(b.numel() * b.element_size() for b in bufs)
+        for _ in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for b in bufs:
+                mlra.mlra_probe_stream_read(b, sink, 4096)
+            e1.record()
+            torch.cuda.synchronize()
+            gbps = total / (e0.elapsed_time(e1) * 1e-3) / 1e9
+            stream_gbps = gbps if stream_gbps is None else max(stream_gbps, gbps)
 
     bytes_decode = rf.decode_bytes(inp.seq_lens, wl.h, wl.d_h, wl.n_blocks, wl.d_cb, wl.d_r, groups=wl.groups)
     if a.q_len > 1:   # the cache is shared by the queries of a sequence; queries and outputs are not
@@ -310,6 +392,7 @@ def main():
     kernel_bytes = bytes_decode["cache"] + bytes_decode["q_abs"] + bytes_decode["q_rope"]
     achieved = kernel_bytes / (main_ms * 1e-3) / 1e9 if main_ms > 0 else 0.0
 
+    traffic, traffic_note = _measured_traffic(a.workload)
     res = {
         "metric": "decode attention us/step, %s bf16 (append_kv + absorb_q + decode_attn)"
                   % ("GLA-2" if wl.groups == 2 and wl.n_blocks == 2 else "MLRA-2" if wl.groups == 2 else "MLRA-4"),
@@ -326,8 +409,12 @@ def main():
         "decode_attn_gbps": bytes_decode["total"] / (float(np.median(dec)) * 1e-6) / 1e9,
         "decode_attn_tflops": flops / (float(np.median(dec)) * 1e-6) / 1e12,
         "kernels_us": {"decode_main": main_ms * 1e3, "merge_upproj": epi_ms * 1e3, "calls": calls},
+        "settle_steps": settle_steps, "settle_decode_main_us": settle_trace,
+        "shader_clock_ghz_under_load": shader_clock_ghz,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": rf.HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / rf.HBM_PEAK_GBS, "traffic": _measured_traffic(a.workload),
+                     "frac": achieved / rf.HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_note,
+                     "stream_ceiling_gbps": stream_gbps,
+                     "frac_of_stream_ceiling": achieved / stream_gbps if stream_gbps else None,
                      "kernel": "mlra decode main kernel", "algorithmic_bytes": kernel_bytes,
                      "mfma_tflops": (flops - wl.batch * wl.h * 2.0 * (wl.n_blocks // wl.groups) * wl.d_cb * wl.d_h)
                      / (main_ms * 1e-3) / 1e12 if main_ms > 0 else 0.0},
@@ -357,9 +444,10 @@ def main():
     if not a.no_cpu_baseline and a.q_len == 1:
         base, ref = _cpu_baseline(inp)
         res["cpu_baseline"] = base
-        if a.parity:
-            got = out.to(torch.float64).cpu().numpy()[: ref.shape[0]]
-            res["max_rel_err_vs_oracle"] = float(np.max(np.abs(got - ref)) / np.max(np.abs(ref)))
+        # the sequences the oracle got through, element by element against the last step's output
+        got = out.to(torch.float64).cpu().numpy()[: ref.shape[0]]
+        res["max_rel_err_vs_oracle"] = float(np.max(np.abs(got - ref)) / np.max(np.abs(ref)))
+        res["max_rel_err_sequences"] = int(ref.shape[0])
     print(json.dumps(res))
 
 

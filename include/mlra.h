@@ -245,6 +245,17 @@ MLRA_API int gqa_decode_attn(const void* k_pool, const void* v_pool, const int32
 MLRA_API int mlra_kernel_timing_begin(int32_t max_calls);
 MLRA_API int mlra_kernel_timing_end(double* main_kernel_ms, double* epilogue_kernel_ms, int32_t* calls);
 
+/* Measurement probes (not part of the decode path).
+ * mlra_probe_stream_read: a plain streaming read of `bytes` bytes (device pointer, 16-byte aligned) by
+ *   `workgroups` workgroups of 256 threads; the XOR of the data is folded into sink[workgroup] (device,
+ *   `workgroups` dwords, owned by the caller) so that the reads are real.  Timed by the caller, it gives the
+ *   streaming-read ceiling of the machine the benchmark runs on, to set beside the 8 TB/s nameplate.
+ * mlra_probe_shader_clock: one wavefront counts shader cycles against the 100 MHz constant counter for about
+ *   spin_us microseconds and stores {cycles, 10 ns ticks} into out[0..1] (device, two int64): launched on a
+ *   second stream while other kernels run, it reads the shader clock the chip sustains under that load. */
+MLRA_API int mlra_probe_stream_read(const void* src, size_t bytes, uint32_t* sink, int32_t workgroups, void* stream);
+MLRA_API int mlra_probe_shader_clock(long long* out, int32_t spin_us, void* stream);
+
 /* Introspection aid (host logic only, touches no device memory and enqueues nothing): which kernels and
  * which context split a decode call of this shape takes.  Arguments as for the decode entry points: h is
  * the total number of query heads, groups is 1 for mlra_decode_attn / mla_decode_attn and 2 for

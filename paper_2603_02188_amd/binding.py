@@ -24,7 +24,7 @@ EXPORTS = ("mlra_strerror", "mlra_append_kv", "mlra_absorb_q", "mlra_decode_work
            "mlra2_decode_attn", "mlra_decode_attn_gated", "mlra_decode_multi_workspace_bytes", "mlra_decode_attn_multi",
            "mlra_pre_attention_workspace_bytes", "mlra_pre_attention",
            "gqa_decode_workspace_bytes", "gqa_decode_attn", "mlra_kernel_timing_begin",
-           "mlra_kernel_timing_end", "mlra_decode_plan_info")
+           "mlra_kernel_timing_end", "mlra_decode_plan_info", "mlra_probe_stream_read", "mlra_probe_shader_clock")
 
 
 class _CacheStruct(ctypes.Structure):
@@ -96,6 +96,10 @@ def load_library() -> ctypes.CDLL:
     lib.gqa_decode_attn.restype = ctypes.c_int
     lib.gqa_decode_attn.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp, f32, vp, i32, vp,
                                     sz, vp]
+    lib.mlra_probe_stream_read.restype = ctypes.c_int
+    lib.mlra_probe_stream_read.argtypes = [vp, sz, vp, i32, vp]
+    lib.mlra_probe_shader_clock.restype = ctypes.c_int
+    lib.mlra_probe_shader_clock.argtypes = [vp, i32, vp]
     lib.mlra_kernel_timing_begin.restype = ctypes.c_int
     lib.mlra_kernel_timing_begin.argtypes = [i32]
     lib.mlra_kernel_timing_end.restype = ctypes.c_int
@@ -435,3 +439,16 @@ def mlra_kernel_timing_end():
     _check(load_library().mlra_kernel_timing_end(ctypes.byref(a), ctypes.byref(b), ctypes.byref(n)),
            "mlra_kernel_timing_end")
     return a.value, b.value, n.value
+
+
+def mlra_probe_stream_read(src: torch.Tensor, sink: torch.Tensor, workgroups: int, stream=None) -> None:
+    """Plain streaming read of the whole tensor `src` (see include/mlra.h); sink: int32/uint32 [workgroups]."""
+    assert sink.numel() >= workgroups and sink.element_size() == 4
+    _check(load_library().mlra_probe_stream_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink),
+                                                 int(workgroups), _stream(stream)), "mlra_probe_stream_read")
+
+
+def mlra_probe_shader_clock(out: torch.Tensor, spin_us: int, stream=None) -> None:
+    """out: int64 [2] on the device; receives {shader cycles, 10 ns ticks} of a spin of about spin_us microseconds."""
+    assert out.dtype == torch.int64 and out.numel() >= 2
+    _check(load_library().mlra_probe_shader_clock(_ptr(out), int(spin_us), _stream(stream)), "mlra_probe_shader_clock")
