@@ -74,6 +74,18 @@ def _copy_scale(acc, counter):
     return COPY_KIB / (sum(big) / len(big))
 
 
+N_SIMD = 1024   # MI355X: 256 compute units x 4 SIMDs; SQ_VALU_MFMA_BUSY_CYCLES is summed over them
+N_SQ = 32       # ... and SQ_BUSY_CYCLES over the 32 shader engines (8 XCDs x 4), each counting the kernel's cycles
+
+
+def mfma_busy_fraction(mfma_busy_cycles: float, sq_busy_cycles: float) -> float:
+    """Share of the kernel's cycles in which a SIMD's matrix pipe is busy (chip average), from the two
+    counters as rocprofv3 reports them per dispatch."""
+    if sq_busy_cycles <= 0:
+        return 0.0
+    return (mfma_busy_cycles / N_SIMD) / (sq_busy_cycles / N_SQ)
+
+
 def counters_summary(fetch_root, write_root, sq_root=None):
     fetch, write = _per_kernel(fetch_root), _per_kernel(write_root)
     fs, ws = _copy_scale(fetch, "FETCH_SIZE"), _copy_scale(write, "WRITE_SIZE")
@@ -95,11 +107,21 @@ def counters_summary(fetch_root, write_root, sq_root=None):
     if sq_root:
         sq = _per_kernel(sq_root)
         names = sorted({c for k in sq for c in sq[k]})
-        out += ["", "| kernel | " + " | ".join(names) + " |", "|---|" + "---|" * len(names)]
+        derived = "SQ_VALU_MFMA_BUSY_CYCLES" in names and "SQ_BUSY_CYCLES" in names
+        head = names + (["matrix pipe busy (derived)"] if derived else [])
+        out += ["", "| kernel | " + " | ".join(head) + " |", "|---|" + "---|" * len(head)]
         for k in sq:
             if k == COPY_KERNEL or k.startswith("at::"):
                 continue
-            out.append(f"| {k} | " + " | ".join(f"{sum(sq[k][c]) / max(1, len(sq[k][c])):.4g}" for c in names) + " |")
+            mean = {c: sum(sq[k][c]) / max(1, len(sq[k][c])) for c in names if sq[k][c]}
+            cells = [f"{mean[c]:.4g}" if c in mean else "-" for c in names]
+            if derived:
+                cells.append(f"{mfma_busy_fraction(mean.get('SQ_VALU_MFMA_BUSY_CYCLES', 0.0), mean.get('SQ_BUSY_CYCLES', 0.0)):.2f}")
+            out.append(f"| {k} | " + " | ".join(cells) + " |")
+        if derived:
+            out += ["", f"matrix pipe busy = (SQ_VALU_MFMA_BUSY_CYCLES / {N_SIMD} SIMDs) / (SQ_BUSY_CYCLES / {N_SQ} "
+                        "shader engines): the share of the kernel's cycles during which a SIMD's matrix pipe is busy, "
+                        "averaged over the chip."]
     return "\n".join(out), traffic
 
 

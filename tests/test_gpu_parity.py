@@ -251,9 +251,8 @@ def test_mla_baseline_one_round_ragged_batch_is_cut_by_length():
     q_nope, q_rope, w_uk, w_uv = device_queries_weights(inp)
     q_abs = mlra.mlra_absorb_q(q_nope, w_uk)
     out = host(mlra.mla_decode_attn(cache, q_abs, q_rope, w_uv, wl.tau, out_dtype=torch.float32))
-    seqs = [0, 3, 17, 50, 99, 139, int(np.argmax(lens))]
-    ref = _mla_reference(inp, seqs=seqs)
-    err = max_rel_err(out[seqs], ref)
+    ref = _mla_reference(inp)
+    err = max_rel_err(out, ref)
     _say(f"[case] MLA baseline, 140 ragged sequences: max rel err {err:.3e}")
     assert np.isfinite(out).all() and err <= 1e-2 and np.all(out[3] == 0)
 

@@ -49,3 +49,11 @@ def test_copy_scale_uses_the_largest_copies():
 
 def test_short_kernel_names():
     assert ps._short(KNAME) == "decode_mfma_kernel<6, 0>"
+
+
+def test_mfma_busy_fraction_from_the_two_counters():
+    # a kernel of 281,600 cycles: every one of the 32 shader engines counts them; the 1024 SIMDs' matrix pipes
+    # are busy 172,800 cycles each -> 0.61 (the figures of the C3 counter profile)
+    assert ps.mfma_busy_fraction(172800.0 * 1024, 281600.0 * 32) == pytest.approx(0.6136, abs=1e-3)
+    assert ps.mfma_busy_fraction(1.769e8, 9.011e6) == pytest.approx(0.61, abs=0.01)
+    assert ps.mfma_busy_fraction(1.0, 0.0) == 0.0
