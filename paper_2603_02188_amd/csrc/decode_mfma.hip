@@ -927,8 +927,8 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
       v[3] += own[3];
       *row = v;
     });
-    // (direct form: 1 / l of the row's head goes into the padding behind its 128 channels)
-    if (p.direct && g == 0) {
+    // (bf16 rows: 1 / l of the row's head goes into the padding behind its 128 channels)
+    if (p.rows_bf16 && g == 0) {
 #pragma unroll
       for (int nt = 0; nt < 2; ++nt)
         zbuf[(hw * 64 + nt * 32 + c32) * kZPitch + kDcb] = l_out[nt] > 0.f ? 1.f / l_out[nt] : 0.f;
@@ -939,15 +939,17 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
   // heads of block blk0 then the same 64 heads of block blk0 + 1
   // (GLA: rows 64..127 are channels 128..255 of the same 64 heads of the one block)
   constexpr int kZRow = GLA ? 2 * kDcb : kDcb;   // channels of one partial row in the workspace
-  if (p.direct) {
-    // One chunk per sequence: nothing is left to merge, so the row leaves as the up-projection wants it,
-    // z * (1 / l) rounded to bf16 (the same two operations the merge kernel applies to a single partial).
+  if (p.rows_bf16) {
+    // The chunk's partial leaves normalised: z * (1 / l) rounded to bf16, with (m, l) beside it in fp32.  A
+    // convex combination of cache rows is no larger than they are, so bf16 holds it as well as it holds
+    // the cache; with one chunk per sequence the row is already what the up-projection consumes, with
+    // several the merge weighs the rows by 2^(m_k - m*) l_k.  Half the bytes of fp32 partials.
     bf16_t* zn = (bf16_t*)p.part_z;
     for (int idx = tid; idx < kHeadsWG * (kDcb / 8); idx += 256) {
       const int hl = idx / (kDcb / 8), f8 = idx % (kDcb / 8);
       const int row_blk = (PAIRED && !GLA) ? blk0 + (hl >> 6) : blk0;
       const int row_head = PAIRED ? hgrp * 64 + (hl & 63) : hgrp * kHeadsWG + hl;
-      const size_t row_unit = (size_t)seq * p.n_blocks + row_blk;
+      const size_t row_unit = ((size_t)seq * p.n_blocks + row_blk) * p.n_splits + split;
       if (row_head < p.h) {
         const float inv = zbuf[hl * kZPitch + kDcb];
         const f32x4 lo = *(const f32x4*)(zbuf + hl * kZPitch + f8 * 8), hi = *(const f32x4*)(zbuf + hl * kZPitch + f8 * 8 + 4);
@@ -960,15 +962,17 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
         *(bf16x8*)(zn + (row_unit * p.h + row_head) * kZRow + (GLA ? (hl >> 6) * kDcb : 0) + f8 * 8) = packed;
       }
     }
-  } else
-  for (int idx = tid; idx < kHeadsWG * (kDcb / 4); idx += 256) {
-    const int hl = idx / (kDcb / 4), f4 = idx % (kDcb / 4);
-    const int row_blk = (PAIRED && !GLA) ? blk0 + (hl >> 6) : blk0;
-    const int row_head = PAIRED ? hgrp * 64 + (hl & 63) : hgrp * kHeadsWG + hl;
-    const size_t row_unit = ((size_t)seq * p.n_blocks + row_blk) * p.n_splits + split;
-    if (row_head < p.h)
-      *(f32x4*)(p.part_z + (row_unit * p.h + row_head) * kZRow + (GLA ? (hl >> 6) * kDcb : 0) + f4 * 4) =
-          *(const f32x4*)(zbuf + hl * kZPitch + f4 * 4);
+  } else {
+    // (for the generic merge kernel, which takes shapes whose tables do not fit the MFMA epilogue's LDS: fp32, not normalised)
+    for (int idx = tid; idx < kHeadsWG * (kDcb / 4); idx += 256) {
+      const int hl = idx / (kDcb / 4), f4 = idx % (kDcb / 4);
+      const int row_blk = (PAIRED && !GLA) ? blk0 + (hl >> 6) : blk0;
+      const int row_head = PAIRED ? hgrp * 64 + (hl & 63) : hgrp * kHeadsWG + hl;
+      const size_t row_unit = ((size_t)seq * p.n_blocks + row_blk) * p.n_splits + split;
+      if (row_head < p.h)
+        *(f32x4*)(p.part_z + (row_unit * p.h + row_head) * kZRow + (GLA ? (hl >> 6) * kDcb : 0) + f4 * 4) =
+            *(const f32x4*)(zbuf + hl * kZPitch + f4 * 4);
+    }
   }
   const size_t unit = ((size_t)seq * p.n_blocks + blk) * p.n_splits + split;
   if (tw == 0 && g == 0 && !(GLA && hw == 1)) {   // (GLA: both channel halves hold the same m and l)
@@ -1060,7 +1064,7 @@ int launch_decode_gla(const DecodeArgs& a) {
   p.chunk = a.plan.chunk_tokens;
   p.batch = a.batch;
   p.scale_log2 = a.softmax_scale * 1.4426950408889634f;
-  p.direct = a.direct ? 1 : 0;
+  p.rows_bf16 = a.rows_bf16 ? 1 : 0;
   p.chunk_tab = a.balanced ? a.chunk_tab : nullptr;
   p.unit_tab = a.balanced ? a.unit_tab : nullptr;
   p.seq_order = nullptr;
@@ -1103,7 +1107,7 @@ int launch_decode_mfma(const DecodeArgs& a) {
   p.chunk = a.plan.chunk_tokens;
   p.batch = a.batch;
   p.scale_log2 = a.softmax_scale * 1.4426950408889634f;
-  p.direct = a.direct ? 1 : 0;
+  p.rows_bf16 = a.rows_bf16 ? 1 : 0;
   const int n_hg = paired ? (a.h + 63) / 64 : (a.h + kHeadsWG - 1) / kHeadsWG;
   const long long n_wg = (long long)a.plan.n_splits * (paired ? a.n_blocks / 2 : a.n_blocks) * n_hg * a.batch;
   if (n_wg <= 0 || n_wg > 0x7fffffffLL) return MLRA_ERR_SHAPE;

@@ -40,8 +40,8 @@ struct MfmaParams {
   int groups;                 // head groups (Eq. (6)): block b serves the h heads of group b / (n_blocks / groups);
                               // q_rope holds groups * h heads.  1 = every block serves every head (Eq. (5))
   float scale_log2;
-  int direct;                 // 1 (one chunk per sequence): part_z receives z / l rounded to bf16, [..][head][channels],
-                              // which is what the up-projection consumes; 0: fp32 partials for the merge
+  int rows_bf16;              // 1: part_z receives each chunk's partial as z / l rounded to bf16, [..][chunk][head][channels]
+                              // (what the MFMA epilogue merges); 0: fp32 partials, not normalised (generic merge, MLA)
 };
 
 // LDS has 64 four-byte banks; a 128-bit read is served 16 lanes at a time and a 64-bit transpose read

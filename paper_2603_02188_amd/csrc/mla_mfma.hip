@@ -394,7 +394,7 @@ int launch_mla_mfma(const DecodeArgs& a) {
   p.chunk = a.plan.chunk_tokens;
   p.batch = a.batch;
   p.scale_log2 = a.softmax_scale * 1.4426950408889634f;
-  p.direct = 0;
+  p.rows_bf16 = 0;
   const int n_hg = (a.h + kMHeads - 1) / kMHeads;
   const long long n_wg = (long long)a.plan.n_splits * n_hg * a.batch;
   if (n_wg <= 0 || n_wg > 0x7fffffffLL) return MLRA_ERR_SHAPE;

@@ -157,7 +157,7 @@ static int decode_common(const mlra_cache* c, int batch, int h, int groups, int 
   a.chunk_tab = (int32_t*)((char*)a.seq_order + align_up((size_t)batch * sizeof(int32_t), 256));
   a.unit_tab = (int32_t*)((char*)a.chunk_tab + align_up((size_t)batch * sizeof(int32_t), 256));
   a.balanced = false;
-  a.direct = false;
+  a.rows_bf16 = false;
   a.latent = c->latent;
   a.rope = c->rope;
   a.page_table = c->page_table;
@@ -188,10 +188,8 @@ static int decode_common(const mlra_cache* c, int batch, int h, int groups, int 
   if (a.plan.target_chunks > 0 && merge_upproj_mfma_supported(a) &&
       (decode_mfma_supported(a) || decode_gla_supported(a) || mla_mfma_supported(a)))
     a.balanced = launch_plan_chunks(a) == MLRA_OK;
-  // one chunk per sequence on the MFMA kernels: the decode kernel hands the up-projection normalised bf16
-  // rows instead of fp32 partials
-  a.direct = a.plan.n_splits == 1 && !a.balanced && merge_upproj_mfma_supported(a) &&
-             (decode_mfma_supported(a) || decode_gla_supported(a));
+  // the MLRA MFMA kernels hand the epilogue normalised bf16 rows (one per chunk) instead of fp32 partials
+  a.rows_bf16 = merge_upproj_mfma_supported(a) && (decode_mfma_supported(a) || decode_gla_supported(a));
   // the MFMA launchers record their kernel's own start and end; the generic kernels are bracketed by stream markers
   const bool main_fast = decode_mfma_supported(a) || decode_gla_supported(a) || mla_mfma_supported(a);
   const bool epi_fast = merge_upproj_mfma_supported(a);

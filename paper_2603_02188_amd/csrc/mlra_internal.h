@@ -100,7 +100,8 @@ struct DecodeArgs {
   int32_t* chunk_tab;  // [batch] per-sequence chunk length (workspace); filled by launch_plan_chunks when used
   int32_t* unit_tab;   // [batch * n_splits] active (sequence, chunk) pairs, then -1 (workspace); same
   bool balanced;       // chunk lengths follow the sequence lengths (chunk_tab) instead of plan.chunk_tokens
-  bool direct;         // one chunk per sequence on the MFMA kernels: part_z holds normalised bf16 rows (see MfmaParams)
+  bool rows_bf16;      // the decode kernel writes each chunk's partial as a normalised bf16 row z / l (the MLRA
+                       // MFMA kernels); otherwise fp32 partials Z (the MLA and the generic kernels)
   SplitPlan plan;
   int dtype;
   hipStream_t stream;

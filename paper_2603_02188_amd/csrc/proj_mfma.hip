@@ -169,7 +169,7 @@ __global__ __launch_bounds__(256) void merge_upproj_mfma_kernel(
     const float* __restrict__ part_z, const float* __restrict__ part_ml, const int32_t* __restrict__ seq_lens,
     const bf16_t* __restrict__ w_uv, TO* __restrict__ out, float* __restrict__ lse, int batch, int h, int nb_total,
     int d_cb, int n_splits, int chunk, const int32_t* __restrict__ chunk_tab, float out_scale,
-    const bf16_t* __restrict__ gate, int direct, int spw) {
+    const bf16_t* __restrict__ gate, int rows_bf16, int spw) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   // blockIdx.z = head group (Eq. (6)); one group of all blocks is Eq. (5).  h: heads per block; this
   // workgroup's head is h * group + head in out, and its branches are blocks [b0, b0 + n_blocks).
@@ -204,6 +204,8 @@ __global__ __launch_bounds__(256) void merge_upproj_mfma_kernel(
   const int items_per_row = R / 8;
   const int n_valid = min(spw, batch - m0);
   const int n_items = n_valid * items_per_row;
+  // normalised bf16 rows, one chunk per sequence: the rows are final (see phase 1b)
+  const bool direct = rows_bf16 && n_splits == 1;
   const bool z_early = direct && n_items <= kZPre * 256;
   if (z_early) {
 #pragma unroll
@@ -247,7 +249,8 @@ __global__ __launch_bounds__(256) void merge_upproj_mfma_kernel(
       for (int k = 0; k < active; ++k) {
         const float w = exp2f(wrow[k] - m_star);
         L += w * lrow[k];
-        wrow[k] = w;
+        // (a partial that arrives normalised, z_k / l_k, carries its row sum in its weight)
+        wrow[k] = rows_bf16 ? w * lrow[k] : w;
       }
       const float inv = L > 0.f ? 1.f / L : 0.f;
       for (int k = 0; k < active; ++k) wrow[k] *= inv;
@@ -324,6 +327,60 @@ __global__ __launch_bounds__(256) void merge_upproj_mfma_kernel(
       }
     }
   };
+  // the same for partials that are normalised bf16 rows (16 bytes per item and chunk)
+  auto merge_rows = [&](auto u_tag) {
+    constexpr int U = decltype(u_tag)::value, KK = 16 / U;
+    const bf16_t* zn = (const bf16_t*)part_z;
+    for (int base = tid; base < n_items; base += U * 256) {
+      float z[U][8];
+      const bf16_t* pz[U];
+      const float* wk[U];
+      int na[U], sl[U], r0[U], kmax = 0;
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int item = base + u * 256;
+        sl[u] = min(item, n_items - 1) / items_per_row;
+        r0[u] = (min(item, n_items - 1) % items_per_row) * 8;
+        const int b = r0[u] / d_cb, c0 = r0[u] % d_cb;
+        na[u] = item < n_items ? act[sl[u]] : 0;
+        kmax = max(kmax, na[u]);
+        pz[u] = zn + ((((size_t)(m0 + sl[u]) * nb_total + b0 + b) * n_splits) * h + head) * d_cb + c0;
+        wk[u] = wtab + sl[u] * units_per_seq + b * n_splits;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) z[u][e] = 0.f;
+      }
+      for (int k0 = 0; k0 < kmax; k0 += KK) {
+        bf16x8 row[KK][U];
+        float w[KK][U];
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk)
+#pragma unroll
+          for (int u = 0; u < U; ++u) {
+            const int k = k0 + kk;
+            const bool on = k < na[u];
+            w[kk][u] = on ? wk[u][k] : 0.f;
+            row[kk][u] = *(const bf16x8*)(pz[u] + (on ? k : 0) * z_stride);   // (chunk 0's slot always exists)
+          }
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk)
+#pragma unroll
+          for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+              // (an inactive chunk has weight 0; what its slot holds may be anything, NaN included)
+              z[u][e] += w[kk][u] != 0.f ? w[kk][u] * (float)row[kk][u][e] : 0.f;
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        if (base + u * 256 < n_items) {
+          bf16x8 packed;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) packed[e] = (__bf16)z[u][e];
+          *(bf16x8*)(zt + sl[u] * zpitch + r0[u]) = packed;
+        }
+      }
+    }
+  };
   if (z_early) {
     // one chunk per sequence and the decode kernel wrote z / l as bf16 rows [.][block][head][d_cb]: the
     // rows fetched at the top go to LDS
@@ -350,6 +407,11 @@ __global__ __launch_bounds__(256) void merge_upproj_mfma_kernel(
       if (act[sl] > 0) v = *(const bf16x8*)(zn + (((size_t)(m0 + sl) * nb_total + b0 + b) * h + head) * d_cb + c0);
       *(bf16x8*)(zt + sl * zpitch + r0) = v;
     }
+  } else if (rows_bf16) {
+    if (n_splits > 8) merge_rows(std::integral_constant<int, 1>{});
+    else if (n_splits > 4) merge_rows(std::integral_constant<int, 2>{});
+    else if (n_splits > 2) merge_rows(std::integral_constant<int, 4>{});
+    else merge_rows(std::integral_constant<int, 8>{});
   } else if (n_splits > 8) merge_items(std::integral_constant<int, 1>{});
   else if (n_splits > 4) merge_items(std::integral_constant<int, 2>{});
   else if (n_splits > 2) merge_items(std::integral_constant<int, 4>{});
@@ -457,7 +519,7 @@ int launch_merge_upproj_mfma(const DecodeArgs& a) {
   while (spw > 8 && (long)a.h * a.groups * ((a.batch + spw - 1) / spw) < device_cu_count()) spw /= 2;
   dim3 grid(a.h, (a.batch + spw - 1) / spw, a.groups);
   const int32_t* const chunk_tab = a.balanced ? a.chunk_tab : nullptr;
-  const int direct = a.direct ? 1 : 0;
+  const int direct = a.rows_bf16 ? 1 : 0;
   if (a.out_dtype == MLRA_BF16)
     MLRA_LAUNCH_TIMED(a.t_epi, merge_upproj_mfma_kernel<bf16_t>, grid, dim3(256), lds, a.stream, (const float*)a.part_z,
                       (const float*)a.part_ml, a.seq_lens, (const bf16_t*)a.w_uv, (bf16_t*)a.out, a.lse, a.batch, a.h,
