@@ -782,8 +782,17 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
         __builtin_amdgcn_s_barrier();
         if (ISSUE) issue_begin();
       }
-      if (ISSUE && m >= 2 && m < 2 + kLoadsTile / 2) { issue_full_part(2 * (m - 2)); issue_full_part(2 * (m - 2) + 1); }
-      if (ISSUE && m == 2 + kLoadsTile / 2) issue_end();
+      // (a compute unit takes about 64 bytes of vector-memory requests per cycle, and its four waves issue
+      // their loads behind the same MFMAs: one 1 KiB load per wave behind every second MFMA stays below
+      // that rate, two behind one MFMA wait on each other for four MFMAs' time.  The forms with ten loads
+      // per tile have no slots to spare and put one behind every MFMA.)
+      if (kLoadsTile <= 6) {
+        if (ISSUE && m >= 2 && (m & 1) == 0 && (m - 2) / 2 < kLoadsTile) issue_full_part((m - 2) / 2);
+        if (ISSUE && m == 2 * kLoadsTile + 1) issue_end();
+      } else {
+        if (ISSUE && m >= 2 && m < 2 + kLoadsTile) issue_full_part(m - 2);
+        if (ISSUE && m == 2 + kLoadsTile) issue_end();
+      }
       // (the last K read is three MFMAs from the end of the step: the first wait of the next step, which
       // covers every LDS read because a scalar load is in flight, then finds them all returned)
       if (GLA && m >= 2 && m <= 5) {
@@ -816,7 +825,7 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
     // the maxima are relative to the reference: it moves only when a head's scores outgrow it by 2^kLazy
     const bool need0 = has_next && mx0 > kLazy;
     const bool need1 = has_next && mx1 > kLazy;
-    if (__any(need0 || need1)) {
+    if (__builtin_expect(__any(need0 || need1), 0)) {
       settle_acc();
       rescale(std::integral_constant<int, 0>{}, need0 ? mx0 : 0.f, n0);
       rescale(std::integral_constant<int, 1>{}, need1 ? mx1 : 0.f, n1);
