@@ -37,20 +37,29 @@ using namespace mfma_tile;
 // Sequence ids sorted by length, longest first (rank sort; ties keep index order).  Used when a launch has
 // more workgroups than the chip runs at once: workgroups are dispatched in id order, so handing out
 // the long sequences first is the longest-processing-time rule and keeps the last round short.
+// group > 1 (several query tokens per sequence): entries [i group, i group + group) of seq_lens are the
+// queries of one sequence, which read the same cache rows.  Whole sequences are ranked (by their longest
+// query) and the queries of the sequence of rank r get the dispatch slots (r / 8) 8 group + 8 q + r % 8:
+// the decode kernels put slot k on XCD k % 8 and slots of one run of 8 group side by side in time, so the
+// queries of a sequence meet in one L2 and its rows come from HBM once.
 __global__ __launch_bounds__(256) void seq_order_kernel(const int32_t* __restrict__ seq_lens,
-                                                        int32_t* __restrict__ order, int batch) {
+                                                        int32_t* __restrict__ order, int n_seqs, int group) {
   extern __shared__ int32_t lens[];            // every length once, then the comparisons run out of LDS
-  for (int j = threadIdx.x; j < batch; j += 256) lens[j] = seq_lens[j];
+  for (int j = threadIdx.x; j < n_seqs; j += 256) lens[j] = seq_lens[(size_t)j * group + group - 1];
   __syncthreads();
   const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i >= batch) return;
+  if (i >= n_seqs) return;
   const int n = lens[i];
   int rank = 0;
-  for (int j = 0; j < batch; ++j) {
+  for (int j = 0; j < n_seqs; ++j) {
     const int nj = lens[j];
     rank += (nj > n || (nj == n && j < i)) ? 1 : 0;
   }
-  order[rank] = i;
+  const int full = n_seqs & ~7;                // ranks below this fill whole runs of 8 sequences
+  for (int q = 0; q < group; ++q) {
+    const int slot = rank < full ? (rank >> 3) * 8 * group + 8 * q + (rank & 7) : full * group + (rank - full) * group + q;
+    order[slot] = i * group + q;
+  }
 }
 
 // Chunk lengths that follow the sequence lengths.  With uniform chunks a ragged batch leaves workgroups
@@ -1012,13 +1021,21 @@ int launch_plan_chunks(const DecodeArgs& a) {
   return check_launch();
 }
 
-// Fills a.seq_order (workspace) with the sequence ids, longest first.  MLRA_ERR_SHAPE (and nothing
-// enqueued) when the batch is outside what the O(batch^2) rank sort is meant for.
+// Fills a.seq_order (workspace) with the sequence ids in dispatch order (see seq_order_kernel).
+// MLRA_ERR_SHAPE (and nothing enqueued) when the batch is outside what the O(batch^2) rank sort is meant for.
 int launch_seq_order(const DecodeArgs& a) {
-  if (!a.seq_order || a.batch <= 1 || a.batch > 8192) return MLRA_ERR_SHAPE;
-  seq_order_kernel<<<(a.batch + 255) / 256, 256, a.batch * sizeof(int32_t), a.stream>>>(a.seq_lens, a.seq_order,
-                                                                                       a.batch);
+  const int group = a.q_group > 1 ? a.q_group : 1;
+  if (!a.seq_order || a.batch <= 1 || a.batch > 8192 || a.batch % group != 0) return MLRA_ERR_SHAPE;
+  const int n_seqs = a.batch / group;
+  seq_order_kernel<<<(n_seqs + 255) / 256, 256, n_seqs * sizeof(int32_t), a.stream>>>(a.seq_lens, a.seq_order, n_seqs,
+                                                                                     group);
   return check_launch();
+}
+
+// (several query tokens per sequence: the order is what brings a sequence's queries together, so it is
+// wanted even when one round of workgroups covers the launch)
+static bool want_seq_order(const DecodeArgs& a, long long n_wg) {
+  return !a.balanced && (n_wg > device_cu_count() || a.q_group > 1);
 }
 
 // Pages of 16 or 32 tokens (a wave's 16 rows of a tile never straddle a page), or whole tiles.
@@ -1079,7 +1096,7 @@ int launch_decode_gla(const DecodeArgs& a) {
   p.seq_order = nullptr;
   const long long n_wg = (long long)a.plan.n_splits * a.n_blocks * ((a.h + 63) / 64) * a.batch;
   if (n_wg <= 0 || n_wg > 0x7fffffffLL) return MLRA_ERR_SHAPE;
-  if (!a.balanced && n_wg > device_cu_count() && launch_seq_order(a) == MLRA_OK) p.seq_order = a.seq_order;
+  if (want_seq_order(a, n_wg) && launch_seq_order(a) == MLRA_OK) p.seq_order = a.seq_order;
   MLRA_LAUNCH_TIMED(a.t_main, (decode_mfma_kernel<kStagesGla, 2>), dim3((unsigned)n_wg), dim3(256), lds, a.stream, p);
   return check_launch();
 }
@@ -1124,7 +1141,7 @@ int launch_decode_mfma(const DecodeArgs& a) {
   p.seq_order = nullptr;
   p.chunk_tab = a.balanced ? a.chunk_tab : nullptr;
   p.unit_tab = a.balanced ? a.unit_tab : nullptr;
-  if (!a.balanced && n_wg > device_cu_count() && launch_seq_order(a) == MLRA_OK) p.seq_order = a.seq_order;
+  if (want_seq_order(a, n_wg) && launch_seq_order(a) == MLRA_OK) p.seq_order = a.seq_order;
   if (paired)
     MLRA_LAUNCH_TIMED(a.t_main, (decode_mfma_kernel<kStagesPaired, 1>), dim3((unsigned)n_wg), dim3(256), lds, a.stream, p);
   else

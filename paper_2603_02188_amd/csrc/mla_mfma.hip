@@ -398,7 +398,7 @@ int launch_mla_mfma(const DecodeArgs& a) {
   const int n_hg = (a.h + kMHeads - 1) / kMHeads;
   const long long n_wg = (long long)a.plan.n_splits * n_hg * a.batch;
   if (n_wg <= 0 || n_wg > 0x7fffffffLL) return MLRA_ERR_SHAPE;
-  if (!a.balanced && n_wg > device_cu_count() && launch_seq_order(a) == MLRA_OK) p.seq_order = a.seq_order;
+  if (!a.balanced && (n_wg > device_cu_count() || a.q_group > 1) && launch_seq_order(a) == MLRA_OK) p.seq_order = a.seq_order;
   MLRA_LAUNCH_TIMED(a.t_main, mla_mfma_kernel, dim3((unsigned)n_wg), dim3(256), kMLds, a.stream, p);
   return check_launch();
 }

@@ -134,7 +134,7 @@ static size_t decode_ws_bytes(int batch, int h, int n_blocks, int d_cb, const Sp
 static int decode_common(const mlra_cache* c, int batch, int h, int groups, int d_h, const void* q_abs,
                          const void* q_rope, const void* w_uv, float softmax_scale, float out_scale, void* out,
                          int out_dtype, float* lse, void* workspace, size_t workspace_bytes, void* stream,
-                         const void* gate = nullptr) {
+                         const void* gate = nullptr, int q_group = 1) {
   if (!c || !q_abs || !q_rope || !w_uv || !out) return MLRA_ERR_NULL;
   if (!c->latent || !c->rope || !c->page_table || !c->seq_lens) return MLRA_ERR_NULL;
   if (!valid_dtype(c->dtype) || !valid_dtype(out_dtype)) return MLRA_ERR_DTYPE;
@@ -158,6 +158,7 @@ static int decode_common(const mlra_cache* c, int batch, int h, int groups, int 
   a.unit_tab = (int32_t*)((char*)a.chunk_tab + align_up((size_t)batch * sizeof(int32_t), 256));
   a.balanced = false;
   a.rows_bf16 = false;
+  a.q_group = q_group;
   a.latent = c->latent;
   a.rope = c->rope;
   a.page_table = c->page_table;
@@ -324,7 +325,7 @@ int mlra_decode_attn_multi(const mlra_cache* c, int32_t batch, int32_t q_len, in
   c2.seq_lens = lens2;
   return decode_common(&c2, units, h, 1, d_h, q_abs, q_rope, w_uv, softmax_scale, out_scale, out, out_dtype, lse,
                        (char*)workspace + lens_bytes + table_bytes, workspace_bytes - lens_bytes - table_bytes,
-                       stream);
+                       stream, nullptr, q_len);
 }
 
 int mlra_decode_attn_gated(const mlra_cache* cache, int32_t batch, int32_t h, int32_t d_h, const void* q_abs,

@@ -96,6 +96,7 @@ struct DecodeArgs {
   const void* gate;    // optional [batch][groups * h][d_h] of the cache dtype: out is multiplied by it elementwise
   float* part_z;   // [batch][n_blocks][n_splits][h][d_cb]
   float* part_ml;  // [batch][n_blocks][n_splits][h][2]  (running max, running sum)
+  int q_group;         // > 1: entries [i q_group, (i + 1) q_group) of the batch are the query tokens of one sequence
   int32_t* seq_order;  // [batch] sequence ids, longest first (workspace); filled by the MFMA launcher when used
   int32_t* chunk_tab;  // [batch] per-sequence chunk length (workspace); filled by launch_plan_chunks when used
   int32_t* unit_tab;   // [batch * n_splits] active (sequence, chunk) pairs, then -1 (workspace); same
