@@ -46,6 +46,7 @@ def _args():
                     help="upper bound of the untimed settle phase (steps run before --warmup until the decode "
                          "kernel's time has stopped falling: the chip raises its clocks over the first milliseconds "
                          "of load); 0 switches it off")
+    ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the step")
     ap.add_argument("--no-probes", action="store_true",
                     help="skip the streaming-read ceiling and shader-clock probes (profiling runs)")
     return ap.parse_args()
@@ -244,10 +245,11 @@ def main():
     c_new, k_new, positions = up(inp.c_kv_new), up(inp.k_rope_new), up(inp.positions)
     q_abs = torch.empty((wl.batch, wl.n_blocks, wl.h // wl.groups, wl.d_cb), dtype=q_nope.dtype, device=dev)
     out = torch.empty((wl.batch, wl.h, wl.d_h), dtype=torch.bfloat16, device=dev)
+    # (the absorb call folds tau log2(e) into the queries, the decode call is told so)
     if wl.groups == 2:   # MLRA-2 (Eq. (6))
-        absorb_q, decode_attn, ws_query = mlra.mlra2_absorb_q, mlra.mlra2_decode_attn, mlra.mlra2_decode_workspace_bytes
+        absorb_q, decode_attn, ws_query = mlra.mlra2_absorb_q_folded, mlra.mlra2_decode_attn, mlra.mlra2_decode_workspace_bytes
     else:
-        absorb_q, decode_attn, ws_query = mlra.mlra_absorb_q, mlra.mlra_decode_attn, mlra.mlra_decode_workspace_bytes
+        absorb_q, decode_attn, ws_query = mlra.mlra_absorb_q_folded, mlra.mlra_decode_attn, mlra.mlra_decode_workspace_bytes
     ws_bytes = ws_query(wl.batch, wl.h, wl.n_blocks, wl.d_cb, caches[0].max_seq_len)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
 
@@ -282,17 +284,19 @@ def main():
         def decode_attn(c, q_abs_, q_rope_, w_uv_, tau, out_scale, out=None, workspace=None):   # noqa: F811
             return mlra.mlra_decode_attn_multi(c, q_abs5, q_rope_, w_uv_, tau, out_scale, out=out, workspace=workspace)
 
+    q_rope_s = torch.empty_like(q_rope)   # the RoPE queries times tau log2(e)
+
     def step(i):
         c = caches[i % copies]
         if pre is None:
             mlra.mlra_append_kv(c, c_new, k_new, positions)
         else:
             mlra.mlra_pre_attention(c, pw, hidden, positions, q_nope, q_rope, pre_ws)
-        absorb_q(q_nope, w_uk, q_abs)
-        decode_attn(c, q_abs, q_rope, w_uv, wl.tau, 1.0, out=out, workspace=ws)
+        absorb_q(q_nope, w_uk, q_rope, wl.tau, q_abs, q_rope_s)
+        decode_attn(c, q_abs, q_rope_s, w_uv, mlra.SCALE_FOLDED, 1.0, out=out, workspace=ws)
 
     def decode_only(i):
-        decode_attn(caches[i % copies], q_abs, q_rope, w_uv, wl.tau, 1.0, out=out, workspace=ws)
+        decode_attn(caches[i % copies], q_abs, q_rope_s, w_uv, mlra.SCALE_FOLDED, 1.0, out=out, workspace=ws)
 
     if a.copy_calibration:
         # a plain copy of known size: 2^30 bytes read, 2^30 bytes written per dispatch
@@ -340,6 +344,23 @@ def main():
         step(a.warmup + a.steps + i)
     torch.cuda.synchronize()
     main_ms, epi_ms, calls = mlra.mlra_kernel_timing_end()
+
+    # the same steps captured once in a HIP graph (one graph = one step on each rotated cache copy) and
+    # replayed: what a serving loop that replays a captured step pays, without the per-call host work
+    graph_us = None
+    if not a.no_graph:
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for i in range(copies):
+                step(i)
+        n_replays = max(1, (a.steps + copies - 1) // copies)
+        g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n_replays):
+            g.replay()
+        torch.cuda.synchronize()
+        graph_us = (time.perf_counter() - t0) * 1e6 / (n_replays * copies)
 
     # shader clock under this load: one wavefront on a second stream (default priority) counts shader cycles
     # against the 100 MHz counter while a few more, untimed, steps run (it shares a SIMD with a decode
@@ -417,6 +438,7 @@ def main():
         "decode_attn_gbps": bytes_decode["total"] / (float(np.median(dec)) * 1e-6) / 1e9,
         "decode_attn_tflops": flops / (float(np.median(dec)) * 1e-6) / 1e12,
         "kernels_us": {"decode_main": main_ms * 1e3, "merge_upproj": epi_ms * 1e3, "calls": calls},
+        "graph_replay_us_per_step": graph_us,
         "settle_steps": settle_steps, "settle_decode_main_us": settle_trace,
         "shader_clock_ghz_under_load": shader_clock_ghz,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": rf.HBM_PEAK_GBS, "unit": "GB/s",

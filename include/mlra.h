@@ -87,6 +87,20 @@ MLRA_API int mlra_append_kv(const mlra_cache* cache, int32_t batch, const void* 
 MLRA_API int mlra_absorb_q(int32_t batch, int32_t h, int32_t d_h, int32_t n_blocks, int32_t d_cb,
                   const void* q_nope, const void* w_uk, void* q_abs, int32_t dtype, void* stream);
 
+/* The same with the softmax scale folded into the queries (Eq. (5): both score terms carry the factor tau,
+ * so it may be applied to the queries once instead of to every score):
+ *   q_abs[s][b][i][:]   = tau log2(e) * W^UK_(b),(i) q_nope[s][i][:]   (multiplied in fp32, rounded once)
+ *   q_rope_out[s][i][:] = tau log2(e) * q_rope[s][i][:]                [batch][h][d_r], may alias q_rope
+ * with tau = softmax_scale > 0.  The decode entry points take such queries with
+ * softmax_scale = MLRA_SCALE_FOLDED: the scores then leave the matrix pipe in the log2 domain and the decode
+ * kernel skips its own multiplication of the queries.  Outputs and lse are those of the unfolded calls up
+ * to the rounding of the queries.  One launch on `stream`; errors as mlra_absorb_q (+ MLRA_ERR_SHAPE for
+ * softmax_scale <= 0 or d_r <= 0). */
+#define MLRA_SCALE_FOLDED 0.0f
+MLRA_API int mlra_absorb_q_folded(int32_t batch, int32_t h, int32_t d_h, int32_t n_blocks, int32_t d_cb, int32_t d_r,
+                         const void* q_nope, const void* w_uk, const void* q_rope, float softmax_scale,
+                         void* q_abs, void* q_rope_out, int32_t dtype, void* stream);
+
 /* Bytes of workspace mlra_decode_attn / mla_decode_attn need for these sizes on the current device
  * (0 on invalid sizes).  max_seq_len is max_pages_per_seq * page_size of the cache passed later. */
 MLRA_API size_t mlra_decode_workspace_bytes(int32_t batch, int32_t h, int32_t n_blocks, int32_t d_cb,
@@ -173,6 +187,11 @@ MLRA_API int mla_decode_attn(const mlra_cache* cache, int32_t batch, int32_t h, 
  * behaviour are those of mlra_absorb_q / mlra_decode_workspace_bytes / mlra_decode_attn. */
 MLRA_API int mlra2_absorb_q(int32_t batch, int32_t h, int32_t d_h, int32_t n_blocks, int32_t d_cb,
                    const void* q_nope, const void* w_uk, void* q_abs, int32_t dtype, void* stream);
+/* (as mlra_absorb_q_folded, for the two head groups of Eq. (6); pass softmax_scale = MLRA_SCALE_FOLDED to
+ * mlra2_decode_attn) */
+MLRA_API int mlra2_absorb_q_folded(int32_t batch, int32_t h, int32_t d_h, int32_t n_blocks, int32_t d_cb, int32_t d_r,
+                          const void* q_nope, const void* w_uk, const void* q_rope, float softmax_scale,
+                          void* q_abs, void* q_rope_out, int32_t dtype, void* stream);
 MLRA_API size_t mlra2_decode_workspace_bytes(int32_t batch, int32_t h, int32_t n_blocks, int32_t d_cb,
                                     int32_t max_seq_len);
 MLRA_API int mlra2_decode_attn(const mlra_cache* cache, int32_t batch, int32_t h, int32_t d_h, const void* q_abs,

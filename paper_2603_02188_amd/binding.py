@@ -19,7 +19,8 @@ _lib: Optional[ctypes.CDLL] = None
 
 MLRA_BF16, MLRA_F32 = 0, 1
 
-EXPORTS = ("mlra_strerror", "mlra_append_kv", "mlra_absorb_q", "mlra_decode_workspace_bytes",
+EXPORTS = ("mlra_strerror", "mlra_append_kv", "mlra_absorb_q", "mlra_absorb_q_folded", "mlra2_absorb_q_folded",
+           "mlra_decode_workspace_bytes",
            "mlra_decode_attn", "mlra_decode_attn_static", "mla_decode_attn", "mlra2_absorb_q", "mlra2_decode_workspace_bytes",
            "mlra2_decode_attn", "mlra_decode_attn_gated", "mlra_decode_multi_workspace_bytes", "mlra_decode_attn_multi",
            "mlra_pre_attention_workspace_bytes", "mlra_pre_attention",
@@ -65,6 +66,9 @@ def load_library() -> ctypes.CDLL:
     lib.mlra_append_kv.argtypes = [cp, i32, vp, vp, i32, vp, vp]
     lib.mlra_absorb_q.restype = ctypes.c_int
     lib.mlra_absorb_q.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, i32, vp]
+    for fn in (lib.mlra_absorb_q_folded, lib.mlra2_absorb_q_folded):
+        fn.restype = ctypes.c_int
+        fn.argtypes = [i32, i32, i32, i32, i32, i32, vp, vp, vp, f32, vp, vp, i32, vp]
     lib.mlra_decode_workspace_bytes.restype = sz
     lib.mlra_decode_workspace_bytes.argtypes = [i32, i32, i32, i32, i32]
     lib.mlra_decode_attn.restype = ctypes.c_int
@@ -183,6 +187,40 @@ def mlra_absorb_q(q_nope: torch.Tensor, w_uk: torch.Tensor, q_abs: Optional[torc
     _check(lib.mlra_absorb_q(batch, h, d_h, n_blocks, d_cb, _ptr(q_nope), _ptr(w_uk), _ptr(q_abs),
                              _dt(q_nope.dtype), _stream(stream)), "mlra_absorb_q")
     return q_abs
+
+
+SCALE_FOLDED = 0.0   # softmax_scale for the decode calls when the queries come from *_absorb_q_folded
+
+
+def _absorb_folded(entry: str, groups: int, q_nope, w_uk, q_rope, softmax_scale, q_abs, q_rope_out, stream):
+    lib = load_library()
+    batch, h, d_h = q_nope.shape
+    n_blocks, d_cb, hd = w_uk.shape
+    d_r = q_rope.shape[-1]
+    assert h % groups == 0 and hd == (h // groups) * d_h and w_uk.dtype == q_nope.dtype == q_rope.dtype
+    assert q_rope.numel() == batch * h * d_r
+    if q_abs is None:
+        q_abs = torch.empty((batch, n_blocks, h // groups, d_cb), dtype=q_nope.dtype, device=q_nope.device)
+    if q_rope_out is None:
+        q_rope_out = torch.empty_like(q_rope)
+    _check(getattr(lib, entry)(batch, h, d_h, n_blocks, d_cb, d_r, _ptr(q_nope), _ptr(w_uk), _ptr(q_rope),
+                               float(softmax_scale), _ptr(q_abs), _ptr(q_rope_out), _dt(q_nope.dtype),
+                               _stream(stream)), entry)
+    return q_abs, q_rope_out
+
+
+def mlra_absorb_q_folded(q_nope: torch.Tensor, w_uk: torch.Tensor, q_rope: torch.Tensor, softmax_scale: float,
+                         q_abs: Optional[torch.Tensor] = None, q_rope_out: Optional[torch.Tensor] = None,
+                         stream=None):
+    """(q_abs, q_rope_out), both multiplied by softmax_scale * log2(e): pass them to the decode calls with
+    softmax_scale = SCALE_FOLDED."""
+    return _absorb_folded("mlra_absorb_q_folded", 1, q_nope, w_uk, q_rope, softmax_scale, q_abs, q_rope_out, stream)
+
+
+def mlra2_absorb_q_folded(q_nope: torch.Tensor, w_uk: torch.Tensor, q_rope: torch.Tensor, softmax_scale: float,
+                          q_abs: Optional[torch.Tensor] = None, q_rope_out: Optional[torch.Tensor] = None,
+                          stream=None):
+    return _absorb_folded("mlra2_absorb_q_folded", 2, q_nope, w_uk, q_rope, softmax_scale, q_abs, q_rope_out, stream)
 
 
 def mlra_decode_workspace_bytes(batch: int, h: int, n_blocks: int, d_cb: int, max_seq_len: int) -> int:

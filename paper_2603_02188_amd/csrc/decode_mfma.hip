@@ -1089,7 +1089,7 @@ int launch_decode_gla(const DecodeArgs& a) {
   p.n_splits = a.plan.n_splits;
   p.chunk = a.plan.chunk_tokens;
   p.batch = a.batch;
-  p.scale_log2 = a.softmax_scale * 1.4426950408889634f;
+  p.scale_log2 = softmax_scale_log2(a.softmax_scale);
   p.rows_bf16 = a.rows_bf16 ? 1 : 0;
   p.chunk_tab = a.balanced ? a.chunk_tab : nullptr;
   p.unit_tab = a.balanced ? a.unit_tab : nullptr;
@@ -1132,7 +1132,7 @@ int launch_decode_mfma(const DecodeArgs& a) {
   p.n_splits = a.plan.n_splits;
   p.chunk = a.plan.chunk_tokens;
   p.batch = a.batch;
-  p.scale_log2 = a.softmax_scale * 1.4426950408889634f;
+  p.scale_log2 = softmax_scale_log2(a.softmax_scale);
   p.rows_bf16 = a.rows_bf16 ? 1 : 0;
   const int n_hg = paired ? (a.h + 63) / 64 : (a.h + kHeadsWG - 1) / kHeadsWG;
   const long long n_wg = (long long)a.plan.n_splits * (paired ? a.n_blocks / 2 : a.n_blocks) * n_hg * a.batch;

@@ -85,9 +85,16 @@ int launch_expand_queries(const int32_t* seq_lens, const int32_t* page_table, in
 // ------------------------------------------------------------------------------------------------
 template <typename T>
 __global__ void absorb_q_generic_kernel(const T* q_nope, const T* w_uk, T* q_abs, int h, int d_h, int n_blocks,
-                                        int groups, int d_cb) {
+                                        int groups, int d_cb, float fold, const T* q_rope, T* q_rope_out, int d_r) {
   extern __shared__ float qs[];
   const int head = blockIdx.x, b = blockIdx.y, s = blockIdx.z;
+  if (b == n_blocks) {   // (launched only when the softmax scale is folded in) the RoPE queries of this head
+    for (int id = threadIdx.x; id < groups * d_r; id += blockDim.x) {
+      const size_t off = ((size_t)s * h * groups + (id / d_r) * h + head) * d_r + id % d_r;
+      store_f32(q_rope_out, off, load_f32(q_rope, off) * fold);
+    }
+    return;
+  }
   const int q_head = (b / (n_blocks / groups)) * h + head;   // Eq. (6): block b serves the heads of its group
   for (int p = threadIdx.x; p < d_h; p += blockDim.x)
     qs[p] = load_f32(q_nope, ((size_t)s * h * groups + q_head) * d_h + p);
@@ -98,20 +105,23 @@ __global__ void absorb_q_generic_kernel(const T* q_nope, const T* w_uk, T* q_abs
     float acc = 0.f;
     for (int p = lane; p < d_h; p += 64) acc += load_f32(w_uk, row + p) * qs[p];
     acc = wave_sum(acc);
-    if (lane == 0) store_f32(q_abs, (((size_t)s * n_blocks + b) * h + head) * d_cb + c, acc);
+    if (lane == 0) store_f32(q_abs, (((size_t)s * n_blocks + b) * h + head) * d_cb + c, acc * fold);
   }
 }
 
 int launch_absorb_q_generic(int batch, int h, int d_h, int n_blocks, int groups, int d_cb, const void* q_nope,
-                            const void* w_uk, void* q_abs, int dtype, hipStream_t stream) {
-  dim3 grid(h, n_blocks, batch);
+                            const void* w_uk, void* q_abs, int dtype, hipStream_t stream, float fold,
+                            const void* q_rope, void* q_rope_out, int d_r) {
+  dim3 grid(h, n_blocks + (q_rope_out ? 1 : 0), batch);
   const size_t lds = (size_t)d_h * sizeof(float);
   if (dtype == MLRA_BF16)
     absorb_q_generic_kernel<bf16_t><<<grid, 256, lds, stream>>>((const bf16_t*)q_nope, (const bf16_t*)w_uk,
-                                                                (bf16_t*)q_abs, h, d_h, n_blocks, groups, d_cb);
+                                                                (bf16_t*)q_abs, h, d_h, n_blocks, groups, d_cb, fold,
+                                                                (const bf16_t*)q_rope, (bf16_t*)q_rope_out, d_r);
   else
     absorb_q_generic_kernel<float><<<grid, 256, lds, stream>>>((const float*)q_nope, (const float*)w_uk,
-                                                               (float*)q_abs, h, d_h, n_blocks, groups, d_cb);
+                                                               (float*)q_abs, h, d_h, n_blocks, groups, d_cb, fold,
+                                                               (const float*)q_rope, (float*)q_rope_out, d_r);
   return check_launch();
 }
 
@@ -232,7 +242,7 @@ int launch_decode_generic(const DecodeArgs& a) {
   if (lds_bytes(TT) > 64 * 1024) return MLRA_ERR_SHAPE;
   const int n_hg = (a.h + HG - 1) / HG;
   dim3 grid(a.plan.n_splits, a.n_blocks * n_hg, a.batch);
-  const float scale_log2 = a.softmax_scale * kLog2e;
+  const float scale_log2 = softmax_scale_log2(a.softmax_scale);
   if (a.dtype == MLRA_BF16)
     decode_generic_kernel<bf16_t><<<grid, 256, lds_bytes(TT), a.stream>>>(
         (const bf16_t*)a.latent, (const bf16_t*)a.rope, a.page_table, a.seq_lens, a.page_size, a.max_pages,
@@ -419,7 +429,7 @@ int launch_gqa_generic(const GqaArgs& a) {
   if (lds_bytes(TT) > 64 * 1024) return MLRA_ERR_SHAPE;
   const int n_sub = (r + HG - 1) / HG;
   dim3 grid(a.plan.n_splits, a.g * n_sub, a.batch);
-  const float scale_log2 = a.softmax_scale * kLog2e;
+  const float scale_log2 = softmax_scale_log2(a.softmax_scale);
   if (a.dtype == MLRA_BF16)
     gqa_generic_kernel<bf16_t><<<grid, 256, lds_bytes(TT), a.stream>>>(
         (const bf16_t*)a.k_pool, (const bf16_t*)a.v_pool, a.page_table, a.seq_lens, a.page_size, a.max_pages, a.h,

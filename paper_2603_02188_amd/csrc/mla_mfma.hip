@@ -393,7 +393,7 @@ int launch_mla_mfma(const DecodeArgs& a) {
   p.n_splits = a.plan.n_splits;
   p.chunk = a.plan.chunk_tokens;
   p.batch = a.batch;
-  p.scale_log2 = a.softmax_scale * 1.4426950408889634f;
+  p.scale_log2 = softmax_scale_log2(a.softmax_scale);
   p.rows_bf16 = 0;
   const int n_hg = (a.h + kMHeads - 1) / kMHeads;
   const long long n_wg = (long long)a.plan.n_splits * n_hg * a.batch;

@@ -237,15 +237,40 @@ int mlra_append_kv(const mlra_cache* c, int32_t batch, const void* c_kv_new, con
   return launch_append_kv(c, batch, c_kv_new, k_rope_new, src_dtype, positions, (hipStream_t)stream);
 }
 
-int mlra_absorb_q(int32_t batch, int32_t h, int32_t d_h, int32_t n_blocks, int32_t d_cb, const void* q_nope,
-                  const void* w_uk, void* q_abs, int32_t dtype, void* stream) {
+static int absorb_common(int batch, int h, int d_h, int n_blocks, int groups, int d_cb, int d_r, const void* q_nope,
+                         const void* w_uk, const void* q_rope, float fold, void* q_abs, void* q_rope_out, int dtype,
+                         void* stream) {
   if (!q_nope || !w_uk || !q_abs) return MLRA_ERR_NULL;
   if (!valid_dtype(dtype)) return MLRA_ERR_DTYPE;
   if (batch <= 0 || h <= 0 || d_h <= 0 || n_blocks <= 0 || d_cb <= 0) return MLRA_ERR_SHAPE;
-  if (h > 65535 || batch > 65535 || n_blocks > 65535 || d_h > 8192) return MLRA_ERR_SHAPE;
-  if (absorb_q_mfma_supported(d_h, d_cb, dtype))
-    return launch_absorb_q_mfma(batch, h, d_h, n_blocks, 1, d_cb, q_nope, w_uk, q_abs, (hipStream_t)stream);
-  return launch_absorb_q_generic(batch, h, d_h, n_blocks, 1, d_cb, q_nope, w_uk, q_abs, dtype, (hipStream_t)stream);
+  if (h % groups != 0 || n_blocks % groups != 0) return MLRA_ERR_SHAPE;
+  if (h > 65535 || batch > 65535 || n_blocks > 65534 || d_h > 8192) return MLRA_ERR_SHAPE;
+  if (absorb_q_mfma_supported(d_h, d_cb, dtype) && (!q_rope_out || d_r % 8 == 0))
+    return launch_absorb_q_mfma(batch, h / groups, d_h, n_blocks, groups, d_cb, q_nope, w_uk, q_abs,
+                                (hipStream_t)stream, fold, q_rope, q_rope_out, d_r);
+  return launch_absorb_q_generic(batch, h / groups, d_h, n_blocks, groups, d_cb, q_nope, w_uk, q_abs, dtype,
+                                 (hipStream_t)stream, fold, q_rope, q_rope_out, d_r);
+}
+
+static int absorb_folded(int batch, int h, int d_h, int n_blocks, int groups, int d_cb, int d_r, const void* q_nope,
+                         const void* w_uk, const void* q_rope, float softmax_scale, void* q_abs, void* q_rope_out,
+                         int dtype, void* stream) {
+  if (!q_rope || !q_rope_out) return MLRA_ERR_NULL;
+  if (!(softmax_scale > 0.f) || d_r <= 0) return MLRA_ERR_SHAPE;
+  return absorb_common(batch, h, d_h, n_blocks, groups, d_cb, d_r, q_nope, w_uk, q_rope,
+                       softmax_scale * 1.4426950408889634f, q_abs, q_rope_out, dtype, stream);
+}
+
+int mlra_absorb_q(int32_t batch, int32_t h, int32_t d_h, int32_t n_blocks, int32_t d_cb, const void* q_nope,
+                  const void* w_uk, void* q_abs, int32_t dtype, void* stream) {
+  return absorb_common(batch, h, d_h, n_blocks, 1, d_cb, 0, q_nope, w_uk, nullptr, 1.f, q_abs, nullptr, dtype, stream);
+}
+
+int mlra_absorb_q_folded(int32_t batch, int32_t h, int32_t d_h, int32_t n_blocks, int32_t d_cb, int32_t d_r,
+                         const void* q_nope, const void* w_uk, const void* q_rope, float softmax_scale, void* q_abs,
+                         void* q_rope_out, int32_t dtype, void* stream) {
+  return absorb_folded(batch, h, d_h, n_blocks, 1, d_cb, d_r, q_nope, w_uk, q_rope, softmax_scale, q_abs, q_rope_out,
+                       dtype, stream);
 }
 
 size_t mlra_decode_workspace_bytes(int32_t batch, int32_t h, int32_t n_blocks, int32_t d_cb, int32_t max_seq_len) {
@@ -339,15 +364,16 @@ int mlra_decode_attn_gated(const mlra_cache* cache, int32_t batch, int32_t h, in
 
 int mlra2_absorb_q(int32_t batch, int32_t h, int32_t d_h, int32_t n_blocks, int32_t d_cb, const void* q_nope,
                    const void* w_uk, void* q_abs, int32_t dtype, void* stream) {
-  if (!q_nope || !w_uk || !q_abs) return MLRA_ERR_NULL;
-  if (!valid_dtype(dtype)) return MLRA_ERR_DTYPE;
-  if (batch <= 0 || h <= 0 || d_h <= 0 || n_blocks <= 0 || d_cb <= 0) return MLRA_ERR_SHAPE;
-  if (h % 2 != 0 || n_blocks % 2 != 0) return MLRA_ERR_SHAPE;
-  if (h > 65535 || batch > 65535 || n_blocks > 65535 || d_h > 8192) return MLRA_ERR_SHAPE;
-  if (absorb_q_mfma_supported(d_h, d_cb, dtype))
-    return launch_absorb_q_mfma(batch, h / 2, d_h, n_blocks, 2, d_cb, q_nope, w_uk, q_abs, (hipStream_t)stream);
-  return launch_absorb_q_generic(batch, h / 2, d_h, n_blocks, 2, d_cb, q_nope, w_uk, q_abs, dtype,
-                                 (hipStream_t)stream);
+  if (h % 2 != 0 || n_blocks % 2 != 0) return (!q_nope || !w_uk || !q_abs) ? MLRA_ERR_NULL : MLRA_ERR_SHAPE;
+  return absorb_common(batch, h, d_h, n_blocks, 2, d_cb, 0, q_nope, w_uk, nullptr, 1.f, q_abs, nullptr, dtype, stream);
+}
+
+int mlra2_absorb_q_folded(int32_t batch, int32_t h, int32_t d_h, int32_t n_blocks, int32_t d_cb, int32_t d_r,
+                          const void* q_nope, const void* w_uk, const void* q_rope, float softmax_scale, void* q_abs,
+                          void* q_rope_out, int32_t dtype, void* stream) {
+  if (h % 2 != 0 || n_blocks % 2 != 0) return (!q_nope || !w_uk || !q_abs) ? MLRA_ERR_NULL : MLRA_ERR_SHAPE;
+  return absorb_folded(batch, h, d_h, n_blocks, 2, d_cb, d_r, q_nope, w_uk, q_rope, softmax_scale, q_abs, q_rope_out,
+                       dtype, stream);
 }
 
 size_t mlra2_decode_workspace_bytes(int32_t batch, int32_t h, int32_t n_blocks, int32_t d_cb, int32_t max_seq_len) {

@@ -109,11 +109,20 @@ struct DecodeArgs {
   KernelTimer t_main, t_epi;   // set by mlra_kernel_timing_begin: the decode kernel and the merge / up-projection
 };
 
+// Factor that takes the raw score to the log2 domain: tau log2(e), or 1 when the caller's queries already
+// carry it (softmax_scale == MLRA_SCALE_FOLDED, see mlra_absorb_q_folded).
+inline float softmax_scale_log2(float softmax_scale) {
+  return softmax_scale == MLRA_SCALE_FOLDED ? 1.0f : softmax_scale * 1.4426950408889634f;
+}
+
 int launch_append_kv(const mlra_cache* c, int batch, const void* c_kv_new, const void* k_rope_new, int src_dtype,
                      const int32_t* positions, hipStream_t stream);
 // (h: heads per block; q_nope holds groups * h heads, block b reads those of group b / (n_blocks / groups))
+// fold: factor on the absorbed queries before rounding; q_rope_out non-null: also q_rope_out = fold * q_rope
+// ([batch][groups * h][d_r]), in the same launch
 int launch_absorb_q_generic(int batch, int h, int d_h, int n_blocks, int groups, int d_cb, const void* q_nope,
-                            const void* w_uk, void* q_abs, int dtype, hipStream_t stream);
+                            const void* w_uk, void* q_abs, int dtype, hipStream_t stream, float fold = 1.f,
+                            const void* q_rope = nullptr, void* q_rope_out = nullptr, int d_r = 0);
 int launch_decode_generic(const DecodeArgs& a);
 // seq_lens_out[s * q_len + j] = max(0, seq_lens[s] - (q_len - 1 - j)); page_table_out row s * q_len + j = row s
 int launch_expand_queries(const int32_t* seq_lens, const int32_t* page_table, int batch, int q_len, int max_pages,
@@ -132,7 +141,8 @@ int launch_decode_gla(const DecodeArgs& a);   // two blocks x 64 heads per workg
 int launch_decode_mfma(const DecodeArgs& a);
 bool absorb_q_mfma_supported(int d_h, int d_cb, int dtype);
 int launch_absorb_q_mfma(int batch, int h, int d_h, int n_blocks, int groups, int d_cb, const void* q_nope,
-                         const void* w_uk, void* q_abs, hipStream_t stream);
+                         const void* w_uk, void* q_abs, hipStream_t stream, float fold = 1.f,
+                         const void* q_rope = nullptr, void* q_rope_out = nullptr, int d_r = 0);   // d_r % 8 == 0
 bool merge_upproj_mfma_supported(const DecodeArgs& a);
 int launch_merge_upproj_mfma(const DecodeArgs& a);
 

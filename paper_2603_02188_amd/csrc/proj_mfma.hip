@@ -59,9 +59,27 @@ static_assert(64 * kAbsPitch <= kAbsW, "the staged results must fit the weight r
 __global__ __launch_bounds__(256) void absorb_q_mfma_kernel(const bf16_t* __restrict__ q_nope,
                                                             const bf16_t* __restrict__ w_uk,
                                                             bf16_t* __restrict__ q_abs, int batch, int h,
-                                                            int n_blocks, int groups, int d_cb) {
+                                                            int n_blocks, int groups, int d_cb, float fold,
+                                                            const bf16_t* __restrict__ q_rope,
+                                                            bf16_t* __restrict__ q_rope_out, int d_r) {
   // h: heads per block; q_nope holds groups * h heads and block b reads those of its group (Eq. (6))
+  // fold: factor applied to the absorbed queries before they are rounded (1, or tau log2(e) when the
+  // softmax scale is folded into the queries); the workgroups with blockIdx.y == n_blocks (launched only
+  // then) apply it to the RoPE queries of head blockIdx.x of every group.
   __shared__ __attribute__((aligned(16))) unsigned char smem[kAbsQ + kAbsW];
+  if (blockIdx.y == (unsigned)n_blocks) {
+    const int m0r = blockIdx.z * 64, q_heads_r = h * groups, per_row = d_r >> 3;   // d_r % 8 == 0 (launcher)
+    for (int id = threadIdx.x; id < 64 * groups * per_row; id += 256) {
+      const int pc = id % per_row, grp = (id / per_row) % groups, s_ = m0r + id / (per_row * groups);
+      if (s_ >= batch) continue;
+      const size_t off = ((size_t)s_ * q_heads_r + grp * h + blockIdx.x) * d_r + pc * 8;
+      bf16x8 v = *(const bf16x8*)(q_rope + off);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] = (__bf16)((float)v[e] * fold);
+      *(bf16x8*)(q_rope_out + off) = v;
+    }
+    return;
+  }
   unsigned char* const qs = smem;
   unsigned char* const ws = smem + kAbsQ;
   unsigned char* const stage = ws;
@@ -131,7 +149,7 @@ __global__ __launch_bounds__(256) void absorb_q_mfma_kernel(const bf16_t* __rest
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int row = 32 * t + (r >> 2) * 8 + g * 4 + (r & 3);
-          *(bf16_t*)(stage + row * kAbsPitch + (wave * 32 + c32) * 2) = f32_to_bf16(acc[t][r]);
+          *(bf16_t*)(stage + row * kAbsPitch + (wave * 32 + c32) * 2) = f32_to_bf16(acc[t][r] * fold);
         }
     }
     __syncthreads();
@@ -479,11 +497,13 @@ bool absorb_q_mfma_supported(int d_h, int d_cb, int dtype) {
 }
 
 int launch_absorb_q_mfma(int batch, int h, int d_h, int n_blocks, int groups, int d_cb, const void* q_nope,
-                         const void* w_uk, void* q_abs, hipStream_t stream) {
+                         const void* w_uk, void* q_abs, hipStream_t stream, float fold, const void* q_rope,
+                         void* q_rope_out, int d_r) {
   (void)d_h;
-  dim3 grid(h, n_blocks, (batch + 63) / 64);
+  dim3 grid(h, n_blocks + (q_rope_out ? 1 : 0), (batch + 63) / 64);
   absorb_q_mfma_kernel<<<grid, 256, 0, stream>>>((const bf16_t*)q_nope, (const bf16_t*)w_uk, (bf16_t*)q_abs, batch, h,
-                                                 n_blocks, groups, d_cb);
+                                                 n_blocks, groups, d_cb, fold, (const bf16_t*)q_rope,
+                                                 (bf16_t*)q_rope_out, d_r);
   return check_launch();
 }
 
