@@ -87,15 +87,17 @@ def _cpu_baseline(inp, max_seconds=25.0):
                       f"{dt:.1f} s of fp64 numpy, scaled to the whole batch by token count"}, np.stack(outs)
 
 
+_DECODE_KERNEL_SOURCES = ("decode_mfma.hip", "mfma_tile.h", "proj_mfma.hip")
+
+
 def _kernel_sources_digest():
-    """sha256 over the library's HIP sources and headers (what the counter profiles were measured on)."""
-    import glob
+    """sha256 over the sources of the kernels of one decode step (the streaming decode kernel, its tile helpers,
+    the absorb and merge + up-projection kernels): what the counter profiles were measured on."""
     import hashlib
     h = hashlib.sha256()
-    for path in sorted(glob.glob(os.path.join(ROOT, "paper_2603_02188_amd", "csrc", "*")) +
-                       glob.glob(os.path.join(ROOT, "include", "*.h"))):
-        h.update(os.path.basename(path).encode())
-        h.update(open(path, "rb").read())
+    for name in _DECODE_KERNEL_SOURCES:
+        h.update(name.encode())
+        h.update(open(os.path.join(ROOT, "paper_2603_02188_amd", "csrc", name), "rb").read())
     return h.hexdigest()[:16]
 
 
@@ -353,7 +355,7 @@ def main():
         with torch.cuda.graph(g):
             for i in range(copies):
                 step(i)
-        n_replays = max(1, (a.steps + copies - 1) // copies)
+        n_replays = max(10, (2 * a.steps + copies - 1) // copies)
         g.replay()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
