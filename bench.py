@@ -91,13 +91,18 @@ _DECODE_KERNEL_SOURCES = ("decode_mfma.hip", "mfma_tile.h", "proj_mfma.hip")
 
 
 def _kernel_sources_digest():
-    """sha256 over the sources of the kernels of one decode step (the streaming decode kernel, its tile helpers,
-    the absorb and merge + up-projection kernels): what the counter profiles were measured on."""
+    """sha256 over the code (comments and blank space stripped) of the kernels of one decode step (the streaming
+    decode kernel, its tile helpers, the absorb and merge + up-projection kernels): what the counter profiles were
+    measured on."""
     import hashlib
+    import re
     h = hashlib.sha256()
     for name in _DECODE_KERNEL_SOURCES:
+        text = open(os.path.join(ROOT, "paper_2603_02188_amd", "csrc", name)).read()
+        text = re.sub(r"/\*.*?\*/", " ", text, flags=re.S)
+        text = re.sub(r"//[^\n]*", " ", text)
         h.update(name.encode())
-        h.update(open(os.path.join(ROOT, "paper_2603_02188_amd", "csrc", name), "rb").read())
+        h.update(" ".join(text.split()).encode())
     return h.hexdigest()[:16]
 
 

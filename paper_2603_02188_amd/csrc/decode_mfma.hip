@@ -11,6 +11,12 @@
 //     Z^T += V^T P^T (channels x heads); V^T comes from the row-major tile through LDS transpose reads.
 //   * Running max is updated lazily (only when it grows by more than 2^8), which is exact: the
 //     partial (m, l, z) stays self-consistent and the merge kernel normalises.
+//   * The queries carry tau log2(e), and the first MFMA of a tile's score chain starts from minus the
+//     running maximum, so a probability is exp2 of what the matrix pipe delivers.
+//   * Z^T and the row sums live in accumulation registers a0..a135 that only inline asm names (the MFMAs of
+//     the main loop are asm statements); the compiler never sees them as values.
+//   * The chunk's partial leaves as the normalised row z / l in bf16 with (m, l) in fp32 beside it (fp32,
+//     un-normalised, for shapes whose epilogue is the generic merge kernel).
 //
 // PAIRED form, for blocks that serve 64 heads (MLRA-2, Eq. (6), at h = 128): one workgroup owns two
 // neighbouring latent blocks and 64 heads.  The head half hw of a wave becomes its block: wave (hw, tw)
