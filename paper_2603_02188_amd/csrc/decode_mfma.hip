@@ -345,8 +345,9 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
 #pragma unroll
   for (int q = 0; q < 2; ++q)
     rope_voff[q] = (lane >> 3) * (kDr * 2) + (((lane & 7) ^ rope_swz(8 * q + (lane >> 3))) << 4);
-  const size_t lat_page_bytes = (size_t)p.n_blocks * p.page_size * kLatRow;
-  const size_t rope_page_bytes = (size_t)p.page_size * (kDr * 2);
+  // (bytes of one page: below 2^32, checked by the launcher, so page id x bytes is one 32 x 32 -> 64 bit product)
+  const unsigned lat_page_bytes = (unsigned)p.n_blocks * (unsigned)p.page_size * (unsigned)kLatRow;
+  const unsigned rope_page_bytes = (unsigned)p.page_size * (unsigned)(kDr * 2);
   const size_t lat_plane_bytes = (size_t)p.page_size * kLatRow;        // one block's rows inside a page
   const size_t lat_half_step = GLA ? kDcb * 2 : lat_plane_bytes;       // from the first latent tile's source to the second's
   const char* lat_blk = (const char*)p.latent + (size_t)blk0 * lat_plane_bytes;
@@ -359,12 +360,12 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
   const char* iss_lat = nullptr;
   const char* iss_rope = nullptr;
   unsigned iss_stage = 0;
-  auto issue_begin = [&]() {
+  auto issue_begin = [&](unsigned stage_off) {   // stage_off: byte offset of the stage that receives the tile
     const unsigned page = (unsigned)issue_page;
     // start of this wave's 16 latent rows (block plane blk0) and RoPE rows of the tile inside the page
-    iss_lat = lat_blk + page * lat_page_bytes + (unsigned)issue_slot * (unsigned)kLatRow;
-    iss_rope = (const char*)p.rope + page * rope_page_bytes + (unsigned)issue_slot * (unsigned)(kDr * 2);
-    iss_stage = lds_base + issue_stage * kStageB;
+    iss_lat = lat_blk + (unsigned long long)page * lat_page_bytes + (unsigned)issue_slot * (unsigned)kLatRow;
+    iss_rope = (const char*)p.rope + (unsigned long long)page * rope_page_bytes + (unsigned)issue_slot * (unsigned)(kDr * 2);
+    iss_stage = lds_base + stage_off;
   };
   // parts 0..3 = latent loads (PAIRED: 4..7 = the second block's), then two RoPE loads
   auto issue_full_part = [&](int part) {
@@ -392,13 +393,13 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
       } while (issue_slot >= p.page_size);
       issue_page = pt_row[min(issue_page_idx, p.max_pages - 1)];
     }
-    issue_stage = (issue_stage + 1 == STAGES) ? 0 : issue_stage + 1;
   };
   auto issue_tile = [&]() {   // a whole full tile at once (prologue)
-    issue_begin();
+    issue_begin(issue_stage * kStageB);
 #pragma unroll
     for (int part = 0; part < kLoadsTile; ++part) issue_full_part(part);
     issue_end();
+    issue_stage = (issue_stage + 1 == STAGES) ? 0 : issue_stage + 1;
   };
   // The chunk's last tile, into the current stage: rows past the chunk's end re-read its last valid row
   // (finite values; their probabilities are masked to zero).  The rows of this wave that exist lie in its
@@ -411,8 +412,8 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
     const int tok = t0 + (ntiles - 1) * kTile + first;
     const int idx = tok / p.page_size, slot = tok - idx * p.page_size;
     const unsigned page = (unsigned)pt_row[idx];
-    const char* src_lat = lat_blk + page * lat_page_bytes + (unsigned)slot * (unsigned)kLatRow;
-    const char* src_rope = (const char*)p.rope + page * rope_page_bytes + (unsigned)slot * (unsigned)(kDr * 2);
+    const char* src_lat = lat_blk + (unsigned long long)page * lat_page_bytes + (unsigned)slot * (unsigned)kLatRow;
+    const char* src_rope = (const char*)p.rope + (unsigned long long)page * rope_page_bytes + (unsigned)slot * (unsigned)(kDr * 2);
     const unsigned stage = lds_base + issue_stage * kStageB;
 #pragma unroll
     for (int jb = 0; jb < kBlocksWG; ++jb)
@@ -473,19 +474,19 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
 
   typedef const __attribute__((address_space(3))) bf16x8* lds_bf16x8_ptr;
   typedef const __attribute__((address_space(3))) unsigned char* lds_byte_ptr;
-  // K operand ks (this wave's 32 token rows x 16 channels) of the tile in stage st
-  auto load_k_part = [&](int st, int ks, bf16x8 (&ka)[12]) {
-    const unsigned base = lds_base + st * kStageB + (ks < 8 ? k_lat_off : k_rope_off);
+  // K operand ks (this wave's 32 token rows x 16 channels) of the tile in the stage at byte offset st_off
+  auto load_k_part = [&](unsigned st_off, int ks, bf16x8 (&ka)[12]) {
+    const unsigned base = lds_base + st_off + (ks < 8 ? k_lat_off : k_rope_off);
     ka[ks] = *(lds_bf16x8_ptr)(size_t)(base ^ ((ks & 7) << 5));
   };
-  auto load_k = [&](int st, bf16x8 (&ka)[12]) {
+  auto load_k = [&](unsigned st_off, bf16x8 (&ka)[12]) {
 #pragma unroll
-    for (int ks = 0; ks < 12; ++ks) load_k_part(st, ks, ka);
+    for (int ks = 0; ks < 12; ++ks) load_k_part(st_off, ks, ka);
   };
-  // transposed V operand (32 channels of tile mt x 16 of this wave's token rows) of the tile in stage st
-  auto load_v_part = [&](int st, int ss, int mt, bf16x8 (&va)[2][4]) {
-    const unsigned lo_base = lds_base + st * kStageB + v_off[0];
-    const unsigned hi_base = lds_base + st * kStageB + v_off[1];
+  // transposed V operand (32 channels of tile mt x 16 of this wave's token rows) of the tile in that stage
+  auto load_v_part = [&](unsigned st_off, int ss, int mt, bf16x8 (&va)[2][4]) {
+    const unsigned lo_base = lds_base + st_off + v_off[0];
+    const unsigned hi_base = lds_base + st_off + v_off[1];
     const lds_byte_ptr lo_p = (lds_byte_ptr)(size_t)(lo_base ^ (mt << 6));
     const lds_byte_ptr hi_p = (lds_byte_ptr)(size_t)(hi_base ^ (mt << 6));
     const short4v lo = lds_tr16(lo_p + ss * 16 * (kDcb * 2));
@@ -712,7 +713,7 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
     // exists); their probabilities are what has to vanish.
     if (nvalid_last < kTile) { mask_tail(sa0); mask_tail(sa1); }
     __builtin_amdgcn_sched_barrier(0);
-    load_k(1 % STAGES, ka);   // (a stale stage if the chunk has a single tile: those scores are never used)
+    load_k((1 % STAGES) * kStageB, ka);   // (a stale stage if the chunk has a single tile: those scores are never used)
   }
 
   // ---- main loop, software-pipelined over tiles; every MFMA is followed by about six issue slots of
@@ -728,16 +729,20 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
   // order: tile 0 is the chunk's last one.)  Issuing steps load a tile that exists and is full, so they are
   // straight-line code; the last STAGES steps of a chunk issue nothing.  sched_barrier(0) pins the
   // interleaving. ----
-  int st_cur = 0;
+  // (the ring position is kept as a byte offset: no multiplication per step.  A step's loads go into the
+  // stage of the tile it consumes, tile j + STAGES into the stage of tile j.)
+  unsigned st_cur = 0;
   auto step = [&](auto issue_tag, int j, f32x16& c0, f32x16& c1, f32x16& n0, f32x16& n1) {
     constexpr bool ISSUE = decltype(issue_tag)::value;   // tile j + STAGES exists (and is a full one)
     const bool has_next = j + 1 < ntiles;
-    const int st_k2 = (st_cur + 2 >= STAGES) ? st_cur + 2 - STAGES : st_cur + 2;   // stage of tile j+2
+    const unsigned st_k2 = (st_cur + 2 * kStageB >= STAGES * kStageB) ? st_cur + 2 * kStageB - STAGES * kStageB
+                                                                       : st_cur + 2 * kStageB;   // stage of tile j+2
 
     __builtin_amdgcn_sched_barrier(0);
     // ---- block A: 24 score MFMAs; the first of each head tile starts from minus the reference maximum.
     // MFMA i < 16 carries the exponentials of probability pair i (pairs 0..7: head tile 0, 8..15: head
     // tile 1) and the bf16 rounding of pair i-1; MFMA 16+q carries the LDS transpose reads of V operand q.
+    // (Measured: moving the roundings behind the MFMAs of the transpose reads instead costs 25 cycles per tile.)
     float pr[4];
 #pragma unroll
     for (int i = 0; i < 24; ++i) {
@@ -795,7 +800,7 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
         // last steps of a chunk simply wait for everything that is left)
         if (ISSUE) wait_vm_lgkm<kLoadsTile * (STAGES - 3)>(); else wait_vm_lgkm<0>();
         __builtin_amdgcn_s_barrier();
-        if (ISSUE) issue_begin();
+        if (ISSUE) issue_begin(st_cur);
       }
       // (a compute unit takes about 64 bytes of vector-memory requests per cycle, and its four waves issue
       // their loads behind the same MFMAs: one 1 KiB load per wave behind every second MFMA stays below
@@ -838,14 +843,17 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
       __builtin_amdgcn_sched_barrier(0);
     }
     // the maxima are relative to the reference: it moves only when a head's scores outgrow it by 2^kLazy
-    const bool need0 = has_next && mx0 > kLazy;
-    const bool need1 = has_next && mx1 > kLazy;
-    if (__builtin_expect(__any(need0 || need1), 0)) {
+    // (one comparison on the larger of the two maxima decides the common case; an issuing step always has a
+    // next tile)
+    float mx_both;
+    asm("v_max_f32 %0, %1, %2" : "=v"(mx_both) : "v"(mx0), "v"(mx1));
+    if (__builtin_expect((ISSUE || has_next) && __any(mx_both > kLazy), 0)) {
+      const bool need0 = mx0 > kLazy, need1 = mx1 > kLazy;
       settle_acc();
       rescale(std::integral_constant<int, 0>{}, need0 ? mx0 : 0.f, n0);
       rescale(std::integral_constant<int, 1>{}, need1 ? mx1 : 0.f, n1);
     }
-    st_cur = (st_cur + 1 == STAGES) ? 0 : st_cur + 1;
+    st_cur = (st_cur + kStageB == STAGES * kStageB) ? 0 : st_cur + kStageB;
   };
   {
     const std::integral_constant<bool, true> issuing;
@@ -1046,10 +1054,12 @@ static bool want_seq_order(const DecodeArgs& a, long long n_wg) {
 
 // Pages of 16 or 32 tokens (a wave's 16 rows of a tile never straddle a page), or whole tiles.
 static bool page_size_ok(int page_size) { return page_size == 16 || page_size == 32 || page_size % kTile == 0; }
+// (the kernels form page id x bytes-per-page from 32-bit factors)
+static bool page_bytes_ok(const DecodeArgs& a) { return (long long)a.n_blocks * a.page_size * a.d_cb * 2 < (1LL << 32); }
 
 bool decode_mfma_supported(const DecodeArgs& a) {
   // (the query rows are addressed with 32-bit byte offsets from q_abs / q_rope)
-  return a.dtype == MLRA_BF16 && a.d_cb == kDcb && a.d_r == kDr && page_size_ok(a.page_size) &&
+  return a.dtype == MLRA_BF16 && a.d_cb == kDcb && a.d_r == kDr && page_size_ok(a.page_size) && page_bytes_ok(a) &&
          a.plan.chunk_tokens % kTile == 0 &&
          (long long)a.batch * a.n_blocks * a.h * (kDcb * 2) < (1LL << 32) &&
          (long long)a.batch * a.h * a.groups * (kDr * 2) < (1LL << 32);
@@ -1061,7 +1071,7 @@ bool decode_mfma_paired(int h, int n_blocks) { return n_blocks % 2 == 0 && (h - 
 
 // GLA-2 shape: latent heads of 256 channels (Section 2.3); 64 heads per workgroup.
 bool decode_gla_supported(const DecodeArgs& a) {
-  return a.dtype == MLRA_BF16 && a.d_cb == 2 * kDcb && a.d_r == kDr && page_size_ok(a.page_size) &&
+  return a.dtype == MLRA_BF16 && a.d_cb == 2 * kDcb && a.d_r == kDr && page_size_ok(a.page_size) && page_bytes_ok(a) &&
          a.plan.chunk_tokens % kTile == 0 &&
          (long long)a.batch * a.n_blocks * a.h * (4 * kDcb) < (1LL << 32) &&
          (long long)a.batch * a.h * a.groups * (kDr * 2) < (1LL << 32);
