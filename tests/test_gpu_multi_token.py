@@ -67,6 +67,13 @@ def test_multi_token_bf16_fast_path(q_len):
     _check(wl, q_len, np.array([2000, 64, 65, 3, 700], dtype=np.int32), out_dtype=torch.bfloat16)
 
 
+def test_multi_token_dispatch_order_full_run_and_tail():
+    """11 ragged sequences x 3 queries: the dispatch order that brings a sequence's queries together has one
+    full run of 8 sequences and a tail of 3 (two different slot formulas), with ties and an empty sequence."""
+    wl = gen.WORKLOADS["C5"].scaled(name="mt-order", batch=11, n_min=0, n_max=1500)
+    _check(wl, 3, np.array([700, 1500, 0, 64, 700, 2, 1280, 65, 700, 1, 333], dtype=np.int32))
+
+
 def test_multi_token_q_len_one_is_the_plain_decode():
     wl = gen.WORKLOADS["C3"].scaled(name="mt-one", batch=3, n_min=100, n_max=900)
     _check(wl, 1, np.array([900, 100, 513], dtype=np.int32))
