@@ -784,6 +784,7 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
     }
     // ---- block B: 16 MFMAs (m = 0..15: ss = m / 8, mt = (m / 2) % 4, nt = m % 2)
     float mx0 = 0.f, mx1 = 0.f;
+    bool need_any = false;
 #pragma unroll
     for (int m = 0; m < 16; ++m) {
       const int ss = m >> 3, mt = (m >> 1) & 3;
@@ -793,6 +794,13 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
         row_sum_mfma(0, pb0[ss]);
         row_sum_mfma(1, pb1[ss]);
       }
+      // (the address arithmetic of this step's loads does not depend on the barrier: it goes in front of it,
+      // where it overlaps with the wait for the slowest wave.  The bookkeeping for the next step's loads issues
+      // a scalar load of the next page id; while that is in flight every wait for an LDS read has to be a wait
+      // for everything, so it goes at the end of the step, where the next wait is one for everything anyway:
+      // measured 1745 cycles per tile there against 1785 behind the barrier and 1800 in front of it.)
+      if (m == 0 && ISSUE) issue_begin(st_cur);
+      if (m == 14 && ISSUE && kLoadsTile <= 6) issue_end();
       if (m == 1) {
         // this wave's LDS reads of V(j) have returned (so has everything older) before it tells the
         // others that the stage may be overwritten
@@ -800,15 +808,14 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
         // last steps of a chunk simply wait for everything that is left)
         if (ISSUE) wait_vm_lgkm<kLoadsTile * (STAGES - 3)>(); else wait_vm_lgkm<0>();
         __builtin_amdgcn_s_barrier();
-        if (ISSUE) issue_begin(st_cur);
       }
       // (a compute unit takes about 64 bytes of vector-memory requests per cycle, and its four waves issue
       // their loads behind the same MFMAs: one 1 KiB load per wave behind every second MFMA stays below
       // that rate, two behind one MFMA wait on each other for four MFMAs' time.  The forms with ten loads
       // per tile have no slots to spare and put one behind every MFMA.)
+      // (the loads sit behind the odd MFMAs: the even ones carry the column maxima)
       if (kLoadsTile <= 6) {
-        if (ISSUE && m >= 2 && (m & 1) == 0 && (m - 2) / 2 < kLoadsTile) issue_full_part((m - 2) / 2);
-        if (ISSUE && m == 2 * kLoadsTile + 1) issue_end();
+        if (ISSUE && m >= 3 && (m & 1) == 1 && (m - 3) / 2 < kLoadsTile) issue_full_part((m - 3) / 2);
       } else {
         if (ISSUE && m >= 2 && m < 2 + kLoadsTile) issue_full_part(m - 2);
         if (ISSUE && m == 2 + kLoadsTile) issue_end();
@@ -835,19 +842,26 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
       if (m == 10) hold(pb0[0]);
       if (m == 11) hold(pb1[0]);
       if (m >= 2 && m <= 13) load_k_part(st_k2, m - 2, ka);
-      if (m == 6) mx0 = max8(n0[0], n0, 0);
-      if (m == 8) mx0 = max8(mx0, n0, 8);
-      if (m == 10) mx1 = max8(n1[0], n1, 0);
-      if (m == 12) mx1 = max8(mx1, n1, 8);
-      if (m == 14) cross_max(mx0, mx1);
+      // (the score chains ended four MFMAs and a barrier before MFMA 2; in the GLA form the partner's partial
+      // scores are added behind MFMAs 2..5 first)
+      constexpr int kMaxAt = GLA ? 6 : 2;
+      if (m == kMaxAt) mx0 = max8(n0[0], n0, 0);
+      if (m == kMaxAt + 2) mx0 = max8(mx0, n0, 8);
+      if (m == kMaxAt + 4) mx1 = max8(n1[0], n1, 0);
+      if (m == kMaxAt + 6) mx1 = max8(mx1, n1, 8);
+      if (m == kMaxAt + 8) {
+        cross_max(mx0, mx1);
+        // (one comparison on the larger of the two maxima decides the common case, here rather than at the
+        // end of the step so that the branch there finds its condition ready)
+        float mx_both;
+        asm("v_max_f32 %0, %1, %2" : "=v"(mx_both) : "v"(mx0), "v"(mx1));
+        need_any = __any(mx_both > kLazy);
+      }
       __builtin_amdgcn_sched_barrier(0);
     }
     // the maxima are relative to the reference: it moves only when a head's scores outgrow it by 2^kLazy
-    // (one comparison on the larger of the two maxima decides the common case; an issuing step always has a
-    // next tile)
-    float mx_both;
-    asm("v_max_f32 %0, %1, %2" : "=v"(mx_both) : "v"(mx0), "v"(mx1));
-    if (__builtin_expect((ISSUE || has_next) && __any(mx_both > kLazy), 0)) {
+    // (an issuing step always has a next tile)
+    if (__builtin_expect((ISSUE || has_next) && need_any, 0)) {
       const bool need0 = mx0 > kLazy, need1 = mx1 > kLazy;
       settle_acc();
       rescale(std::integral_constant<int, 0>{}, need0 ? mx0 : 0.f, n0);
