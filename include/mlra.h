@@ -118,6 +118,8 @@ MLRA_API size_t mlra_decode_workspace_bytes(int32_t batch, int32_t h, int32_t n_
  *   lse    optional [batch][n_blocks][h] fp32: natural-log sum of exp(score_b); may be NULL
  *   workspace: at least mlra_decode_workspace_bytes(batch, h, n_blocks, d_cb,
  *              max_pages_per_seq*page_size) bytes, 256-byte aligned; contents are overwritten.
+ *   softmax_scale: tau > 0, or MLRA_SCALE_FOLDED when q_abs and q_rope come from mlra_absorb_q_folded
+ *              (they then carry tau log2(e) and the scores are not scaled again).
  * Context is split into chunks processed by independent workgroups whose partial (max, sum, z) are
  * merged with a log-sum-exp merge; results are deterministic (no atomics). */
 MLRA_API int mlra_decode_attn(const mlra_cache* cache, int32_t batch, int32_t h, int32_t d_h, const void* q_abs,
@@ -154,8 +156,8 @@ MLRA_API int mlra_decode_attn_gated(const mlra_cache* cache, int32_t batch, int3
  * (Section 2.1: a position attends to its prefix).  A query whose prefix is empty gives a zero row.
  *   q_abs [batch][q_len][n_blocks][h][d_cb]   (mlra_absorb_q with batch*q_len rows produces this)
  *   q_rope [batch][q_len][h][d_r], out [batch][q_len][h][d_h], lse optional [batch][q_len][n_blocks][h]
- * Everything else as mlra_decode_attn.  The q_len queries of a sequence run as q_len independent decode
- * units over the same pages (their cache reads meet in the memory-side cache); workspace from
+ * Everything else as mlra_decode_attn.  The q_len queries of a sequence run as q_len decode units over the
+ * same pages, dispatched so that they share one XCD's L2 (the sequence's rows leave HBM once); workspace from
  * mlra_decode_multi_workspace_bytes (max_pages_per_seq as in the cache passed later). */
 MLRA_API size_t mlra_decode_multi_workspace_bytes(int32_t batch, int32_t q_len, int32_t h, int32_t n_blocks,
                                          int32_t d_cb, int32_t page_size, int32_t max_pages_per_seq);
