@@ -875,6 +875,12 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(MfmaParams p) {
     // steps 0 .. ntiles - STAGES - 1 issue a tile each, the last STAGES steps only drain the pipeline
     const int n_issue = ntiles > STAGES ? ntiles - STAGES : 0;
     int j = 0;
+    for (; j + 4 <= n_issue; j += 4) {   // (four steps per trip: the taken branch at the end costs a refetch)
+      step(issuing, j, sa0, sa1, sb0, sb1);
+      step(issuing, j + 1, sb0, sb1, sa0, sa1);
+      step(issuing, j + 2, sa0, sa1, sb0, sb1);
+      step(issuing, j + 3, sb0, sb1, sa0, sa1);
+    }
     for (; j + 2 <= n_issue; j += 2) {
       step(issuing, j, sa0, sa1, sb0, sb1);
       step(issuing, j + 1, sb0, sb1, sa0, sa1);
